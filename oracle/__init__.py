@@ -1,0 +1,204 @@
+"""CPU oracle for Diagonal-Tiled Mixed-Precision Attention -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes access to ``dma_oracle.c`` (plain C, double arithmetic).  Only the tests, the smoke
+check and the benchmark's CPU-baseline leg may import this package; the GPU library and its
+Python binding never do, and nothing here imports them.
+
+bf16 tensors are passed as ``numpy.uint16`` arrays holding the raw bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+FMT_BF16 = 0
+FMT_E4M3 = 1
+FMT_E2M1 = 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dma_oracle.c")
+_LIB = os.path.join(_HERE, "libdma_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile dma_oracle.c with gcc (-O2, no fast-math, OpenMP) into libdma_oracle.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-shared",
+               "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        u16p, u8p, i64p = (ctypes.POINTER(ctypes.c_uint16), ctypes.POINTER(ctypes.c_uint8),
+                           ctypes.POINTER(ctypes.c_int64))
+        f32p, f64p = ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)
+        L.oracle_bf16_to_f32.restype = ctypes.c_float
+        L.oracle_bf16_to_f32.argtypes = [ctypes.c_uint16]
+        L.oracle_round_to_bf16.restype = ctypes.c_double
+        L.oracle_round_to_bf16.argtypes = [ctypes.c_double]
+        L.oracle_e2m1_decode.restype = ctypes.c_double
+        L.oracle_e2m1_decode.argtypes = [ctypes.c_uint8]
+        L.oracle_e2m1_encode.restype = ctypes.c_uint8
+        L.oracle_e2m1_encode.argtypes = [ctypes.c_double, ctypes.c_int]
+        L.oracle_e4m3_decode.restype = ctypes.c_double
+        L.oracle_e4m3_decode.argtypes = [ctypes.c_uint8]
+        L.oracle_e4m3_encode.restype = ctypes.c_uint8
+        L.oracle_e4m3_encode.argtypes = [ctypes.c_double, ctypes.c_int]
+        L.oracle_e8m0_from_amax.restype = ctypes.c_uint8
+        L.oracle_e8m0_from_amax.argtypes = [ctypes.c_float, ctypes.c_int]
+        L.oracle_query_prescale.restype = ctypes.c_float
+        L.oracle_query_prescale.argtypes = [ctypes.c_int]
+        L.oracle_mx_quantize.restype = ctypes.c_int
+        L.oracle_mx_quantize.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, u8p, u8p]
+        L.oracle_mx_dequantize.restype = ctypes.c_int
+        L.oracle_mx_dequantize.argtypes = [u8p, u8p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, f64p]
+        L.oracle_dma_attn_rows.restype = ctypes.c_int
+        L.oracle_dma_attn_rows.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_int, ctypes.c_int, ctypes.c_int, i64p, ctypes.c_int64, f32p]
+        L.oracle_ref_attn_rows.restype = ctypes.c_int
+        L.oracle_ref_attn_rows.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_int64, ctypes.c_int, i64p, ctypes.c_int64, f64p]
+        L.oracle_num_threads.restype = ctypes.c_int
+        L.oracle_num_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def _as_bits(x) -> np.ndarray:
+    a = np.ascontiguousarray(x)
+    if a.dtype != np.uint16:
+        raise TypeError("bf16 data must be passed as uint16 bit patterns")
+    return a
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise RuntimeError(f"{what} failed with code {rc}")
+
+
+# ---- scalar helpers (used by the pins) ---------------------------------------------------------
+
+def bf16_to_f32(bits: int) -> float:
+    return float(lib().oracle_bf16_to_f32(int(bits)))
+
+
+def round_to_bf16(p: float) -> float:
+    return float(lib().oracle_round_to_bf16(float(p)))
+
+
+def e2m1_encode(y: float) -> int:
+    neg = 1 if np.signbit(y) else 0
+    return int(lib().oracle_e2m1_encode(float(y), neg))
+
+
+def e2m1_decode(code: int) -> float:
+    return float(lib().oracle_e2m1_decode(int(code)))
+
+
+def e4m3_encode(y: float) -> int:
+    neg = 1 if np.signbit(y) else 0
+    return int(lib().oracle_e4m3_encode(float(y), neg))
+
+
+def e4m3_decode(code: int) -> float:
+    return float(lib().oracle_e4m3_decode(int(code)))
+
+
+def e8m0_from_amax(amax: float, fmt: int) -> int:
+    return int(lib().oracle_e8m0_from_amax(float(np.float32(amax)), int(fmt)))
+
+
+def query_prescale(D: int) -> float:
+    return float(lib().oracle_query_prescale(int(D)))
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+# ---- tensor functions --------------------------------------------------------------------------
+
+def mx_quantize(x_bits, fmt: int, is_query: bool):
+    """x_bits: [..., D] uint16 (bf16 bits).  Returns (codes uint8 [..., D or D/2], scales uint8 [..., D/32])."""
+    x = _as_bits(x_bits)
+    D = x.shape[-1]
+    rows = x.size // D
+    cb = D // 2 if fmt == FMT_E2M1 else D
+    codes = np.zeros(x.shape[:-1] + (cb,), dtype=np.uint8)
+    scales = np.zeros(x.shape[:-1] + (D // 32,), dtype=np.uint8)
+    _check(lib().oracle_mx_quantize(_p(x, ctypes.c_uint16), rows, D, fmt, int(bool(is_query)),
+                                    _p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint8)), "oracle_mx_quantize")
+    return codes, scales
+
+
+def mx_dequantize(codes, scales, fmt: int) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.uint8)
+    D = scales.shape[-1] * 32
+    rows = scales.size // scales.shape[-1]
+    out = np.empty(scales.shape[:-1] + (D,), dtype=np.float64)
+    _check(lib().oracle_mx_dequantize(_p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint8), rows, D, fmt,
+                                      _p(out, ctypes.c_double)), "oracle_mx_dequantize")
+    return out
+
+
+def sort_rows(rows) -> np.ndarray:
+    """Order (b, hq, i) triples so that rows of one (b, hq) are adjacent (the C loops then reuse the
+    decoded keys of a kv head when consecutive q heads share it)."""
+    r = np.asarray(rows, dtype=np.int64).reshape(-1, 3)
+    order = np.lexsort((r[:, 2], r[:, 1], r[:, 0]))
+    return np.ascontiguousarray(r[order])
+
+
+def dma_attn_rows(q_bits, k_bits, v_bits, rows, *, tile: int, band: int, hi_fmt: int = FMT_E4M3,
+                  lo_fmt: int = FMT_E2M1, p_round: bool = True) -> np.ndarray:
+    """Diagonal-tiled attention output for the given (b, hq, i) rows -> float32 [n_rows, D]."""
+    q, k, v = _as_bits(q_bits), _as_bits(k_bits), _as_bits(v_bits)
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == (B, Hkv, S, D) and v.shape == k.shape
+    r = np.ascontiguousarray(np.asarray(rows, dtype=np.int64).reshape(-1, 3))
+    out = np.empty((r.shape[0], D), dtype=np.float32)
+    _check(lib().oracle_dma_attn_rows(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
+                                      B, Hq, Hkv, S, D, tile, band, hi_fmt, lo_fmt, int(bool(p_round)),
+                                      _p(r, ctypes.c_int64), r.shape[0], _p(out, ctypes.c_float)),
+           "oracle_dma_attn_rows")
+    return out
+
+
+def all_rows(B: int, Hq: int, S: int) -> np.ndarray:
+    b, h, i = np.meshgrid(np.arange(B), np.arange(Hq), np.arange(S), indexing="ij")
+    return np.stack([b.ravel(), h.ravel(), i.ravel()], axis=1).astype(np.int64)
+
+
+def dma_attn(q_bits, k_bits, v_bits, **kw) -> np.ndarray:
+    """Full output [B, Hq, S, D] float32 (small problems only)."""
+    B, Hq, S, D = q_bits.shape
+    return dma_attn_rows(q_bits, k_bits, v_bits, all_rows(B, Hq, S), **kw).reshape(B, Hq, S, D)
+
+
+def ref_attn_rows(q_bits, k_bits, v_bits, rows) -> np.ndarray:
+    """Exact causal softmax attention of the unquantized inputs, float64 [n_rows, D]."""
+    q, k, v = _as_bits(q_bits), _as_bits(k_bits), _as_bits(v_bits)
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    r = np.ascontiguousarray(np.asarray(rows, dtype=np.int64).reshape(-1, 3))
+    out = np.empty((r.shape[0], D), dtype=np.float64)
+    _check(lib().oracle_ref_attn_rows(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
+                                      B, Hq, Hkv, S, D, _p(r, ctypes.c_int64), r.shape[0],
+                                      _p(out, ctypes.c_double)), "oracle_ref_attn_rows")
+    return out

@@ -1,0 +1,447 @@
+/*
+ * dma_oracle.c -- CPU oracle for Diagonal-Tiled Mixed-Precision Attention (DMA).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, step-by-step statement of what the
+ * method computes.  It is used by the tests, by the smoke check and by the benchmark's CPU
+ * baseline leg, and by nothing else; the GPU library never links, loads or calls it, and it
+ * shares no code, table or header with the GPU path.
+ *
+ * Everything after quantization is done in double.  Each function cites the passage of the
+ * paper it follows (section / algorithm / equation / table).
+ *
+ * Formats: 0 = unquantized bf16, 1 = MXFP8 with E4M3 elements, 2 = MXFP4 with E2M1 elements;
+ * MX block = 32 consecutive elements along the head dimension with one E8M0 scale byte
+ * (Table "Comparison of representative MXFP data formats"; Sec. 3.1).
+ *
+ * Readings taken where the paper is silent or inconsistent are listed at each place they are
+ * used, prefixed "Reading:".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_FMT_BF16 0
+#define ORACLE_FMT_E4M3 1
+#define ORACLE_FMT_E2M1 2
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG (-1)
+#define ORACLE_ERR_MEM (-2)
+
+/* ------------------------------------------------------------------------------------------ */
+/* bf16 <-> binary32 / double                                                                 */
+/* ------------------------------------------------------------------------------------------ */
+
+/* bf16 is the upper half of a binary32 word, so widening is exact. */
+float oracle_bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* Round a double to the nearest bf16 (8 significand bits incl. the hidden one), ties to even,
+ * in ONE rounding step (no detour through binary32).  Returns the value as a double.
+ * Used for the probabilities that enter the P*V product (Reading: P is rounded to the 16-bit
+ * type of V before the second product, the flash-attention idiom; Alg. 1 keeps V in 16 bit). */
+double oracle_round_to_bf16(double p)
+{
+    if (p == 0.0 || isnan(p) || isinf(p)) return p;
+    int ex;
+    (void)frexp(p, &ex);              /* |p| = f * 2^ex, f in [0.5, 1)  ->  floor(log2|p|) = ex-1 */
+    int quantum = (ex - 1) - 7;       /* spacing of bf16 numbers in [2^(ex-1), 2^ex) is 2^(ex-1-7) */
+    if (quantum < -133) quantum = -133; /* bf16 subnormals: fixed spacing 2^-133 */
+    double scaled = ldexp(p, -quantum);
+    double r = nearbyint(scaled);     /* default rounding mode = to nearest, ties to even */
+    return ldexp(r, quantum);
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Element encoders / decoders                                                                */
+/* ------------------------------------------------------------------------------------------ */
+
+/* E2M1 decode: bit layout (S<<3)|(E<<1)|M with exponent bias 1 (Alg. 3, Step 4.4).
+ * E = 0 is subnormal: value M * 0.5.  Otherwise (1 + M/2) * 2^(E-1).
+ * Magnitudes by code 0..7: 0, 0.5, 1, 1.5, 2, 3, 4, 6. */
+double oracle_e2m1_decode(uint8_t code)
+{
+    int s = (code >> 3) & 1, e = (code >> 1) & 3, m = code & 1;
+    double a = (e == 0) ? 0.5 * m : ldexp(1.0 + 0.5 * m, e - 1);
+    return s ? -a : a;
+}
+
+/* E2M1 encode of a value already scaled and clamped to [-6, 6] (Alg. 2 Step 4; Alg. 3).
+ * Reading: the printed mantissa rule is not a complete rounding (no carry into the exponent,
+ * and its subnormal threshold is inconsistent with the text); the text states the intent:
+ * round to nearest with ties to the even mantissa (its example: 5 -> 4), thresholds strict.
+ * This is that rounding, written out.  The sign bit is the sign bit of the input, also for
+ * results that round to zero (Alg. 3 Step 4.1 takes the sign first). */
+uint8_t oracle_e2m1_encode(double y, int negative)
+{
+    double a = fabs(y);
+    int mag;
+    if (a < 1.0) {
+        /* subnormal range and the step up to 1.0: grid 0, 0.5, 1.0  = codes 0, 1, 2 */
+        mag = (int)nearbyint(2.0 * a);
+    } else {
+        int ex;
+        (void)frexp(a, &ex);
+        int e = ex - 1;                                   /* floor(log2 a): 0, 1 or 2 */
+        int m = (int)nearbyint(2.0 * (ldexp(a, -e) - 1.0)); /* 0, 1, or 2 (= carry) */
+        if (m == 2) { e += 1; m = 0; }
+        mag = ((e + 1) << 1) | m;
+    }
+    if (mag > 7) mag = 7;
+    return (uint8_t)((negative ? 8 : 0) | mag);
+}
+
+/* E4M3 decode (OCP variant: bias 7, exponent field 15 is an ordinary binade, no infinities;
+ * Sec. 4.2 "Compute shared scale": e_max = 8).  E = 0: M * 2^-9.  Else (1 + M/8) * 2^(E-7). */
+double oracle_e4m3_decode(uint8_t code)
+{
+    int s = (code >> 7) & 1, e = (code >> 3) & 15, m = code & 7;
+    double a = (e == 0) ? ldexp((double)m, -9) : ldexp(1.0 + m / 8.0, e - 7);
+    return s ? -a : a;
+}
+
+/* E4M3 encode of a value already scaled and clamped to [-448, 448] (Alg. 2 Step 6).
+ * Reading: the algorithm shows only the clamp; the element conversion is round to nearest,
+ * ties to even, with subnormals, as for the 4-bit format.  0x7F / 0xFF are never produced. */
+uint8_t oracle_e4m3_encode(double y, int negative)
+{
+    double a = fabs(y);
+    int mag;
+    if (a < ldexp(1.0, -6)) {
+        mag = (int)nearbyint(ldexp(a, 9));                /* 0..8; 8 is the first normal */
+    } else {
+        int ex;
+        (void)frexp(a, &ex);
+        int e = ex - 1;                                   /* -6 .. 8 */
+        int m = (int)nearbyint(8.0 * (ldexp(a, -e) - 1.0)); /* 0..8 (8 = carry) */
+        if (m == 8) { e += 1; m = 0; }
+        mag = ((e + 7) << 3) | m;
+    }
+    if (mag > 0x7E) mag = 0x7E;
+    return (uint8_t)((negative ? 0x80 : 0) | mag);
+}
+
+/* Exponent of the largest normal number of the element format (Sec. 4.2: 8 for E4M3; for E2M1
+ * the largest normal is 6 = 1.5 * 2^2, so 2).  Reading: the MXFP4 copy uses the same E8M0 rule
+ * as the MXFP8 copy (text of "Compute shared scale"), not the max/6 rule of Alg. 2 Step 3,
+ * which is the NVFP4 flavour. */
+static int fmt_emax(int fmt) { return fmt == ORACLE_FMT_E2M1 ? 2 : 8; }
+static double fmt_maxval(int fmt) { return fmt == ORACLE_FMT_E2M1 ? 6.0 : 448.0; }
+
+/* E8M0 scale byte of a block whose absolute maximum (a binary32 value) is amax
+ * (Alg. 2 Step 6: S_shared = floor(log2 amax) - e_max;  Step 7: clamp(S_shared + 127, 0, 254)).
+ * amax = 0 gives log2 = -inf, which the clamp maps to 0. */
+uint8_t oracle_e8m0_from_amax(float amax, int fmt)
+{
+    if (!(amax > 0.0f)) return 0;
+    int ex;
+    (void)frexp((double)amax, &ex);
+    long shared = (long)(ex - 1) - fmt_emax(fmt);   /* floor(log2 amax) - e_max */
+    long biased = shared + 127;
+    if (biased < 0) biased = 0;
+    if (biased > 254) biased = 254;
+    return (uint8_t)biased;
+}
+
+/* The query pre-scale log2(e)/sqrt(D) (Alg. 2 Step 1), as the binary32 constant.
+ * Reading: the product x * c is ONE binary32 multiplication, kept in binary32. */
+float oracle_query_prescale(int D)
+{
+    return (float)(1.4426950408889634074 / sqrt((double)D));
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* MX quantization of a [rows, D] bf16 matrix (Alg. 2, Steps 1 and 3-7)                       */
+/* ------------------------------------------------------------------------------------------ */
+
+/* Quantize one row.  codes: D bytes (E4M3) or D/2 bytes (E2M1, element 2t in the low nibble and
+ * 2t+1 in the high nibble: Alg. 2 Step 5 and "Packing").  scales: D/32 bytes.
+ * Reading: the per-token scale S_q of Alg. 2 Step 2 is 1 on this path (it exists to fit the
+ * E4M3-typed scale of NVFP4; an E8M0 scale already spans the binary32 range, Sec. 3.1). */
+static void quantize_row(const uint16_t *x, int D, int fmt, int is_query, uint8_t *codes, uint8_t *scales)
+{
+    const float c = oracle_query_prescale(D);
+    float xs[32];
+    for (int blk = 0; blk < D / 32; ++blk) {
+        float amax = 0.0f;
+        for (int t = 0; t < 32; ++t) {
+            float v = oracle_bf16_to_f32(x[blk * 32 + t]);
+            if (is_query) {
+                volatile float prod = v * c;     /* one binary32 multiply, rounded once */
+                v = prod;
+            }
+            xs[t] = v;
+            float av = fabsf(v);
+            if (av > amax) amax = av;
+        }
+        uint8_t sc = oracle_e8m0_from_amax(amax, fmt);
+        scales[blk] = sc;
+        const double u = fmt_maxval(fmt);
+        for (int t = 0; t < 32; ++t) {
+            int neg = signbit(xs[t]) ? 1 : 0;
+            double y = ldexp((double)xs[t], 127 - (int)sc);     /* x / 2^S_shared, exact */
+            if (y > u) y = u;                                   /* clamp(., l, u) */
+            if (y < -u) y = -u;
+            int d = blk * 32 + t;
+            if (fmt == ORACLE_FMT_E2M1) {
+                uint8_t cd = oracle_e2m1_encode(y, neg);
+                if (d & 1) codes[d >> 1] = (uint8_t)(codes[d >> 1] | (cd << 4));
+                else       codes[d >> 1] = cd;
+            } else {
+                codes[d] = oracle_e4m3_encode(y, neg);
+            }
+        }
+    }
+}
+
+int oracle_mx_quantize(const uint16_t *x, int64_t rows, int D, int fmt, int is_query,
+                       uint8_t *codes, uint8_t *scales)
+{
+    if (!x || !codes || !scales || rows < 0 || D <= 0 || D % 32 != 0) return ORACLE_ERR_ARG;
+    if (fmt != ORACLE_FMT_E4M3 && fmt != ORACLE_FMT_E2M1) return ORACLE_ERR_ARG;
+    const int64_t cb = (fmt == ORACLE_FMT_E2M1) ? D / 2 : D;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        quantize_row(x + r * D, D, fmt, is_query, codes + r * cb, scales + r * (D / 32));
+    return ORACLE_OK;
+}
+
+/* Decode codes + scales back to real values: element * 2^(scale - 127), exact in double. */
+int oracle_mx_dequantize(const uint8_t *codes, const uint8_t *scales, int64_t rows, int D, int fmt,
+                         double *out)
+{
+    if (!codes || !scales || !out || rows < 0 || D <= 0 || D % 32 != 0) return ORACLE_ERR_ARG;
+    if (fmt != ORACLE_FMT_E4M3 && fmt != ORACLE_FMT_E2M1) return ORACLE_ERR_ARG;
+    const int64_t cb = (fmt == ORACLE_FMT_E2M1) ? D / 2 : D;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int d = 0; d < D; ++d) {
+            int sc = scales[r * (D / 32) + d / 32];
+            double e;
+            if (fmt == ORACLE_FMT_E2M1) {
+                uint8_t b = codes[r * cb + (d >> 1)];
+                e = oracle_e2m1_decode((d & 1) ? (uint8_t)(b >> 4) : (uint8_t)(b & 15));
+            } else {
+                e = oracle_e4m3_decode(codes[r * cb + d]);
+            }
+            out[r * D + d] = ldexp(e, sc - 127);
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* What a row looks like to the score product in format fmt, as doubles:
+ * quantized formats: quantize then decode; bf16: the values themselves (the softmax factor is
+ * then applied to the score, see score_scale()). */
+static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, double *out)
+{
+    if (fmt == ORACLE_FMT_BF16) {
+        for (int d = 0; d < D; ++d) out[d] = (double)oracle_bf16_to_f32(x[d]);
+        return;
+    }
+    uint8_t codes[1024];
+    uint8_t scales[64];
+    memset(codes, 0, sizeof codes);
+    quantize_row(x, D, fmt, is_query, codes, scales);
+    oracle_mx_dequantize(codes, scales, 1, D, fmt, out);
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Diagonal-tiled attention for a list of query rows (Alg. 1 + Sec. 3.2)                       */
+/* ------------------------------------------------------------------------------------------ */
+
+/* Output of one query row.  kseen_lo / kseen_hi: keys of this kv head as seen by the low / high
+ * format, [S, D] doubles.  v: [S, D] bf16 of this kv head.
+ *
+ * Steps, in the paper's order, for the query tile it = i / tile:
+ *   running state m = -inf, l = 1, O = 0                                   (Alg. 1 line 1)
+ *   key tiles jt = 0 .. it ascending; Phase 1 = tiles before the window in the low format,
+ *   Phase 2 = the last `band` tiles up to and including the diagonal one in the high format.
+ *   Reading: the loop bounds are half open and n_Q*B_M means the END of the query tile, so a
+ *   window of T = band * B_N tokens is exactly the last `band` key tiles ("only the last T
+ *   tokens", Sec. 4.1).
+ *   score s_j = q~ . k_j in that tile's format (Alg. 1 lines 3 and 7; base-2 scaling folded
+ *   into q~, Alg. 2 Step 1); keys after the query are set to -inf (lines 8-9).
+ *   Reading: -inf is selected where the mask holds (the printed S - inf*Delta would give NaN
+ *   elsewhere), and the mask applies to the diagonal tile whatever its format.
+ *   OnlineSoftmax (Sec. 3.2): m' = max(m, max_j s_j); alpha = 2^(m-m'); p_j = 2^(s_j - m');
+ *   l = alpha*l + sum_j p_j;  O = alpha*O + sum_j p^_j * v_j;  finally O / l (line 12).
+ *   Reading: p^_j = p_j rounded to bf16 when p_round != 0 (l sums the unrounded p_j).
+ */
+static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const double *kseen_hi,
+                         const uint16_t *v, int64_t i, int D, int tile, int band, int hi_fmt,
+                         int lo_fmt, int p_round, float *out)
+{
+    double q_lo[512], q_hi[512], O[512];
+    double *s = (double *)malloc(sizeof(double) * (size_t)tile);
+    row_as_seen(qrow, D, lo_fmt, 1, q_lo);
+    row_as_seen(qrow, D, hi_fmt, 1, q_hi);
+    const double c = 1.4426950408889634074 / sqrt((double)D);
+    const double sc_lo = (lo_fmt == ORACLE_FMT_BF16) ? c : 1.0;   /* bf16 rows are not pre-scaled */
+    const double sc_hi = (hi_fmt == ORACLE_FMT_BF16) ? c : 1.0;
+
+    double m = -INFINITY, l = 1.0;
+    for (int d = 0; d < D; ++d) O[d] = 0.0;
+
+    const int64_t it = i / tile;
+    for (int64_t jt = 0; jt <= it; ++jt) {
+        const int use_hi = (it - jt) < (int64_t)band;
+        const double *qq = use_hi ? q_hi : q_lo;
+        const double *kk = use_hi ? kseen_hi : kseen_lo;
+        const double sc = use_hi ? sc_hi : sc_lo;
+        double tmax = -INFINITY;
+        for (int t = 0; t < tile; ++t) {
+            int64_t j = jt * tile + t;
+            double acc;
+            if (j > i) {
+                acc = -INFINITY;
+            } else {
+                acc = 0.0;
+                const double *kr = kk + j * D;
+                for (int d = 0; d < D; ++d) acc += qq[d] * kr[d];
+                acc *= sc;
+            }
+            s[t] = acc;
+            if (acc > tmax) tmax = acc;
+        }
+        const double mnew = (tmax > m) ? tmax : m;
+        const double alpha = exp2(m - mnew);
+        double psum = 0.0;
+        for (int d = 0; d < D; ++d) O[d] *= alpha;
+        for (int t = 0; t < tile; ++t) {
+            int64_t j = jt * tile + t;
+            if (j > i) continue;                       /* p = 2^(-inf) = 0 */
+            double p = exp2(s[t] - mnew);
+            psum += p;
+            double ph = p_round ? oracle_round_to_bf16(p) : p;
+            const uint16_t *vr = v + j * D;
+            for (int d = 0; d < D; ++d) O[d] += ph * (double)oracle_bf16_to_f32(vr[d]);
+        }
+        l = alpha * l + psum;
+        m = mnew;
+    }
+    for (int d = 0; d < D; ++d) out[d] = (float)(O[d] / l);
+    free(s);
+}
+
+/* Keys of one kv head as seen in a format, rows 0 .. n-1, [n, D] doubles. */
+static double *keys_as_seen(const uint16_t *k, int64_t n, int D, int fmt)
+{
+    double *out = (double *)malloc(sizeof(double) * (size_t)n * (size_t)D);
+    if (!out) return NULL;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < n; ++r) row_as_seen(k + r * D, D, fmt, 0, out + r * D);
+    return out;
+}
+
+/*
+ * q: [B, Hq, S, D] bf16; k, v: [B, Hkv, S, D] bf16 (contiguous, D innermost; q head h uses kv
+ * head h / (Hq/Hkv)).  rows: n_rows triples (b, hq, i).  out: [n_rows, D] float, in the order
+ * of `rows`.  tile = B_M = B_N; band = T / B_N (0: every tile low; >= S/tile: every tile high).
+ * Rows should be grouped by (b, kv head) for speed; any order is correct.
+ */
+int oracle_dma_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq,
+                         int Hkv, int64_t S, int D, int tile, int band, int hi_fmt, int lo_fmt,
+                         int p_round, const int64_t *rows, int64_t n_rows, float *out)
+{
+    if (!q || !k || !v || !out || (!rows && n_rows > 0)) return ORACLE_ERR_ARG;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || S <= 0 || D <= 0 || D % 32 != 0 || D > 512)
+        return ORACLE_ERR_ARG;
+    if (tile <= 0 || band < 0) return ORACLE_ERR_ARG;
+    for (int f = 0; f < 2; ++f) {
+        int fm = f ? hi_fmt : lo_fmt;
+        if (fm != ORACLE_FMT_BF16 && fm != ORACLE_FMT_E4M3 && fm != ORACLE_FMT_E2M1) return ORACLE_ERR_ARG;
+    }
+    for (int64_t r = 0; r < n_rows; ++r) {
+        if (rows[3 * r] < 0 || rows[3 * r] >= B || rows[3 * r + 1] < 0 || rows[3 * r + 1] >= Hq ||
+            rows[3 * r + 2] < 0 || rows[3 * r + 2] >= S)
+            return ORACLE_ERR_ARG;
+    }
+    const int group = Hq / Hkv;
+    int64_t r0 = 0;
+    while (r0 < n_rows) {
+        /* maximal run of rows sharing (b, kv head) */
+        const int64_t b = rows[3 * r0], hkv = rows[3 * r0 + 1] / group;
+        int64_t r1 = r0, imax = 0;
+        while (r1 < n_rows && rows[3 * r1] == b && rows[3 * r1 + 1] / group == hkv) {
+            if (rows[3 * r1 + 2] > imax) imax = rows[3 * r1 + 2];
+            ++r1;
+        }
+        const uint16_t *kh = k + ((int64_t)b * Hkv + hkv) * S * D;
+        const uint16_t *vh = v + ((int64_t)b * Hkv + hkv) * S * D;
+        double *klo = keys_as_seen(kh, imax + 1, D, lo_fmt);
+        double *khi = (hi_fmt == lo_fmt) ? klo : keys_as_seen(kh, imax + 1, D, hi_fmt);
+        if (!klo || !khi) { free(klo); if (khi != klo) free(khi); return ORACLE_ERR_MEM; }
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int64_t r = r0; r < r1; ++r) {
+            const int64_t hq = rows[3 * r + 1], i = rows[3 * r + 2];
+            const uint16_t *qrow = q + (((int64_t)b * Hq + hq) * S + i) * D;
+            attn_one_row(qrow, klo, khi, vh, i, D, tile, band, hi_fmt, lo_fmt, p_round, out + r * D);
+        }
+        if (khi != klo) free(khi);
+        free(klo);
+        r0 = r1;
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Exact causal softmax attention of the unquantized inputs (Sec. 3.2, eq. 1), for reporting   */
+/* the method's own error.  Natural-base softmax of q.k/sqrt(D), two passes, double.           */
+/* ------------------------------------------------------------------------------------------ */
+int oracle_ref_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq,
+                         int Hkv, int64_t S, int D, const int64_t *rows, int64_t n_rows, double *out)
+{
+    if (!q || !k || !v || !out || (!rows && n_rows > 0)) return ORACLE_ERR_ARG;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || S <= 0 || D <= 0) return ORACLE_ERR_ARG;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        if (rows[3 * r] < 0 || rows[3 * r] >= B || rows[3 * r + 1] < 0 || rows[3 * r + 1] >= Hq ||
+            rows[3 * r + 2] < 0 || rows[3 * r + 2] >= S)
+            return ORACLE_ERR_ARG;
+    }
+    const int group = Hq / Hkv;
+    const double inv = 1.0 / sqrt((double)D);
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const int64_t b = rows[3 * r], hq = rows[3 * r + 1], i = rows[3 * r + 2];
+        const uint16_t *qrow = q + ((b * Hq + hq) * S + i) * D;
+        const uint16_t *kh = k + (b * Hkv + hq / group) * S * D;
+        const uint16_t *vh = v + (b * Hkv + hq / group) * S * D;
+        double *s = (double *)malloc(sizeof(double) * (size_t)(i + 1));
+        if (!s) { err = 1; continue; }
+        double mx = -INFINITY;
+        for (int64_t j = 0; j <= i; ++j) {
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d)
+                acc += (double)oracle_bf16_to_f32(qrow[d]) * (double)oracle_bf16_to_f32(kh[j * D + d]);
+            s[j] = acc * inv;
+            if (s[j] > mx) mx = s[j];
+        }
+        double den = 0.0;
+        double *o = out + r * D;
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        for (int64_t j = 0; j <= i; ++j) {
+            double p = exp(s[j] - mx);
+            den += p;
+            for (int d = 0; d < D; ++d) o[d] += p * (double)oracle_bf16_to_f32(vh[j * D + d]);
+        }
+        for (int d = 0; d < D; ++d) o[d] /= den;
+        free(s);
+    }
+    return err ? ORACLE_ERR_MEM : ORACLE_OK;
+}
+
+/* Number of OpenMP threads the loops above use (for reporting the CPU baseline). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif

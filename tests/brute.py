@@ -1,0 +1,155 @@
+"""Brute-force, per-element definitions used to pin the CPU oracle (tiny inputs only).
+
+Written from the definitions (nearest grid value, largest power of two not above a number, plain
+row softmax), not from the oracle's formulas, and sharing no code with it.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# Representable magnitudes by code.  E2M1: Alg. 3 (bias 1, codes (E<<1)|M).  E4M3: OCP layout,
+# bias 7, exponent field 15 is an ordinary binade (Sec. 4.2), 0x7F is not a number.
+E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+E4M3_GRID = np.array([(m * 2.0 ** -9) if e == 0 else (1 + m / 8.0) * 2.0 ** (e - 7)
+                      for e in range(16) for m in range(8)][:0x7F])
+
+
+def nearest_code(grid: np.ndarray, a: float) -> int:
+    """Index of the grid value nearest to a >= 0; exact ties go to the even index; values beyond
+    the largest grid value saturate."""
+    a = float(a)
+    if a >= grid[-1]:
+        return len(grid) - 1
+    d = np.abs(grid - a)               # exact: grid values and a are doubles with few bits
+    best = np.flatnonzero(d == d.min())
+    if len(best) == 1:
+        return int(best[0])
+    even = [int(b) for b in best if b % 2 == 0]
+    return even[0]
+
+
+def floor_log2(a: float) -> int:
+    """Largest integer e with 2**e <= a, by search (a > 0)."""
+    e = 0
+    while 2.0 ** (e + 1) <= a:
+        e += 1
+    while 2.0 ** e > a:
+        e -= 1
+    return e
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def quantize_block(x32: np.ndarray, fmt: str):
+    """One MX block (32 float32 values, already pre-scaled if a query).
+    Returns (scale_byte, codes[32] with sign bit, decoded float64[32])."""
+    grid, emax, signbit = (E2M1_GRID, 2, 8) if fmt == "e2m1" else (E4M3_GRID, 8, 0x80)
+    amax = float(np.max(np.abs(x32)))
+    if amax == 0.0:
+        sb = 0
+    else:
+        sb = min(max(floor_log2(amax) - emax + 127, 0), 254)
+    codes = np.zeros(32, dtype=np.uint8)
+    dec = np.zeros(32)
+    for t in range(32):
+        y = float(x32[t]) * 2.0 ** (127 - sb)     # exact in double
+        c = nearest_code(grid, abs(y))
+        neg = bool(np.signbit(x32[t]))
+        codes[t] = c | (signbit if neg else 0)
+        dec[t] = (-grid[c] if neg else grid[c]) * 2.0 ** (sb - 127)
+    return sb, codes, dec
+
+
+def quantize_rows(bits: np.ndarray, fmt: str, is_query: bool):
+    """bits: [rows, D] uint16.  Returns (scales[rows, D/32], codes[rows, D] unpacked, decoded[rows, D])."""
+    rows, D = bits.shape
+    x = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    if is_query:
+        c = np.float32(np.log2(np.e) / np.sqrt(np.float64(D)))
+        x = (x * c).astype(np.float32)            # one float32 multiply per element
+    scales = np.zeros((rows, D // 32), dtype=np.uint8)
+    codes = np.zeros((rows, D), dtype=np.uint8)
+    dec = np.zeros((rows, D))
+    for r in range(rows):
+        for b in range(D // 32):
+            sb, cd, de = quantize_block(x[r, 32 * b:32 * b + 32], fmt)
+            scales[r, b] = sb
+            codes[r, 32 * b:32 * b + 32] = cd
+            dec[r, 32 * b:32 * b + 32] = de
+    return scales, codes, dec
+
+
+def pack_fp4(codes: np.ndarray) -> np.ndarray:
+    """Two 4-bit codes per byte, the higher index in the high nibble (Alg. 2 Step 5)."""
+    return (codes[..., 1::2].astype(np.uint8) << 4) | codes[..., 0::2].astype(np.uint8)
+
+
+def round_bf16_nearest_of_two(p: np.ndarray) -> np.ndarray:
+    """Round positive doubles to bf16 by comparing the two neighbouring bf16 numbers."""
+    p = np.asarray(p, dtype=np.float64)
+    out = np.zeros_like(p)
+    nz = p > 0
+    _, ex = np.frexp(p[nz])
+    q = np.exp2((ex - 1 - 7).astype(np.float64))          # spacing of bf16 numbers around p
+    q = np.maximum(q, 2.0 ** -133)
+    lo_n = np.floor(p[nz] / q)
+    lo, hi = lo_n * q, (lo_n + 1) * q
+    dl, dh = p[nz] - lo, hi - p[nz]
+    pick_hi = (dh < dl) | ((dh == dl) & (lo_n % 2 == 1))
+    out[nz] = np.where(pick_hi, hi, lo)
+    return out
+
+
+def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p_round=True):
+    """Per-element rewrite of the diagonal-tiled attention for q[Hq,S,D], k,v[Hkv,S,D] (one batch).
+
+    For every (i, j <= i) the score comes from the format of the tile pair (i // tile, j // tile);
+    with p_round the probabilities are formed against the running maximum over key-tile prefixes
+    and rounded to bf16, otherwise it is a plain base-2 row softmax."""
+    Hq, S, D = q_bits.shape
+    Hkv = k_bits.shape[0]
+    g = Hq // Hkv
+    out = np.zeros((Hq, S, D))
+    v = bf16_bits_to_f64(v_bits)
+    for h in range(Hq):
+        _, _, q_hi = quantize_rows(q_bits[h], hi, True)
+        _, _, q_lo = quantize_rows(q_bits[h], lo, True)
+        _, _, k_hi = quantize_rows(k_bits[h // g], hi, False)
+        _, _, k_lo = quantize_rows(k_bits[h // g], lo, False)
+        s_hi = q_hi @ k_hi.T
+        s_lo = q_lo @ k_lo.T
+        ti = np.arange(S)[:, None] // tile
+        tj = np.arange(S)[None, :] // tile
+        s = np.where(ti - tj < band, s_hi, s_lo)
+        for i in range(S):
+            si = s[i, :i + 1]
+            if not p_round:
+                p = np.exp2(si - si.max())
+                out[h, i] = (p @ v[h // g, :i + 1]) / p.sum()
+                continue
+            nt = i // tile + 1
+            # running maximum after each key tile
+            run = np.array([si[:min((t + 1) * tile, i + 1)].max() for t in range(nt)])
+            mj = run[np.arange(i + 1) // tile]           # maximum in force when key j was processed
+            mfin = run[-1]
+            p_at = np.exp2(si - mj)
+            p_hat = round_bf16_nearest_of_two(p_at)
+            w_num = p_hat * np.exp2(mj - mfin)
+            w_den = (p_at * np.exp2(mj - mfin)).sum()
+            out[h, i] = (w_num @ v[h // g, :i + 1]) / w_den
+    return out
+
+
+def softmax_attention_fp64(q, k, v):
+    """Plain causal softmax attention of real-valued q[Hq,S,D], k,v[Hkv,S,D] (doubles)."""
+    Hq, S, D = q.shape
+    g = Hq // k.shape[0]
+    out = np.zeros((Hq, S, D))
+    for h in range(Hq):
+        s = (q[h] @ k[h // g].T) / np.sqrt(D)
+        s = np.where(np.arange(S)[None, :] > np.arange(S)[:, None], -np.inf, s)
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        out[h] = (p / p.sum(axis=1, keepdims=True)) @ v[h // g]
+    return out

@@ -1,0 +1,342 @@
+"""Pins for the CPU oracle: values the paper prints, closed forms, brute force on tiny inputs and
+library routines.  None of these touch the GPU or the HIP library."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import brute
+from paper_2604_03950_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def all_bf16_in(lo, hi):
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = brute.bf16_bits_to_f64(bits)
+    keep = np.isfinite(vals) & (vals >= lo) & (vals <= hi)
+    return bits[keep], vals[keep]
+
+
+# ------------------------------------------------------------------ element formats
+
+def test_e2m1_paper_examples(oracle):
+    """Alg. 3 / "Encoding of FP4 format": bit layout (S<<3)|(E<<1)|M, thresholds {1,2,4}, the
+    tie example 5 -> 4, strict comparison at the midpoints 0.25 and 1.25 (normalised)."""
+    with open(os.path.join(GOLDEN, "e2m1_paper_examples.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        assert oracle.e2m1_encode(c["x"]) == c["code"], c
+        assert oracle.e2m1_decode(c["code"]) == c["decoded"], c
+
+
+def test_e2m1_grid_roundtrip_and_ties(oracle):
+    for code in range(16):
+        v = oracle.e2m1_decode(code)
+        assert abs(v) == brute.E2M1_GRID[code & 7]
+        assert np.signbit(v) == bool(code & 8)
+        assert oracle.e2m1_encode(v) == code
+    # midpoints go to the even code
+    for x, want in [(0.25, 0.0), (0.75, 1.0), (1.25, 1.0), (1.75, 2.0), (2.5, 2.0), (3.5, 4.0), (5.0, 4.0)]:
+        assert oracle.e2m1_decode(oracle.e2m1_encode(x)) == want
+        assert oracle.e2m1_decode(oracle.e2m1_encode(-x)) == -want
+    # just past a midpoint goes up
+    for x, want in [(0.2501, 0.5), (1.2501, 1.5), (5.0001, 6.0), (0.7501, 1.0)]:
+        assert oracle.e2m1_decode(oracle.e2m1_encode(x)) == want
+    assert oracle.e2m1_encode(-0.0) == 8 and oracle.e2m1_encode(-0.1) == 8    # sign survives underflow
+
+
+def test_e2m1_bruteforce_all_bf16(oracle):
+    bits, vals = all_bf16_in(-6.0, 6.0)
+    for b, v in zip(bits, vals):
+        neg = bool(b & 0x8000)
+        want = brute.nearest_code(brute.E2M1_GRID, abs(v)) | (8 if neg else 0)
+        assert oracle.e2m1_encode(float(v)) == want, (hex(b), v)
+
+
+def test_e4m3_codes_roundtrip_and_fixed_points(oracle):
+    for code in list(range(0x7F)) + list(range(0x80, 0xFF)):
+        v = oracle.e4m3_decode(code)
+        assert abs(v) == brute.E4M3_GRID[code & 0x7F]
+        assert oracle.e4m3_encode(v) == code
+    assert oracle.e4m3_decode(0x7E) == 448.0 and oracle.e4m3_encode(448.0) == 0x7E
+    assert oracle.e4m3_decode(0x38) == 1.0 and oracle.e4m3_decode(0x08) == 2.0 ** -6
+    assert oracle.e4m3_encode(2.0 ** -9) == 0x01
+    assert oracle.e4m3_encode(2.0 ** -10) == 0x00          # tie between 0 and 2^-9 -> even
+    assert oracle.e4m3_encode(3 * 2.0 ** -10) == 0x02      # tie between codes 1 and 2 -> even
+    assert oracle.e4m3_encode(-(2.0 ** -12)) == 0x80       # negative underflow keeps the sign
+    assert oracle.e4m3_encode(1.0625) == 0x38              # tie 1.0 / 1.125 -> even mantissa
+    assert oracle.e4m3_encode(1.1875) == 0x3A              # tie 1.125 / 1.25 -> even mantissa
+    assert oracle.e4m3_encode(1.96875) == 0x40             # rounds up across the binade
+    assert oracle.e4m3_encode(464.0) == 0x7E               # would round past the top: saturates
+
+
+def test_e4m3_bruteforce_all_bf16(oracle):
+    bits, vals = all_bf16_in(-448.0, 448.0)
+    rng = np.random.default_rng(0)
+    idx = np.unique(np.concatenate([rng.choice(len(bits), 6000, replace=False),
+                                    np.flatnonzero(np.abs(vals) >= 2.0 ** -11)[::3]]))
+    for i in idx:
+        b, v = bits[i], vals[i]
+        want = brute.nearest_code(brute.E4M3_GRID, abs(v)) | (0x80 if (b & 0x8000) else 0)
+        assert oracle.e4m3_encode(float(v)) == want, (hex(b), v)
+
+
+# ------------------------------------------------------------------ shared scale (Alg. 2 Steps 6-7)
+
+def test_e8m0_hand_built_blocks(oracle):
+    for k in (-20, -3, 0, 1, 7, 40):
+        assert oracle.e8m0_from_amax(6.0 * 2.0 ** k, oracle.FMT_E2M1) == 127 + k
+        assert oracle.e8m0_from_amax(7.0 * 2.0 ** k, oracle.FMT_E2M1) == 127 + k
+        assert oracle.e8m0_from_amax(448.0 * 2.0 ** k, oracle.FMT_E4M3) == 127 + k
+        assert oracle.e8m0_from_amax(4.0 * 2.0 ** k, oracle.FMT_E2M1) == 127 + k
+        assert oracle.e8m0_from_amax(3.999 * 2.0 ** k, oracle.FMT_E2M1) == 126 + k
+    assert oracle.e8m0_from_amax(1.0, oracle.FMT_E2M1) == 125
+    assert oracle.e8m0_from_amax(1.0, oracle.FMT_E4M3) == 119
+    assert oracle.e8m0_from_amax(0.0, oracle.FMT_E2M1) == 0
+    assert oracle.e8m0_from_amax(0.0, oracle.FMT_E4M3) == 0
+    assert oracle.e8m0_from_amax(1e-45, oracle.FMT_E4M3) == 0            # clamp at 0
+    assert oracle.e8m0_from_amax(2.0 ** -126, oracle.FMT_E2M1) == 0
+    assert oracle.e8m0_from_amax(3.0e38, oracle.FMT_E2M1) == 127 + 127 - 2
+
+
+def test_e8m0_matches_floor_log2_search(oracle):
+    rng = np.random.default_rng(1)
+    a = np.exp2(rng.uniform(-60, 60, 500)).astype(np.float32)
+    for x in a:
+        for fmt, emax in ((oracle.FMT_E2M1, 2), (oracle.FMT_E4M3, 8)):
+            want = min(max(brute.floor_log2(float(x)) - emax + 127, 0), 254)
+            assert oracle.e8m0_from_amax(float(x), fmt) == want
+
+
+def test_saturating_block(oracle):
+    """amax = 7 * 2^k: scale 127+k and the maximum saturates to 6 (clamp before encode, Alg. 2 Step 3)."""
+    x = np.zeros((1, 32), dtype=np.float32)
+    x[0, 3] = 7.0 * 4
+    x[0, 4] = -7.5 * 4
+    x[0, 5] = 1.0
+    codes, scales = oracle.mx_quantize(wl.f32_to_bf16_bits(x), oracle.FMT_E2M1, False)
+    assert scales[0, 0] == 129
+    dec = oracle.mx_dequantize(codes, scales, oracle.FMT_E2M1)
+    assert dec[0, 3] == 24.0 and dec[0, 4] == -24.0
+    assert dec[0, 5] == 0.0           # 1/4 is the midpoint of 0 and 0.5: tie -> even code 0
+    x = np.zeros((1, 32), dtype=np.float32)
+    x[0, 0] = 500.0          # E4M3: floor(log2 500) = 8 -> scale 127, 500 > 448 saturates
+    codes, scales = oracle.mx_quantize(wl.f32_to_bf16_bits(x), oracle.FMT_E4M3, False)
+    assert scales[0, 0] == 127 and codes[0, 0] == 0x7E
+
+
+def test_packing_nibbles(oracle):
+    """Alg. 2 Step 5 / "Packing": (H << 4) | L, higher index in the high nibble."""
+    x = np.zeros((1, 32), dtype=np.float32)
+    x[0, 0] = 1.5       # code 3
+    x[0, 1] = -1.0      # code 8|2 = 10
+    x[0, 31] = 6.0      # block max -> scale 127
+    codes, scales = oracle.mx_quantize(wl.f32_to_bf16_bits(x), oracle.FMT_E2M1, False)
+    assert scales[0, 0] == 127
+    assert codes[0, 0] == 0xA3
+    assert codes[0, 15] == 0x70
+
+
+def test_grid_values_roundtrip_every_scale(oracle):
+    """Blocks made of grid values times a power of two, with a full-scale element, decode to themselves."""
+    rng = np.random.default_rng(2)
+    for fmt, grid, top in ((oracle.FMT_E2M1, brute.E2M1_GRID, 6.0), (oracle.FMT_E4M3, brute.E4M3_GRID[::5], 448.0)):
+        for k in range(-30, 31, 3):
+            vals = rng.choice(grid, size=(4, 64)) * rng.choice([-1.0, 1.0], size=(4, 64))
+            vals[:, 0] = top
+            vals[:, 32] = -top
+            x = (vals * 2.0 ** k).astype(np.float32)
+            bits = wl.f32_to_bf16_bits(x)
+            assert np.array_equal(wl.bf16_bits_to_f32(bits), x)         # representable in bf16
+            codes, scales = oracle.mx_quantize(bits, fmt, False)
+            assert np.all(scales == 127 + k)
+            assert np.array_equal(oracle.mx_dequantize(codes, scales, fmt), x.astype(np.float64))
+
+
+def test_query_prescale_single_rounding(oracle):
+    """Alg. 2 Step 1: x * log2(e)/sqrt(D) as one float32 multiply."""
+    assert oracle.query_prescale(64) == float(np.float32(np.log2(np.e) / 8.0))
+    assert oracle.query_prescale(128) == float(np.float32(np.log2(np.e) / np.sqrt(128.0)))
+    rng = np.random.default_rng(3)
+    bits = wl.f32_to_bf16_bits(rng.standard_normal((8, 64)).astype(np.float32) * 3)
+    x = brute.bf16_bits_to_f64(bits)
+    c = float(np.float32(np.log2(np.e) / 8.0))
+    prod = (x * c).astype(np.float32)                   # double product rounded once == float32 product
+    _, codes_q = None, None
+    sc_b, cd_b, _ = brute.quantize_rows(bits, "e4m3", True)
+    codes, scales = oracle.mx_quantize(bits, oracle.FMT_E4M3, True)
+    assert np.array_equal(codes, cd_b) and np.array_equal(scales, sc_b)
+    # and the scale really comes from the pre-scaled values
+    amax = np.abs(prod.reshape(8, 2, 32)).max(-1)
+    want = np.array([[oracle.e8m0_from_amax(float(a), oracle.FMT_E4M3) for a in r] for r in amax])
+    assert np.array_equal(scales, want)
+
+
+def test_quantizer_matches_bruteforce_on_tiny_workload(oracle):
+    q, k, _ = wl.generate(wl.CONFIGS["tiny"])
+    for bits, is_q in ((q[0, 0, :96], True), (k[0, 1, 64:160], False)):
+        for fmt, name in ((oracle.FMT_E2M1, "e2m1"), (oracle.FMT_E4M3, "e4m3")):
+            sc_b, cd_b, dec_b = brute.quantize_rows(bits, name, is_q)
+            codes, scales = oracle.mx_quantize(bits, fmt, is_q)
+            assert np.array_equal(scales, sc_b)
+            want = brute.pack_fp4(cd_b) if fmt == oracle.FMT_E2M1 else cd_b
+            assert np.array_equal(codes, want)
+            assert np.array_equal(oracle.mx_dequantize(codes, scales, fmt), dec_b)
+
+
+def test_edge_blocks(oracle):
+    """Zero block, negative zero, tiny and huge magnitudes, mixed-sign underflow."""
+    x = np.zeros((5, 32), dtype=np.float32)
+    x[1, :] = -0.0
+    x[2, 0], x[2, 1], x[2, 2] = 1.0, -1e-6, 1e-6
+    x[3, 0], x[3, 1] = 3.0e38, -1.0e38
+    x[4, 0], x[4, 1] = 2.0 ** -130, -(2.0 ** -133)
+    bits = wl.f32_to_bf16_bits(x)
+    for fmt, name, neg0 in ((oracle.FMT_E2M1, "e2m1", 8), (oracle.FMT_E4M3, "e4m3", 0x80)):
+        sc_b, cd_b, _ = brute.quantize_rows(bits, name, False)
+        codes, scales = oracle.mx_quantize(bits, fmt, False)
+        want = brute.pack_fp4(cd_b) if fmt == oracle.FMT_E2M1 else cd_b
+        assert np.array_equal(codes, want) and np.array_equal(scales, sc_b)
+        assert scales[0, 0] == 0 and scales[1, 0] == 0
+        first = codes[1, 0] & 15 if fmt == oracle.FMT_E2M1 else codes[1, 0]
+        assert first == neg0
+
+
+# ------------------------------------------------------------------ bf16 rounding of P
+
+def test_round_to_bf16_against_torch_and_ties(oracle):
+    rng = np.random.default_rng(4)
+    x = np.exp2(rng.uniform(-30, 0, 4000)).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    got = np.array([oracle.round_to_bf16(float(v)) for v in x])
+    assert np.array_equal(got, want)
+    assert oracle.round_to_bf16(1.0 + 2.0 ** -8) == 1.0                  # tie -> even
+    assert oracle.round_to_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6  # tie -> even (up)
+    assert oracle.round_to_bf16(1.0 + 2.0 ** -8 + 2.0 ** -40) == 1.0 + 2.0 ** -7   # single rounding
+    assert oracle.round_to_bf16(1.0 + 2.0 ** -8 - 2.0 ** -40) == 1.0
+    assert oracle.round_to_bf16(0.0) == 0.0 and oracle.round_to_bf16(1.0) == 1.0
+    p = np.exp2(rng.uniform(-20, 0, 2000))
+    assert np.array_equal(np.array([oracle.round_to_bf16(float(v)) for v in p]),
+                          brute.round_bf16_nearest_of_two(p))
+
+
+# ------------------------------------------------------------------ attention
+
+@pytest.fixture(scope="module")
+def tiny():
+    w = wl.CONFIGS["tiny"]
+    return (w,) + wl.generate(w)
+
+
+def test_unquantized_reference_matches_torch_sdpa(oracle, tiny):
+    w, q, k, v = tiny
+    rows = oracle.all_rows(w.B, w.Hq, w.S)
+    got = oracle.ref_attn_rows(q, k, v, rows).reshape(w.B, w.Hq, w.S, w.D)
+    tq, tk, tv = (torch.from_numpy(wl.bf16_bits_to_f32(a)).double() for a in (q, k, v))
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True).numpy()
+    assert np.max(np.abs(got - want)) < 1e-12
+
+
+def test_online_softmax_skeleton_against_sdpa(oracle, tiny):
+    """With both formats = bf16 and exact P, the tiled base-2 online softmax with the causal mask
+    must equal the library's causal attention (Sec. 3.2, eq. 1), for several tile sizes and GQA."""
+    w, q, k, v = tiny
+    tq, tk, tv = (torch.from_numpy(wl.bf16_bits_to_f32(a)).double() for a in (q, k, v))
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True).numpy()
+    for tile in (16, 64, 256):
+        for band in (0, 1, 3):
+            got = oracle.dma_attn(q, k, v, tile=tile, band=band, hi_fmt=oracle.FMT_BF16,
+                                  lo_fmt=oracle.FMT_BF16, p_round=False)
+            assert np.max(np.abs(got - want)) < 2e-6      # float32 output rounding only
+    # grouped-query mapping: q head h reads kv head h // (Hq/Hkv)
+    k1, v1 = k[:, :1], v[:, :1]
+    got = oracle.dma_attn(q, k1, v1, tile=64, band=1, hi_fmt=oracle.FMT_BF16, lo_fmt=oracle.FMT_BF16,
+                          p_round=False)
+    want = torch.nn.functional.scaled_dot_product_attention(
+        tq, tk[:, :1].expand(-1, 2, -1, -1), tv[:, :1].expand(-1, 2, -1, -1), is_causal=True).numpy()
+    assert np.max(np.abs(got - want)) < 2e-6
+
+
+def test_all_high_equals_softmax_of_dequantized(oracle, tiny):
+    """Band covering every tile, E4M3, exact P == brute-force fp64 attention of the decoded Q~, K."""
+    w, q, k, v = tiny
+    got = oracle.dma_attn(q, k, v, tile=w.tile, band=10 ** 6, p_round=False)[0]
+    cq, sq = oracle.mx_quantize(q, oracle.FMT_E4M3, True)
+    ck, sk = oracle.mx_quantize(k, oracle.FMT_E4M3, False)
+    dq = oracle.mx_dequantize(cq, sq, oracle.FMT_E4M3)[0] * np.sqrt(w.D) / np.log2(np.e)
+    dk = oracle.mx_dequantize(ck, sk, oracle.FMT_E4M3)[0]
+    want = brute.softmax_attention_fp64(dq, dk, brute.bf16_bits_to_f64(v[0]))
+    assert np.max(np.abs(got - want)) < 2e-6
+
+
+@pytest.mark.parametrize("band", [0, 1, 2])
+@pytest.mark.parametrize("p_round", [False, True])
+def test_mixed_tiles_match_per_element_rewrite(oracle, tiny, band, p_round):
+    w, q, k, v = tiny
+    got = oracle.dma_attn(q, k, v, tile=w.tile, band=band, p_round=p_round)[0]
+    want = brute.dma_attention(q[0], k[0], v[0], tile=w.tile, band=band, p_round=p_round)
+    assert np.max(np.abs(got - want)) < 2e-6       # float32 output rounding only (|out| < 8)
+    assert np.max(np.abs(got - want) / np.maximum(np.abs(want), 1.0)) < 1.5e-7
+
+
+def test_first_row_and_constant_values(oracle, tiny):
+    w, q, k, v = tiny
+    for p_round in (False, True):
+        for band in (0, 1):
+            out = oracle.dma_attn(q, k, v, tile=w.tile, band=band, p_round=p_round)
+            # row 0 sees only key 0: p = 1 exactly, output = V[0]
+            assert np.array_equal(out[:, :, 0, :], wl.bf16_bits_to_f32(v)[:, :, 0, :])
+    vc = np.broadcast_to(v[:, :, :1, :], v.shape).copy()      # every value row identical
+    out = oracle.dma_attn(q, k, vc, tile=w.tile, band=1, p_round=False)
+    want = np.broadcast_to(wl.bf16_bits_to_f32(vc)[:, :, :1, :], out.shape)
+    assert np.max(np.abs(out - want)) < 1e-6                  # sum_j p_j / l == 1
+    out = oracle.dma_attn(q, k, vc, tile=w.tile, band=1, p_round=True)
+    assert np.max(np.abs(out - want) / np.abs(want).clip(1e-3)) < 2.0 ** -8
+
+
+def test_band_is_irrelevant_when_formats_coincide(oracle, tiny):
+    w, q, k, v = tiny
+    base = oracle.dma_attn(q, k, v, tile=w.tile, band=0, hi_fmt=oracle.FMT_E4M3, lo_fmt=oracle.FMT_E4M3)
+    for band in (1, 2, 100):
+        assert np.array_equal(base, oracle.dma_attn(q, k, v, tile=w.tile, band=band, hi_fmt=oracle.FMT_E4M3,
+                                                    lo_fmt=oracle.FMT_E4M3))
+    # a band covering everything == the high format everywhere
+    assert np.array_equal(base, oracle.dma_attn(q, k, v, tile=w.tile, band=w.S // w.tile))
+    lo_all = oracle.dma_attn(q, k, v, tile=w.tile, band=0)
+    assert np.array_equal(lo_all, oracle.dma_attn(q, k, v, tile=w.tile, band=0, hi_fmt=oracle.FMT_E2M1,
+                                                  lo_fmt=oracle.FMT_E2M1))
+
+
+def test_grid_exact_keys_make_formats_agree(oracle):
+    """Keys on the E2M1 grid with power-of-two block maxima decode identically in both formats, so
+    with the query format held fixed the band has no effect."""
+    rng = np.random.default_rng(5)
+    S, D = 128, 64
+    kv = rng.choice(brute.E2M1_GRID, size=(1, 1, S, D)) * rng.choice([-1.0, 1.0], size=(1, 1, S, D))
+    kv[..., 0] = 4.0
+    kv[..., 32] = -4.0
+    k = wl.f32_to_bf16_bits(kv.astype(np.float32))
+    ck4, sk4 = oracle.mx_quantize(k, oracle.FMT_E2M1, False)
+    ck8, sk8 = oracle.mx_quantize(k, oracle.FMT_E4M3, False)
+    assert np.array_equal(oracle.mx_dequantize(ck4, sk4, oracle.FMT_E2M1), kv)
+    assert np.array_equal(oracle.mx_dequantize(ck8, sk8, oracle.FMT_E4M3), kv)
+
+
+def test_error_trend_with_band(oracle):
+    """Sanity only (Tables 2 and 5): more high-precision tiles -> closer to the unquantized result,
+    and all-MXFP8 beats all-MXFP4."""
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=1024, Hq=2, Hkv=2)
+    q, k, v = wl.generate(w)
+    rows = wl.sample_rows(w, [7], [(0, 0), (0, 1)], 0, 1)
+    ref = oracle.ref_attn_rows(q, k, v, rows)
+    errs = []
+    for band in (0, 1, 2, 4, 8):
+        out = oracle.dma_attn_rows(q, k, v, rows, tile=128, band=band)
+        errs.append(float(np.sqrt(np.mean((out - ref) ** 2))))
+    assert errs[-1] < errs[0]
+    assert all(errs[i + 1] <= errs[i] * 1.05 for i in range(len(errs) - 1)), errs
+    all8 = oracle.dma_attn_rows(q, k, v, rows, tile=128, band=8)
+    assert float(np.sqrt(np.mean((all8 - ref) ** 2))) < 0.5 * errs[0]
