@@ -1,0 +1,127 @@
+/*
+ * dma.h -- C ABI of the MI355X (gfx950) library for the fused forward pass of Diagonal-Tiled
+ * Mixed-Precision Attention (DMA).
+ *
+ * Conventions for every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller (e.g. the storage of a PyTorch
+ *     tensor); the library allocates nothing, keeps no state between calls and writes only to the
+ *     output buffers named below.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue their
+ *     kernels on it and return without waiting.
+ *   - Return value: DMA_OK (0) or a negative error code.  On error nothing has been enqueued.
+ *     No C++ exception crosses the boundary.  dma_error_string() maps a code to a static string.
+ *   - bf16 tensors are dense and row-major with the head dimension D innermost.
+ *   - Inputs are assumed finite; NaN/Inf give unspecified results (never a fault).
+ */
+#ifndef DMA_H_
+#define DMA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    DMA_OK = 0,
+    DMA_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, bad enum value, misaligned pointer */
+    DMA_ERR_UNSUPPORTED = -2,   /* a valid request this build has no kernel for */
+    DMA_ERR_HIP = -3            /* the HIP runtime reported an error at launch */
+};
+
+/* Element formats.  MX formats carry one E8M0 scale byte per block of 32 consecutive elements
+ * along D (paper, Table 1 and Sec. 3.1). */
+enum {
+    DMA_FMT_BF16 = 0,           /* no quantization: plain bf16 operands */
+    DMA_FMT_MXFP8_E4M3 = 1,     /* FP8 E4M3 elements + E8M0 scale per 32 */
+    DMA_FMT_MXFP4_E2M1 = 2      /* FP4 E2M1 elements (two per byte) + E8M0 scale per 32 */
+};
+
+/*
+ * MX quantization of a matrix (paper, Alg. 2 "Fused Mixed-Precision Quantization", Steps 1 and 3-7,
+ * with the per-token scale of Step 2 equal to one; element encoding per Alg. 3 completed to a full
+ * round-to-nearest-even).
+ *
+ *   x_bf16   [rows, D] bf16, device, read only.  16-byte aligned.
+ *   rows     >= 0 (0 is a no-op).   D: multiple of 32, 32 <= D <= 1024.
+ *   fmt      DMA_FMT_MXFP8_E4M3 or DMA_FMT_MXFP4_E2M1.
+ *   is_query non-zero: every element is first multiplied by log2(e)/sqrt(D) in one binary32
+ *            multiplication (Alg. 2 Step 1).
+ *   codes_u8 out, device.  E4M3: [rows, D] bytes.  E2M1: [rows, D/2] bytes, element 2t in the low
+ *            nibble and 2t+1 in the high nibble (Alg. 2 Step 5).
+ *   scales_u8 out, device, [rows, D/32] bytes: clamp(floor(log2 max|block|) - e_max + 127, 0, 254)
+ *            with e_max = 8 (E4M3) or 2 (E2M1) (Alg. 2 Steps 6-7); an all-zero block gives 0.
+ *   Element = round-to-nearest-even of x / 2^(scale-127) after clamping to +-448 / +-6; the sign bit
+ *   is the sign bit of x even when the magnitude rounds to zero.
+ */
+int dma_mx_quantize(const void* x_bf16, int64_t rows, int D, int fmt, int is_query,
+                    void* codes_u8, void* scales_u8, void* stream);
+
+/* The same with both formats produced from ONE read of x (the "MP" fusion of Alg. 2: low copy =
+ * MXFP4 E2M1, high copy = MXFP8 E4M3).  Buffers as above. */
+int dma_mx_quantize_dual(const void* x_bf16, int64_t rows, int D, int is_query,
+                         void* codes_lo_u8, void* scales_lo_u8,
+                         void* codes_hi_u8, void* scales_hi_u8, void* stream);
+
+/*
+ * Fused DMA forward (paper, Alg. 1 "Diagonal-Tiled Mixed-Precision Attention" with the online
+ * softmax of Sec. 3.2, and the quantization of Alg. 2 done inside the kernel).
+ *
+ *   q   [B, Hq,  S, D] bf16      k, v [B, Hkv, S, D] bf16      out [B, Hq, S, D] float32
+ *   All device, dense, 16-byte aligned.  Hq % Hkv == 0; query head h reads kv head h / (Hq/Hkv).
+ *   causal            must be non-zero (the non-causal variant is not built: DMA_ERR_UNSUPPORTED).
+ *   diag_band_tiles   b = T / B_N >= 0.  For the query tile `it`, key tile `jt` (jt <= it) is computed
+ *                     in hi_fmt iff it - jt < b, otherwise in lo_fmt.  b = 0: every tile in lo_fmt;
+ *                     b >= S/tile: every tile in hi_fmt.
+ *   hi_fmt, lo_fmt    DMA_FMT_* for the Q K^T product of the tiles in / outside the diagonal band.
+ *                     Supported pairs (lo, hi): (E2M1, E4M3), (E2M1, E2M1), (E4M3, E4M3), (BF16, BF16);
+ *                     any other pair returns DMA_ERR_UNSUPPORTED.
+ *   The logical tile is B_M = B_N = 128 for dma_attn_fwd; D must be 128 and S a multiple of 128.
+ *
+ *   Per key tile: scores in base 2 (the factor log2(e)/sqrt(D) is folded into Q before quantization;
+ *   for BF16 it multiplies the binary32 score), keys after the query masked to -inf on the diagonal
+ *   tile, running maximum / sum in binary32, probabilities rounded to bf16 for the P V product
+ *   (V stays bf16), binary32 accumulation, final division by the running sum.  No intermediate is
+ *   written to device memory.
+ */
+int dma_attn_fwd(const void* q, const void* k, const void* v, void* out,
+                 int B, int Hq, int Hkv, int S, int D, int causal,
+                 int diag_band_tiles, int hi_fmt, int lo_fmt, void* stream);
+
+/* Options for dma_attn_fwd_ex.  Zero-initialise, then set fields. */
+typedef struct dma_attn_opts {
+    int tile;             /* logical tile B_M = B_N: 128 (with D = 128) or 64 (with D = 64); 0 = 128 */
+    int sink_tiles;       /* must be 0 (a high-precision sink window is not built) */
+    int pv_fmt;           /* must be DMA_FMT_BF16 (V and P stay 16-bit, as in Alg. 1) */
+    int per_token_scale;  /* must be 0 (Alg. 2 Step 2 is the identity on this path) */
+    int fp8_mfma;         /* how MXFP8 tiles form Q K^T.
+                             0 (default): the E4M3 codes and E8M0 scales are decoded exactly to bf16 and
+                               multiplied on the bf16 MFMA: the product of the quantized operands is exact up to
+                               binary32 accumulation, as the method defines it.
+                             1: the codes and scales go to the block-scaled FP8 MFMA.  Its adder aligns the
+                               products of a block to the largest one and drops the bits below a fixed window,
+                               so scores dominated by a few large products carry an error of about 2^-11 of
+                               the largest product; twice the matrix rate of mode 0 on those tiles.
+                             MXFP4 tiles always use the block-scaled FP4 MFMA, which sums exactly. */
+} dma_attn_opts;
+
+/* dma_attn_fwd with explicit options; opts == NULL means the defaults of dma_attn_fwd. */
+int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out,
+                    int B, int Hq, int Hkv, int S, int D, int causal,
+                    int diag_band_tiles, int hi_fmt, int lo_fmt,
+                    const dma_attn_opts* opts, void* stream);
+
+/* Device scratch the forward needs beyond its inputs and output: always 0. */
+size_t dma_attn_fwd_workspace_bytes(int B, int Hq, int Hkv, int S, int D);
+
+/* Static, NUL-terminated description of a return code. */
+const char* dma_error_string(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int dma_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMA_H_ */

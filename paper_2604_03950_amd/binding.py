@@ -1,0 +1,147 @@
+"""Thin Python binding of the C-ABI library (``include/dma.h``): argument marshalling only.
+
+Every function takes PyTorch tensors that live on the GPU, passes their device pointers and the
+current HIP stream to the entry point of the same name, and raises ``DmaError`` on a non-zero
+return code.  There is no CPU fallback: if ``libdma_mi355x.so`` has not been built
+(``python -m paper_2604_03950_amd.build``) loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+FMT_BF16 = 0
+FMT_MXFP8_E4M3 = 1
+FMT_MXFP4_E2M1 = 2
+
+EXPORTS = ("dma_mx_quantize", "dma_mx_quantize_dual", "dma_attn_fwd", "dma_attn_fwd_ex",
+           "dma_attn_fwd_workspace_bytes", "dma_error_string", "dma_version")
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdma_mi355x.so")
+_lib = None
+
+
+class DmaError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {error_string(code)} (code {code})")
+
+
+class AttnOpts(ctypes.Structure):
+    _fields_ = [("tile", ctypes.c_int), ("sink_tiles", ctypes.c_int), ("pv_fmt", ctypes.c_int),
+                ("per_token_scale", ctypes.c_int), ("fp8_mfma", ctypes.c_int)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load the shared library (once).  Raises if it is missing: there is no other code path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(f"{_LIB_PATH} not found: build it with `python -m paper_2604_03950_amd.build`")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        L.dma_mx_quantize.restype = ci
+        L.dma_mx_quantize.argtypes = [vp, i64, ci, ci, ci, vp, vp, vp]
+        L.dma_mx_quantize_dual.restype = ci
+        L.dma_mx_quantize_dual.argtypes = [vp, i64, ci, ci, vp, vp, vp, vp, vp]
+        L.dma_attn_fwd.restype = ci
+        L.dma_attn_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, vp]
+        L.dma_attn_fwd_ex.restype = ci
+        L.dma_attn_fwd_ex.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(AttnOpts), vp]
+        L.dma_attn_fwd_workspace_bytes.restype = ctypes.c_size_t
+        L.dma_attn_fwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+        L.dma_error_string.restype = ctypes.c_char_p
+        L.dma_error_string.argtypes = [ci]
+        L.dma_version.restype = ci
+        L.dma_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def error_string(code: int) -> str:
+    return load().dma_error_string(int(code)).decode()
+
+
+def version() -> int:
+    return int(load().dma_version())
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, what: str) -> int:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{what}: need a contiguous {dtype} tensor on the GPU")
+    return t.data_ptr()
+
+
+def dma_mx_quantize(x: torch.Tensor, fmt: int, is_query: bool, codes: torch.Tensor | None = None,
+                    scales: torch.Tensor | None = None):
+    """x: [..., D] bf16 -> (codes uint8 [..., D] or [..., D/2], scales uint8 [..., D/32])."""
+    D = x.shape[-1]
+    rows = x.numel() // D
+    cb = D // 2 if fmt == FMT_MXFP4_E2M1 else D
+    if codes is None:
+        codes = torch.empty(x.shape[:-1] + (cb,), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty(x.shape[:-1] + (D // 32,), dtype=torch.uint8, device=x.device)
+    rc = load().dma_mx_quantize(_dev(x, torch.bfloat16, "x"), rows, D, fmt, int(bool(is_query)),
+                                _dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"), _stream())
+    if rc:
+        raise DmaError(rc, "dma_mx_quantize")
+    return codes, scales
+
+
+def dma_mx_quantize_dual(x: torch.Tensor, is_query: bool, out=None):
+    """One read of x -> (codes_lo, scales_lo, codes_hi, scales_hi): MXFP4 E2M1 and MXFP8 E4M3 copies."""
+    D = x.shape[-1]
+    rows = x.numel() // D
+    if out is None:
+        mk = lambda n: torch.empty(x.shape[:-1] + (n,), dtype=torch.uint8, device=x.device)
+        out = (mk(D // 2), mk(D // 32), mk(D), mk(D // 32))
+    c4, s4, c8, s8 = out
+    rc = load().dma_mx_quantize_dual(_dev(x, torch.bfloat16, "x"), rows, D, int(bool(is_query)),
+                                     _dev(c4, torch.uint8, "codes_lo"), _dev(s4, torch.uint8, "scales_lo"),
+                                     _dev(c8, torch.uint8, "codes_hi"), _dev(s8, torch.uint8, "scales_hi"), _stream())
+    if rc:
+        raise DmaError(rc, "dma_mx_quantize_dual")
+    return out
+
+
+def dma_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, diag_band_tiles: int,
+                 hi_fmt: int = FMT_MXFP8_E4M3, lo_fmt: int = FMT_MXFP4_E2M1, causal: bool = True,
+                 tile: int | None = None, fp8_mfma: bool = False, out: torch.Tensor | None = None) -> torch.Tensor:
+    """q [B,Hq,S,D], k/v [B,Hkv,S,D] bf16 -> out [B,Hq,S,D] float32.  With tile=None and fp8_mfma=False
+    this is dma_attn_fwd (logical tile 128); otherwise dma_attn_fwd_ex with those options."""
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    if k.shape != (B, Hkv, S, D) or v.shape != k.shape:
+        raise ValueError("k and v must be [B, Hkv, S, D] matching q")
+    if out is None:
+        out = torch.empty((B, Hq, S, D), dtype=torch.float32, device=q.device)
+    args = [_dev(q, torch.bfloat16, "q"), _dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v"),
+            _dev(out, torch.float32, "out"), B, Hq, Hkv, S, D, int(bool(causal)), int(diag_band_tiles),
+            int(hi_fmt), int(lo_fmt)]
+    if tile is None and not fp8_mfma:
+        rc = load().dma_attn_fwd(*args, _stream())
+    else:
+        opts = AttnOpts(tile=int(tile or 0), sink_tiles=0, pv_fmt=FMT_BF16, per_token_scale=0,
+                        fp8_mfma=int(bool(fp8_mfma)))
+        rc = load().dma_attn_fwd_ex(*args, ctypes.byref(opts), _stream())
+    if rc:
+        raise DmaError(rc, "dma_attn_fwd")
+    return out
+
+
+def bits_to_bf16_tensor(bits, device="cuda") -> torch.Tensor:
+    """uint16 numpy bit patterns -> bf16 tensor on the GPU (no value conversion)."""
+    import numpy as np
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16))
+    return t.view(torch.bfloat16).to(device)

@@ -1,0 +1,111 @@
+// C ABI entry points: argument checks and dispatch.  Every step of the path runs in the kernels.
+#include "../../include/dma.h"
+#include "dma_internal.hpp"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool valid_fmt(int f) { return f == DMA_FMT_BF16 || f == DMA_FMT_MXFP8_E4M3 || f == DMA_FMT_MXFP4_E2M1; }
+
+// rows == 0 is a no-op that never looks at the pointers (an empty tensor has none).
+int check_quant_common(const void* x, int64_t rows, int D)
+{
+    if (rows < 0) return DMA_ERR_INVALID_ARG;
+    if (D < 32 || D > 1024 || D % 32 != 0) return DMA_ERR_INVALID_ARG;
+    if (rows == 0) return DMA_OK;
+    if (!x) return DMA_ERR_INVALID_ARG;
+    if (!aligned16(x)) return DMA_ERR_INVALID_ARG;
+    if (rows > (int64_t)1 << 40) return DMA_ERR_UNSUPPORTED;
+    return DMA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dma_mx_quantize(const void* x_bf16, int64_t rows, int D, int fmt, int is_query, void* codes_u8,
+                    void* scales_u8, void* stream)
+{
+    int rc = check_quant_common(x_bf16, rows, D);
+    if (rc != DMA_OK) return rc;
+    if (fmt != DMA_FMT_MXFP8_E4M3 && fmt != DMA_FMT_MXFP4_E2M1) return DMA_ERR_INVALID_ARG;
+    if (rows == 0) return DMA_OK;
+    if (!codes_u8 || !scales_u8) return DMA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(codes_u8) & 7u) != 0) return DMA_ERR_INVALID_ARG;
+    if (fmt == DMA_FMT_MXFP4_E2M1)
+        return dma::launch_mx_quantize(x_bf16, rows, D, 2, is_query != 0, codes_u8, scales_u8, nullptr, nullptr,
+                                       (hipStream_t)stream);
+    return dma::launch_mx_quantize(x_bf16, rows, D, 1, is_query != 0, nullptr, nullptr, codes_u8, scales_u8,
+                                   (hipStream_t)stream);
+}
+
+int dma_mx_quantize_dual(const void* x_bf16, int64_t rows, int D, int is_query, void* codes_lo_u8,
+                         void* scales_lo_u8, void* codes_hi_u8, void* scales_hi_u8, void* stream)
+{
+    int rc = check_quant_common(x_bf16, rows, D);
+    if (rc != DMA_OK) return rc;
+    if (rows == 0) return DMA_OK;
+    if (!codes_lo_u8 || !scales_lo_u8 || !codes_hi_u8 || !scales_hi_u8) return DMA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(codes_lo_u8) & 3u) != 0 || (reinterpret_cast<uintptr_t>(codes_hi_u8) & 7u) != 0)
+        return DMA_ERR_INVALID_ARG;
+    return dma::launch_mx_quantize(x_bf16, rows, D, 3, is_query != 0, codes_lo_u8, scales_lo_u8, codes_hi_u8,
+                                   scales_hi_u8, (hipStream_t)stream);
+}
+
+int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int B, int Hq, int Hkv, int S,
+                    int D, int causal, int diag_band_tiles, int hi_fmt, int lo_fmt, const dma_attn_opts* opts,
+                    void* stream)
+{
+    if (!q || !k || !v || !out) return DMA_ERR_INVALID_ARG;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || S <= 0 || D <= 0) return DMA_ERR_INVALID_ARG;
+    if (Hq % Hkv != 0) return DMA_ERR_INVALID_ARG;
+    if (diag_band_tiles < 0) return DMA_ERR_INVALID_ARG;
+    if (!valid_fmt(hi_fmt) || !valid_fmt(lo_fmt)) return DMA_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return DMA_ERR_INVALID_ARG;
+    int tile = 128;
+    int fp8_mfma = 0;
+    if (opts) {
+        if (opts->fp8_mfma != 0 && opts->fp8_mfma != 1) return DMA_ERR_INVALID_ARG;
+        fp8_mfma = opts->fp8_mfma;
+        if (opts->tile != 0) tile = opts->tile;
+        if (opts->tile < 0) return DMA_ERR_INVALID_ARG;
+        if (opts->sink_tiles != 0 || opts->per_token_scale != 0) return DMA_ERR_UNSUPPORTED;
+        if (opts->pv_fmt != DMA_FMT_BF16) return DMA_ERR_UNSUPPORTED;
+    }
+    if (!causal) return DMA_ERR_UNSUPPORTED;
+    if (S % tile != 0) return DMA_ERR_UNSUPPORTED;
+    if ((int64_t)B * Hq * S * D > (int64_t)1 << 40) return DMA_ERR_UNSUPPORTED;
+    dma::AttnArgs a;
+    a.q = q; a.k = k; a.v = v; a.out = (float*)out;
+    a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.S = S; a.D = D;
+    a.tile = tile;
+    a.band = diag_band_tiles > S / tile ? S / tile : diag_band_tiles;
+    // public element format -> product path of the kernels (3 = MXFP8 decoded exactly, bf16 MFMA)
+    a.hi_fmt = (hi_fmt == DMA_FMT_MXFP8_E4M3 && !fp8_mfma) ? 3 : hi_fmt;
+    a.lo_fmt = (lo_fmt == DMA_FMT_MXFP8_E4M3 && !fp8_mfma) ? 3 : lo_fmt;
+    return dma::launch_attn_fwd(a, (hipStream_t)stream);
+}
+
+int dma_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int Hq, int Hkv, int S, int D,
+                 int causal, int diag_band_tiles, int hi_fmt, int lo_fmt, void* stream)
+{
+    return dma_attn_fwd_ex(q, k, v, out, B, Hq, Hkv, S, D, causal, diag_band_tiles, hi_fmt, lo_fmt, nullptr, stream);
+}
+
+size_t dma_attn_fwd_workspace_bytes(int, int, int, int, int) { return 0; }
+
+const char* dma_error_string(int code)
+{
+    switch (code) {
+        case DMA_OK: return "ok";
+        case DMA_ERR_INVALID_ARG: return "invalid argument (null or misaligned pointer, bad size or enum)";
+        case DMA_ERR_UNSUPPORTED: return "valid request, but no kernel in this build covers it";
+        case DMA_ERR_HIP: return "the HIP runtime reported an error at kernel launch";
+    }
+    return "unknown error code";
+}
+
+int dma_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,185 @@
+// Device-side building blocks shared by the DMA kernels (gfx950 / CDNA4 only).
+//
+// Operand layouts of the matrix instructions used here (wave64, lane l):
+//   v_mfma_scale_f32_32x32x64_f8f6f4, A (32 x 64) / B (64 x 32): lane l holds row (column) l % 32.
+//     FP4: 4 VGPRs = 32 consecutive k = 32 * (l / 32) + [0, 32), two codes per byte, even k in the
+//          low nibble.  The lane's own scale byte scales these 32 elements.
+//     FP8: 8 VGPRs.  VGPR 0-3 = k 16 * (l / 32) + [0, 16); VGPR 4-7 = k 32 + 16 * (l / 32) + [0, 16).
+//          The scale byte of lane l scales the 32-element block k in [32 * (l / 32), +32) of row l % 32.
+//   v_mfma_f32_32x32x16_bf16, A (32 x 16) / B (16 x 32): lane l holds row (column) l % 32,
+//          k = 8 * (l / 32) + [0, 8).
+//   32 x 32 accumulator: lane l holds column l % 32; VGPR r holds row 8 * (r / 4) + 4 * (l / 32) + r % 4.
+//   ds_read_b64_tr_b16: inside each group of 16 lanes, lane i receives element i % 4 ... precisely,
+//          out[i][e] = chunk[4 * e + i / 4][i % 4], where chunk[j] is the 8-byte row lane j points to.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define DMA_DEV __device__ __forceinline__
+#define DMA_DEV_CONSTEXPR __host__ __device__ constexpr
+
+namespace dma {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef short v2s __attribute__((ext_vector_type(2)));
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+// How the Q K^T product of a tile is formed.
+constexpr int FMT_BF16 = 0;      // unquantized bf16 operands, bf16 MFMA, score scaled afterwards
+constexpr int FMT_E4M3 = 1;      // MXFP8 codes + E8M0 scales fed to the block-scaled FP8 MFMA
+constexpr int FMT_E2M1 = 2;      // MXFP4 codes + E8M0 scales fed to the block-scaled FP4 MFMA
+constexpr int FMT_E4M3_X = 3;    // MXFP8-quantized values decoded exactly to bf16, bf16 MFMA
+// The FP8 datapath of the block-scaled MFMA aligns the products of a block to the largest one and
+// drops the bits below a fixed window, so a score dominated by one large product loses about
+// 2^-11 of that product; FP4 products and bf16 products are summed without such loss.  FMT_E4M3_X
+// therefore is the default for high-precision tiles: same codes and scales, exact product.
+DMA_DEV_CONSTEXPR bool uses_bf16_mfma(int fmt) { return fmt == FMT_BF16 || fmt == FMT_E4M3_X; }
+DMA_DEV_CONSTEXPR bool is_e4m3(int fmt) { return fmt == FMT_E4M3 || fmt == FMT_E4M3_X; }
+
+
+// Compile-time loop: body(std::integral_constant-like I) for I = 0 .. N-1.
+template <int I>
+struct IC {
+    static constexpr int value = I;
+    constexpr operator int() const { return I; }
+};
+template <int N, int I = 0, typename F>
+DMA_DEV void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(IC<I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
+DMA_DEV float bf16_lo(int w) { return __int_as_float(w << 16); }
+DMA_DEV float bf16_hi(int w) { return __int_as_float(w & 0xffff0000); }
+
+// max over the 4 lanes of a quad (lanes 4n .. 4n+3) with two DPP quad permutes.
+DMA_DEV float quad_max(float a)
+{
+    float b = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(a), 0xB1, 0xF, 0xF, true));  // [1,0,3,2]
+    a = fmaxf(a, b);
+    b = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(a), 0x4E, 0xF, 0xF, true));        // [2,3,0,1]
+    return fmaxf(a, b);
+}
+
+// E8M0 byte of a block with absolute maximum amax >= 0 (Alg. 2 Steps 6-7):
+// clamp(floor(log2 amax) - e_max + 127, 0, 254) == max(biased_exponent(amax) - e_max, 0).
+template <int FMT>
+DMA_DEV int e8m0_code(float amax)
+{
+    constexpr int emax = (FMT == FMT_E2M1) ? 2 : 8;      // E4M3 (either product path): 8
+    int e = (__float_as_int(amax) >> 23) & 0xff;
+    return max(e - emax, 0);
+}
+
+// The float handed to the scaled converts: they divide by 2^(exponent field - 127) and ignore the
+// mantissa, so a set mantissa bit keeps code 0 (2^-127) from reading as a zero.
+DMA_DEV float cvt_scale_operand(int code) { return __int_as_float((code << 23) | 0x00400000); }
+
+// Eight binary32 values -> eight E2M1 codes in one dword (element t in nibble t), divided by
+// 2^(code-127), round to nearest even, saturating at +-6, sign kept on underflow.
+DMA_DEV int encode8_e2m1(const float (&x)[8], int code)
+{
+    const float sc = cvt_scale_operand(code);
+    unsigned r = 0;
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, x[0], x[1], sc, 0);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, x[2], x[3], sc, 1);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, x[4], x[5], sc, 2);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, x[6], x[7], sc, 3);
+    return (int)r;
+}
+
+// Eight binary32 values -> eight E4M3 bytes (two dwords).  The hardware convert yields the NaN
+// code for magnitudes that round above 448, so values are clamped to +-448 * 2^(code-127) first
+// (Alg. 2 Step 6 clamps before the element conversion).
+DMA_DEV v2i encode8_e4m3(const float (&x)[8], int code)
+{
+    const float sc = cvt_scale_operand(code);
+    const float lim = __int_as_float(((code + 8) << 23) | 0x00600000);   // 1.75 * 2^(code + 8 - 127)
+    float y[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) y[t] = __builtin_amdgcn_fmed3f(x[t], -lim, lim);
+    v2s a = {0, 0}, b = {0, 0};
+    a = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(a, y[0], y[1], sc, false);
+    a = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(a, y[2], y[3], sc, true);
+    b = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(b, y[4], y[5], sc, false);
+    b = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(b, y[6], y[7], sc, true);
+    v2i r;
+    r[0] = __builtin_bit_cast(int, a);
+    r[1] = __builtin_bit_cast(int, b);
+    return r;
+}
+
+// Eight binary32 values -> MXFP8 E4M3 with scale byte `code` -> the decoded values as eight bf16
+// (exact: 4 significand bits and the combined exponent fit bf16; only blocks whose maximum is
+// below 2^-109 can underflow).  The decode convert multiplies by its scale operand, which is given
+// as the exact power of two 2^(code-127).
+DMA_DEV v4i quant_dequant8_e4m3(const float (&x)[8], int code)
+{
+    const v2i q = encode8_e4m3(x, code);
+    const float sc = __int_as_float(code ? (code << 23) : 0x00400000);
+    v4i r;
+    r[0] = __builtin_bit_cast(int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)q[0], sc, false));
+    r[1] = __builtin_bit_cast(int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)q[0], sc, true));
+    r[2] = __builtin_bit_cast(int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)q[1], sc, false));
+    r[3] = __builtin_bit_cast(int, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((unsigned)q[1], sc, true));
+    return r;
+}
+
+// Unpack a 16-byte chunk of eight bf16 into binary32, optionally pre-scaled (one multiply each).
+template <bool PRESCALE>
+DMA_DEV void unpack8(const v4i& w, float c, float (&x)[8])
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        x[2 * t] = bf16_lo(w[t]);
+        x[2 * t + 1] = bf16_hi(w[t]);
+    }
+    if (PRESCALE) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) x[t] = __fmul_rn(x[t], c);
+    }
+}
+
+DMA_DEV float amax8(const float (&x)[8])
+{
+    float a = fmaxf(fabsf(x[0]), fabsf(x[1]));
+    a = fmaxf(a, fmaxf(fabsf(x[2]), fabsf(x[3])));
+    a = fmaxf(a, fmaxf(fabsf(x[4]), fabsf(x[5])));
+    a = fmaxf(a, fmaxf(fabsf(x[6]), fabsf(x[7])));
+    return a;
+}
+
+// Exchange the upper 32 lanes of `a` with the lower 32 lanes of `b` (v_permlane32_swap).
+DMA_DEV void swap_halves(int& a, int& b)
+{
+    v2u r = __builtin_amdgcn_permlane32_swap((unsigned)a, (unsigned)b, false, false);
+    a = (int)r[0];
+    b = (int)r[1];
+}
+
+// Combine a value across the two half-waves (lane l and lane l ^ 32).
+DMA_DEV float cross_half_max(float x)
+{
+    v2u r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+DMA_DEV float cross_half_sum(float x)
+{
+    v2u r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+}  // namespace dma

@@ -1,0 +1,32 @@
+// Declarations shared by the translation units of the library (host side).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dma {
+
+// Mirror of the public return codes (the public header is included only by dma_api.hip).
+constexpr int DMA_OK_ = 0;
+constexpr int DMA_ERR_INVALID_ARG_ = -1;
+constexpr int DMA_ERR_UNSUPPORTED_ = -2;
+constexpr int DMA_ERR_HIP_ = -3;
+
+// mode: 1 = E4M3 only (c8/s8), 2 = E2M1 only (c4/s4), 3 = both.
+int launch_mx_quantize(const void* x, int64_t rows, int D, int mode, int is_query, void* c4, void* s4,
+                       void* c8, void* s8, hipStream_t stream);
+
+struct AttnArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    float* out;
+    int B, Hq, Hkv, S, D;
+    int tile;
+    int band;
+    int hi_fmt, lo_fmt;
+};
+
+int launch_attn_fwd(const AttnArgs& a, hipStream_t stream);
+
+}  // namespace dma

@@ -1,0 +1,80 @@
+// Standalone MX quantizer (paper, Alg. 2 Steps 1, 3-7; Alg. 3): one streaming pass, HBM bound.
+//
+// Work split: one lane converts one 16-byte chunk (8 bf16); the 4 lanes of a quad hold one MX block
+// of 32 elements, so the block maximum is two DPP quad permutes.  Loads are 16 B per lane and
+// contiguous across the wave; code stores are 4 B (FP4) / 8 B (FP8) per lane, contiguous; the scale
+// byte is written by the first lane of each quad.
+#include "dma_device.hpp"
+#include "dma_internal.hpp"
+
+namespace dma {
+
+constexpr int QUANT_THREADS = 256;
+constexpr int QUANT_UNROLL = 4;     // chunks per thread
+
+// MODE: 1 = E4M3 only, 2 = E2M1 only, 3 = both (low copy E2M1 + high copy E4M3).
+template <int MODE, bool IS_QUERY>
+__global__ void __launch_bounds__(QUANT_THREADS)
+mx_quantize_kernel(const v4i* __restrict__ x, int64_t n_chunks, float c,
+                   int* __restrict__ codes4, uint8_t* __restrict__ scales4,
+                   v2i* __restrict__ codes8, uint8_t* __restrict__ scales8)
+{
+    const int64_t base = ((int64_t)blockIdx.x * QUANT_UNROLL) * QUANT_THREADS + threadIdx.x;
+    v4i w[QUANT_UNROLL];
+#pragma unroll
+    for (int u = 0; u < QUANT_UNROLL; ++u) {
+        const int64_t ch = base + (int64_t)u * QUANT_THREADS;
+        w[u] = (ch < n_chunks) ? __builtin_nontemporal_load(x + ch) : v4i{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int u = 0; u < QUANT_UNROLL; ++u) {
+        const int64_t ch = base + (int64_t)u * QUANT_THREADS;
+        float v[8];
+        unpack8<IS_QUERY>(w[u], c, v);
+        const float amax = quad_max(amax8(v));      // every lane of the wave executes the DPP
+        if (ch >= n_chunks) continue;
+        const bool writes_scale = (threadIdx.x & 3) == 0;
+        if (MODE & 2) {
+            const int code = e8m0_code<FMT_E2M1>(amax);
+            __builtin_nontemporal_store(encode8_e2m1(v, code), codes4 + ch);
+            if (writes_scale) scales4[ch >> 2] = (uint8_t)code;
+        }
+        if (MODE & 1) {
+            const int code = e8m0_code<FMT_E4M3>(amax);
+            __builtin_nontemporal_store(encode8_e4m3(v, code), codes8 + ch);
+            if (writes_scale) scales8[ch >> 2] = (uint8_t)code;
+        }
+    }
+}
+
+template <int MODE>
+static int launch_mode(const void* x, int64_t rows, int D, int is_query, void* c4, void* s4, void* c8,
+                       void* s8, hipStream_t stream)
+{
+    const int64_t n_chunks = rows * (int64_t)(D / 8);
+    if (n_chunks == 0) return DMA_OK_;
+    const int64_t per_block = (int64_t)QUANT_THREADS * QUANT_UNROLL;
+    const int64_t blocks = (n_chunks + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
+    const float c = (float)(1.4426950408889634074 / sqrt((double)D));
+    if (is_query)
+        hipLaunchKernelGGL((mx_quantize_kernel<MODE, true>), dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream,
+                           (const v4i*)x, n_chunks, c, (int*)c4, (uint8_t*)s4, (v2i*)c8, (uint8_t*)s8);
+    else
+        hipLaunchKernelGGL((mx_quantize_kernel<MODE, false>), dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream,
+                           (const v4i*)x, n_chunks, c, (int*)c4, (uint8_t*)s4, (v2i*)c8, (uint8_t*)s8);
+    return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
+}
+
+int launch_mx_quantize(const void* x, int64_t rows, int D, int mode, int is_query, void* c4, void* s4,
+                       void* c8, void* s8, hipStream_t stream)
+{
+    switch (mode) {
+        case 1: return launch_mode<1>(x, rows, D, is_query, c4, s4, c8, s8, stream);
+        case 2: return launch_mode<2>(x, rows, D, is_query, c4, s4, c8, s8, stream);
+        case 3: return launch_mode<3>(x, rows, D, is_query, c4, s4, c8, s8, stream);
+    }
+    return DMA_ERR_INVALID_ARG_;
+}
+
+}  // namespace dma

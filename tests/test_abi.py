@@ -1,0 +1,67 @@
+"""The C-ABI library loads and exports every symbol include/dma.h declares; argument checks that
+return before any GPU work behave as documented.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2604_03950_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dma.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dma_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.lib_path()):
+        from paper_2604_03950_amd import build
+        build.build()
+    return binding.load()
+
+
+def test_header_and_library_agree(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_error_strings(lib):
+    assert binding.version() >= 100
+    assert binding.error_string(0) == "ok"
+    for code in (-1, -2, -3, -99):
+        assert isinstance(binding.error_string(code), str) and binding.error_string(code)
+
+
+def test_argument_checks_return_before_any_launch(lib):
+    fake = ctypes.c_void_p(0x1000)       # never dereferenced: every call below fails validation first
+    assert lib.dma_mx_quantize(None, 4, 128, 2, 0, fake, fake, None) == -1
+    assert lib.dma_mx_quantize(fake, 4, 100, 2, 0, fake, fake, None) == -1          # D not a multiple of 32
+    assert lib.dma_mx_quantize(fake, -1, 128, 2, 0, fake, fake, None) == -1
+    assert lib.dma_mx_quantize(fake, 4, 128, 0, 0, fake, fake, None) == -1          # bf16 is not a quantized format
+    assert lib.dma_mx_quantize(ctypes.c_void_p(0x1004), 4, 128, 2, 0, fake, fake, None) == -1   # misaligned
+    assert lib.dma_mx_quantize_dual(fake, 4, 128, 0, fake, None, fake, fake, None) == -1
+    args = dict(B=1, Hq=4, Hkv=2, S=256, D=128, causal=1, band=1, hi=1, lo=2)
+
+    def attn(**kw):
+        a = dict(args, **kw)
+        return lib.dma_attn_fwd(fake, fake, fake, fake, a["B"], a["Hq"], a["Hkv"], a["S"], a["D"], a["causal"],
+                                a["band"], a["hi"], a["lo"], None)
+    assert attn(Hq=3) == -1                   # Hq % Hkv != 0
+    assert attn(band=-1) == -1
+    assert attn(hi=7) == -1
+    assert attn(B=0) == -1
+    assert attn(causal=0) == -2               # non-causal: not built
+    assert attn(S=200) == -2                  # not a multiple of the tile
+    assert attn(D=96) == -2                   # no kernel for this head dimension
+    assert attn(hi=2, lo=1) == -2             # unsupported format pair
+    assert lib.dma_attn_fwd(None, fake, fake, fake, 1, 4, 2, 256, 128, 1, 1, 1, 2, None) == -1
+    opts = binding.AttnOpts(tile=128, sink_tiles=1, pv_fmt=0, per_token_scale=0, fp8_mfma=0)
+    assert lib.dma_attn_fwd_ex(fake, fake, fake, fake, 1, 4, 2, 256, 128, 1, 1, 1, 2, ctypes.byref(opts), None) == -2
+    assert lib.dma_attn_fwd_workspace_bytes(1, 32, 8, 32768, 128) == 0
