@@ -1,35 +1,46 @@
 // Fused forward of Diagonal-Tiled Mixed-Precision Attention for gfx950 (paper, Alg. 1 with the
 // online softmax of Sec. 3.2; Q/K quantization of Alg. 2 done in-kernel).
 //
-// One workgroup owns one logical query tile (B_M = BT rows) of one (batch, query head) and walks the
-// key tiles jt = 0 .. it in ascending order: Phase 1 = tiles before the diagonal band in the low
-// format, Phase 2 = the last `band` tiles in the high format.  Each wave owns QB blocks of 32 query
-// rows.  Everything is computed transposed so that a query row lives in one lane column:
+// Work split.  One workgroup owns TPW consecutive logical query tiles (B_M = BT rows each) of one
+// (batch, query head) and walks the key tiles jt = 0, 1, ... in ascending order, so one K/V tile
+// fetched and quantized once serves TPW * BT query rows.  Each wave owns 32 query rows of one
+// logical tile `it` and follows Alg. 1 for that tile: key tiles before the diagonal band in the low
+// format (Phase 1), the last `band` tiles up to the diagonal one in the high format (Phase 2),
+// tiles after its diagonal are skipped.
+//
+// Everything is computed transposed so that a query row lives in one lane column:
 //     S^T[key, query] = K . Q^T      block-scaled MFMA 32x32x64 (A = K codes from LDS, B = Q codes in VGPRs)
+//                                     or bf16 MFMA 32x32x16 for the exact MXFP8 / unquantized paths
 //     O^T[d,  query] += V^T . P^T    bf16 MFMA 32x32x16 (A = V^T via LDS transpose reads, B = P^T = the
 //                                     exponentiated S^T accumulators, already in operand layout)
 // so the row maximum / sum need one cross-half exchange and the running state (m, l) is per lane.
 //
-// Per key tile: all threads stream K and V (bf16, 16 B per lane, coalesced) into registers one tile
-// ahead; K is quantized to the tile's format (block maximum over a lane quad by DPP, E8M0 scale,
-// hardware scaled converts) and written to LDS as codes + scale bytes; V goes to LDS as bf16.
+// Pipeline.  K and V of tile jt+2 are in flight from global memory (16 B per lane, coalesced) while
+// tile jt is computed out of LDS buffer jt & 1 and tile jt+1 is quantized (block maximum over a lane
+// quad by DPP, E8M0 scale, hardware scaled converts) into buffer (jt+1) & 1: one barrier per tile.
+// Two waves per SIMD let the matrix pipe of one wave overlap the softmax / quantization VALU work of
+// the other.
 #include "dma_device.hpp"
 #include "dma_internal.hpp"
 
 namespace dma {
 
-template <int D_, int BT_, int NW_, int QB_>
+template <int A, int B>
+constexpr int cmax() { return A > B ? A : B; }
+
+template <int D_, int BT_, int TPW_>
 struct Cfg {
-    static constexpr int D = D_, BT = BT_, NW = NW_, QB = QB_;
+    static constexpr int D = D_, BT = BT_, TPW = TPW_;
+    static constexpr int WPT = BT / 32;          // waves per logical query tile (32 rows each)
+    static constexpr int NW = WPT * TPW;         // waves per workgroup
     static constexpr int T = NW * 64;            // threads per workgroup
     static constexpr int NKB = BT / 32;          // 32-key blocks per key tile
     static constexpr int NDB = D / 32;           // 32-wide blocks of the head dimension (output)
     static constexpr int NH = D / 64;            // k=64 scaled MFMAs per score block
-    static constexpr int NKK = D / 16;           // k=16 bf16 MFMAs per score block (BF16 format)
+    static constexpr int NKK = D / 16;           // k=16 bf16 MFMAs per score block
     static constexpr int CPR = D / 8;            // 16-byte chunks per row
     static constexpr int CH = BT * CPR;          // chunks per tile
     static constexpr int CPT = CH / T;           // chunks per thread
-    static_assert(NW * QB * 32 == BT, "a workgroup covers exactly one logical query tile");
     static_assert(CH % T == 0, "tile must split evenly over the threads");
     static_assert(D % 64 == 0, "head dimension must be a multiple of 64");
     // LDS row strides in bytes; the padding spreads consecutive rows over the banks.
@@ -37,88 +48,76 @@ struct Cfg {
     static constexpr int KS8 = D + 16;           // E4M3 codes
     static constexpr int KSB = 2 * D + 16;       // bf16 keys
     static constexpr int VS = 2 * D + 64;        // bf16 values (transpose reads)
+    static constexpr int KSC = BT * 8;           // scale bytes of one tile (2 dwords per key)
+    static constexpr int VBYTES = BT * VS;
     template <int FMT>
-    static constexpr int kstride() { return FMT == FMT_E2M1 ? KS4 : FMT == FMT_E4M3 ? KS8 : KSB; }   // bf16 MFMA paths: KSB
+    static constexpr int kstride() { return FMT == FMT_E2M1 ? KS4 : FMT == FMT_E4M3 ? KS8 : KSB; }
+    template <int FMT>
+    static constexpr int kbytes() { return BT * kstride<FMT>(); }
+    // Query operand storage in 16-byte units: scaled MFMA: NH x (4 or 8 dwords); bf16 MFMA: NKK x 4 dwords.
+    template <int FMT>
+    static constexpr int qregs() { return FMT == FMT_E2M1 ? NH : FMT == FMT_E4M3 ? 2 * NH : NKK; }
 };
 
-template <int A, int B>
-constexpr int cmax() { return A > B ? A : B; }
-
 // ---------------------------------------------------------------------------------------------
-// Query operands of one phase: codes (or bf16) of the wave's QB * 32 rows in MFMA B-operand layout.
+// Query operand of a wave: its 32 rows in MFMA B-operand layout for format FMT, held in `qr`
+// (scaled MFMA formats also fill `qscale`: byte h = E8M0 of block 2h + g of the lane's row).
 // ---------------------------------------------------------------------------------------------
-template <typename C, int FMT>
-struct QOperand {
-    // scaled MFMA: [qb][h] 8 dwords (E2M1 uses the first 4); bf16 MFMA: [qb][kk] 4 dwords.
-    static constexpr bool BF = uses_bf16_mfma(FMT);
-    v8i mx[BF ? 1 : C::QB][BF ? 1 : C::NH];
-    v4i bf[BF ? C::QB : 1][BF ? C::NKK : 1];
-    int scale[C::QB];    // byte h = E8M0 of block 2h + g of the lane's row
-};
-
-template <typename C, int FMT>
-DMA_DEV void load_q(QOperand<C, FMT>& qo, const uint16_t* __restrict__ qhead, int row0, int j, int g, float c)
+template <typename C, int FMT, int QR>
+DMA_DEV void load_q(v4i (&qr)[QR], int& qscale, const uint16_t* __restrict__ qhead, int row0, int j, int g, float c)
 {
+    const uint16_t* rowp = qhead + (int64_t)(row0 + j) * C::D;
+    qscale = 0;
+    if constexpr (FMT == FMT_BF16) {
 #pragma unroll
-    for (int qb = 0; qb < C::QB; ++qb) {
-        const uint16_t* rowp = qhead + (int64_t)(row0 + qb * 32 + j) * C::D;
-        if constexpr (FMT == FMT_BF16) {
+        for (int kk = 0; kk < C::NKK; ++kk) qr[kk] = *(const v4i*)(rowp + 16 * kk + 8 * g);
+    } else if constexpr (FMT == FMT_E4M3_X) {
+        // The lane holds elements 16kk + 8g + [0, 8): MX block b = kk / 2 is spread over both half-waves.
 #pragma unroll
-            for (int kk = 0; kk < C::NKK; ++kk) qo.bf[qb][kk] = *(const v4i*)(rowp + 16 * kk + 8 * g);
-            qo.scale[qb] = 0;
-        } else if constexpr (FMT == FMT_E4M3_X) {
-            // The lane holds elements 16kk + 8g + [0, 8): MX block b = kk / 2 is spread over both half-waves.
-            float x[C::NKK][8];
+        for (int b = 0; b < C::NKK / 2; ++b) {
+            float x0[8], x1[8];
+            unpack8<true>(*(const v4i*)(rowp + 32 * b + 8 * g), c, x0);
+            unpack8<true>(*(const v4i*)(rowp + 32 * b + 16 + 8 * g), c, x1);
+            const float amax = cross_half_max(fmaxf(amax8(x0), amax8(x1)));
+            const int code = e8m0_code<FMT_E4M3>(amax);
+            qr[2 * b] = quant_dequant8_e4m3(x0, code);
+            qr[2 * b + 1] = quant_dequant8_e4m3(x1, code);
+        }
+    } else {
+        static_for<C::NH>([&](auto H) {
+            constexpr int h = H;
+            const v4i* src = (const v4i*)(rowp + 32 * (2 * h + g));     // the lane's whole MX block
+            float x[4][8];
+            float amax = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < C::NKK; ++kk) unpack8<true>(*(const v4i*)(rowp + 16 * kk + 8 * g), c, x[kk]);
-#pragma unroll
-            for (int b = 0; b < C::NKK / 2; ++b) {
-                const float amax = cross_half_max(fmaxf(amax8(x[2 * b]), amax8(x[2 * b + 1])));
-                const int code = e8m0_code<FMT_E4M3>(amax);
-                qo.bf[qb][2 * b] = quant_dequant8_e4m3(x[2 * b], code);
-                qo.bf[qb][2 * b + 1] = quant_dequant8_e4m3(x[2 * b + 1], code);
+            for (int t = 0; t < 4; ++t) {
+                unpack8<true>(src[t], c, x[t]);
+                amax = fmaxf(amax, amax8(x[t]));
             }
-            qo.scale[qb] = 0;
-        } else {
-            int sc = 0;
-            static_for<C::NH>([&](auto H) {
-                constexpr int h = H;
-                const v4i* src = (const v4i*)(rowp + 32 * (2 * h + g));     // the lane's MX block
-                float x[4][8];
-                float amax = 0.f;
+            const int code = e8m0_code<FMT>(amax);
+            qscale |= code << (8 * h);
+            if constexpr (FMT == FMT_E2M1) {
+                v4i r;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) r[t] = encode8_e2m1(x[t], code);
+                qr[h] = r;
+            } else {
+                int r[8];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    unpack8<true>(src[t], c, x[t]);
-                    amax = fmaxf(amax, amax8(x[t]));
+                    const v2i e = encode8_e4m3(x[t], code);
+                    r[2 * t] = e[0];
+                    r[2 * t + 1] = e[1];
                 }
-                const int code = e8m0_code<FMT>(amax);
-                sc |= code << (8 * h);
-                v8i r = {0, 0, 0, 0, 0, 0, 0, 0};
-                if constexpr (FMT == FMT_E2M1) {
+                // E4M3 operand layout: VGPR 0-3 = first half of block 2h (lower lanes) / second half of
+                // block 2h (upper lanes); VGPR 4-7 the same for block 2h+1.  Each lane encoded one whole
+                // block, so the lower lanes' VGPR 4-7 trade places with the upper lanes' VGPR 0-3.
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) r[t] = encode8_e2m1(x[t], code);
-                } else {
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        v2i e = encode8_e4m3(x[t], code);
-                        r[2 * t] = e[0];
-                        r[2 * t + 1] = e[1];
-                    }
-                    // E4M3 operand layout: VGPR 0-3 = first half of block 2h (lower lanes) / second half of
-                    // block 2h (upper lanes); VGPR 4-7 the same for block 2h+1.  Each lane encoded one whole
-                    // block, so the lower lanes' VGPR 4-7 trade places with the upper lanes' VGPR 0-3.
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        int lo = r[t], hi = r[4 + t];
-                        swap_halves(lo, hi);
-                        r[t] = lo;
-                        r[4 + t] = hi;
-                    }
-                }
-                qo.mx[qb][h] = r;
-            });
-            qo.scale[qb] = sc;
-        }
+                for (int t = 0; t < 4; ++t) swap_halves(r[t], r[4 + t]);
+                qr[2 * h] = v4i{r[0], r[1], r[2], r[3]};
+                qr[2 * h + 1] = v4i{r[4], r[5], r[6], r[7]};
+            }
+        });
     }
 }
 
@@ -144,20 +143,27 @@ DMA_DEV void stage_k(const v4i (&reg)[C::CPT], uint8_t* ldsK, uint8_t* ldsKs, in
         const int key = ch / C::CPR, dc = ch % C::CPR;
         if constexpr (FMT == FMT_BF16) {
             *(v4i*)(ldsK + key * C::KSB + dc * 16) = reg[r];
+        } else if constexpr (FMT == FMT_E2M1) {
+            // keys are not pre-scaled: block maximum and converts work on the packed bf16 directly
+            const int code = max((int)(quad_max_u32(amax8_bf16_bits(reg[r])) >> 7) - 2, 0);
+            *(int*)(ldsK + key * C::KS4 + dc * 4) = encode8_e2m1_bf16(reg[r], code);
+            if ((dc & 3) == 0) {
+                const int b = dc >> 2;                              // MX block index along D
+                ldsKs[key * 8 + 4 * (b & 1) + (b >> 1)] = (uint8_t)code;
+            }
         } else {
             float x[8];
             unpack8<false>(reg[r], 1.f, x);
             const float amax = quad_max(amax8(x));
-            const int code = e8m0_code<FMT>(amax);
+            const int code = e8m0_code<FMT_E4M3>(amax);
             if constexpr (FMT == FMT_E4M3_X) {
                 *(v4i*)(ldsK + key * C::KSB + dc * 16) = quant_dequant8_e4m3(x, code);
-                continue;
-            }
-            if constexpr (FMT == FMT_E2M1) *(int*)(ldsK + key * C::KS4 + dc * 4) = encode8_e2m1(x, code);
-            if constexpr (FMT == FMT_E4M3) *(v2i*)(ldsK + key * C::KS8 + dc * 8) = encode8_e4m3(x, code);
-            if ((dc & 3) == 0) {
-                const int b = dc >> 2;                              // MX block index along D
-                ldsKs[key * 8 + 4 * (b & 1) + (b >> 1)] = (uint8_t)code;
+            } else {
+                *(v2i*)(ldsK + key * C::KS8 + dc * 8) = encode8_e4m3(x, code);
+                if ((dc & 3) == 0) {
+                    const int b = dc >> 2;
+                    ldsKs[key * 8 + 4 * (b & 1) + (b >> 1)] = (uint8_t)code;
+                }
             }
         }
     }
@@ -175,7 +181,7 @@ DMA_DEV void stage_v(const v4i (&reg)[C::CPT], uint8_t* ldsV, int tid)
 }
 
 // ---------------------------------------------------------------------------------------------
-// One key tile: scores, mask, online softmax, P V
+// One key tile for one wave: scores, mask, online softmax, P V
 // ---------------------------------------------------------------------------------------------
 template <int FMT, int H>
 DMA_DEV v16f mfma_mx(const v8i& a, const v8i& b, const v16f& c, int sa, int sb)
@@ -184,195 +190,201 @@ DMA_DEV v16f mfma_mx(const v8i& a, const v8i& b, const v16f& c, int sa, int sb)
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, code, code, H, sa, H, sb);
 }
 
-template <typename C, int FMT>
-DMA_DEV void compute_tile(const QOperand<C, FMT>& qo, const uint8_t* ldsK, const uint8_t* ldsKs,
-                          const uint8_t* ldsV, bool diagonal, int wave, int lane, float c,
-                          float (&m)[C::QB], float (&l)[C::QB], v16f (&o)[C::QB][C::NDB])
+DMA_DEV v8i widen(const v4i& lo) { return v8i{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0}; }
+DMA_DEV v8i widen(const v4i& lo, const v4i& hi) { return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]}; }
+
+// V^T operands of one group of PV MFMAs: the NDB d-blocks of one 16-key chunk (two transpose reads each).
+template <typename C>
+DMA_DEV void read_vt(v8s (&a)[C::NDB], const uint8_t* vk)
+{
+    typedef __attribute__((address_space(3))) v4s lds_v4s;
+#pragma unroll
+    for (int db = 0; db < C::NDB; ++db) {
+        const v4s a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s*)(vk + 64 * db));
+        const v4s a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s*)(vk + 8 * C::VS + 64 * db));
+        a[db] = v8s{a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+    }
+}
+
+// MAYBE_DIAG = false compiles the mask away (tiles strictly below the diagonal).
+template <typename C, int FMT, bool MAYBE_DIAG, int QR>
+DMA_DEV void compute_tile(const v4i (&qr)[QR], int qscale, const uint8_t* ldsK, const uint8_t* ldsKs,
+                          const uint8_t* ldsV, bool diagonal, int qrow_in_tile, int lane, float c,
+                          float& m, float& l, v16f (&o)[C::NDB])
 {
     const int j = lane & 31, g = lane >> 5;
-    v16f s[C::QB][C::NKB];
+    v16f s[C::NKB];
+#pragma unroll
+    for (int kb = 0; kb < C::NKB; ++kb) s[kb] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-    // ---- S^T = K . Q^T
+    // ---- S^T = K . Q^T.  Operands are fetched from LDS ahead of the MFMAs that use them.
+    if constexpr (FMT == FMT_E2M1) {
+        // every operand of the tile first (NKB * NH 16-byte reads + NKB scale dwords), then the MFMAs, h-major so
+        // that two MFMAs into the same accumulator are NKB instructions apart
+        v4i a[C::NKB][C::NH];
+        int ksc[C::NKB];
 #pragma unroll
-    for (int kb = 0; kb < C::NKB; ++kb) {
+        for (int kb = 0; kb < C::NKB; ++kb) {
+            const int key = kb * 32 + j;
+            ksc[kb] = *(const int*)(ldsKs + key * 8 + 4 * g);
 #pragma unroll
-        for (int qb = 0; qb < C::QB; ++qb) s[qb][kb] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-        const int key = kb * 32 + j;
-        if constexpr (uses_bf16_mfma(FMT)) {
+            for (int h = 0; h < C::NH; ++h) a[kb][h] = *(const v4i*)(ldsK + key * C::KS4 + 16 * (2 * h + g));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<C::NH>([&](auto H) {
+            constexpr int h = H;
+            const v8i b = widen(qr[h]);
 #pragma unroll
-            for (int kk = 0; kk < C::NKK; ++kk) {
-                const v4i a = *(const v4i*)(ldsK + key * C::KSB + 32 * kk + 16 * g);
+            for (int kb = 0; kb < C::NKB; ++kb) s[kb] = mfma_mx<FMT, h>(widen(a[kb][h]), b, s[kb], ksc[kb], qscale);
+        });
+    } else if constexpr (FMT == FMT_E4M3) {
 #pragma unroll
-                for (int qb = 0; qb < C::QB; ++qb)
-                    s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a),
-                                                                        __builtin_bit_cast(v8bf, qo.bf[qb][kk]),
-                                                                        s[qb][kb], 0, 0, 0);
-            }
-            if constexpr (FMT == FMT_BF16) {       // unquantized operands: the softmax factor multiplies the score
-#pragma unroll
-                for (int qb = 0; qb < C::QB; ++qb) s[qb][kb] *= c;
-            }
-        } else {
+        for (int kb = 0; kb < C::NKB; ++kb) {
+            const int key = kb * 32 + j;
             const int ksc = *(const int*)(ldsKs + key * 8 + 4 * g);
             static_for<C::NH>([&](auto H) {
                 constexpr int h = H;
-                v8i a = {0, 0, 0, 0, 0, 0, 0, 0};
-                if constexpr (FMT == FMT_E2M1) {
-                    const v4i lo = *(const v4i*)(ldsK + key * C::KS4 + 16 * (2 * h + g));
-                    a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
-                } else {
-                    const v4i lo = *(const v4i*)(ldsK + key * C::KS8 + 64 * h + 16 * g);
-                    const v4i hi = *(const v4i*)(ldsK + key * C::KS8 + 64 * h + 32 + 16 * g);
-                    a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
-                    a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
-                }
-#pragma unroll
-                for (int qb = 0; qb < C::QB; ++qb)
-                    s[qb][kb] = mfma_mx<FMT, h>(a, qo.mx[qb][h], s[qb][kb], ksc, qo.scale[qb]);
+                const v4i lo = *(const v4i*)(ldsK + key * C::KS8 + 64 * h + 16 * g);
+                const v4i hi = *(const v4i*)(ldsK + key * C::KS8 + 64 * h + 32 + 16 * g);
+                s[kb] = mfma_mx<FMT, h>(widen(lo, hi), widen(qr[2 * h], qr[2 * h + 1]), s[kb], ksc, qscale);
             });
+        }
+    } else {
+        // bf16 MFMA (unquantized, or MXFP8 decoded exactly): NKK k=16 steps per 32-key block, next block's operands
+        // in flight while the current block multiplies
+        v4i a[2][C::NKK];
+#pragma unroll
+        for (int kk = 0; kk < C::NKK; ++kk) a[0][kk] = *(const v4i*)(ldsK + j * C::KSB + 32 * kk + 16 * g);
+#pragma unroll
+        for (int kb = 0; kb < C::NKB; ++kb) {
+            if (kb + 1 < C::NKB) {
+#pragma unroll
+                for (int kk = 0; kk < C::NKK; ++kk)
+                    a[(kb + 1) & 1][kk] = *(const v4i*)(ldsK + ((kb + 1) * 32 + j) * C::KSB + 32 * kk + 16 * g);
+            }
+#pragma unroll
+            for (int kk = 0; kk < C::NKK; ++kk)
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a[kb & 1][kk]),
+                                                                __builtin_bit_cast(v8bf, qr[kk]), s[kb], 0, 0, 0);
+            if constexpr (FMT == FMT_BF16) s[kb] *= c;      // unquantized operands: the softmax factor multiplies the score
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
     // ---- causal mask on the tile that straddles the diagonal: key > query -> -inf
-    if (diagonal) {
-#pragma unroll
-        for (int qb = 0; qb < C::QB; ++qb) {
-            const int qi = (wave * C::QB + qb) * 32 + j;
+    if constexpr (MAYBE_DIAG) {
+        if (diagonal) {
+            const int qi = qrow_in_tile + j;
 #pragma unroll
             for (int kb = 0; kb < C::NKB; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int kj = kb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (kj > qi) s[qb][kb][r] = -INFINITY;
+                    if (kj > qi) s[kb][r] = -INFINITY;
                 }
         }
     }
 
-    // ---- online softmax in base 2
+    // ---- online softmax in base 2: running maximum and rescale factor
+    float mx = -INFINITY;
 #pragma unroll
-    for (int qb = 0; qb < C::QB; ++qb) {
-        float mx = -INFINITY;
+    for (int kb = 0; kb < C::NKB; ++kb)
 #pragma unroll
-        for (int kb = 0; kb < C::NKB; ++kb)
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
+    mx = cross_half_max(mx);
+    const float mnew = fmaxf(m, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+    m = mnew;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {      // skipped when no row of the wave moved its maximum
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[qb][kb][r]);
-        mx = cross_half_max(mx);
-        const float mnew = fmaxf(m[qb], mx);
-        const float alpha = __builtin_amdgcn_exp2f(m[qb] - mnew);
-        m[qb] = mnew;
-        float psum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < C::NKB; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(s[qb][kb][r] - mnew);
-                psum += p;
-                s[qb][kb][r] = p;
-            }
-        l[qb] = l[qb] * alpha + psum;
-#pragma unroll
-        for (int db = 0; db < C::NDB; ++db) o[qb][db] *= alpha;
+        for (int db = 0; db < C::NDB; ++db) o[db] *= alpha;
     }
 
-    // ---- O^T += V^T . P^T
+    // ---- P = 2^(S - m), row sums, O^T += V^T . P^T, in groups of 16 keys: while the MFMAs of one group run, the
+    // V^T operands of the next group are in flight from LDS and its probabilities are exponentiated
     const int l16 = lane & 15, q16 = lane >> 4;
     // transpose read: lane l16 of a 16-lane group points at row (l16 / 4) of a 4-key x 16-column patch
     const uint8_t* vlane = ldsV + (4 * g + (l16 >> 2)) * C::VS + 2 * (16 * (q16 & 1) + 4 * (l16 & 3));
+    float psum[2] = {0.f, 0.f};
+    auto exp_group = [&](int grp) {                 // keys 16 grp .. 16 grp + 15 of the tile -> P^T operand
+        v8bf pb;
 #pragma unroll
-    for (int kb = 0; kb < C::NKB; ++kb) {
-#pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
-            v8bf pb[C::QB];
-#pragma unroll
-            for (int qb = 0; qb < C::QB; ++qb) {
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    v2f f = {s[qb][kb][8 * cc + 2 * t], s[qb][kb][8 * cc + 2 * t + 1]};
-                    v2bf h2 = __builtin_convertvector(f, v2bf);
-                    pb[qb][2 * t] = h2[0];
-                    pb[qb][2 * t + 1] = h2[1];
-                }
-            }
-            const uint8_t* vk = vlane + (kb * 32 + cc * 16) * C::VS;
-#pragma unroll
-            for (int db = 0; db < C::NDB; ++db) {
-                typedef __attribute__((address_space(3))) v4s lds_v4s;
-                const v4s a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s*)(vk + 64 * db));
-                const v4s a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s*)(vk + 8 * C::VS + 64 * db));
-                v8s a;
-                a[0] = a0[0]; a[1] = a0[1]; a[2] = a0[2]; a[3] = a0[3];
-                a[4] = a1[0]; a[5] = a1[1]; a[6] = a1[2]; a[7] = a1[3];
-#pragma unroll
-                for (int qb = 0; qb < C::QB; ++qb)
-                    o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), pb[qb],
-                                                                        o[qb][db], 0, 0, 0);
-            }
+        for (int t = 0; t < 4; ++t) {
+            const float p0 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t] - mnew);
+            const float p1 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t + 1] - mnew);
+            psum[0] += p0;
+            psum[1] += p1;
+            const v2bf h2 = __builtin_convertvector(v2f{p0, p1}, v2bf);
+            pb[2 * t] = h2[0];
+            pb[2 * t + 1] = h2[1];
         }
+        return pb;
+    };
+    constexpr int NG = 2 * C::NKB;
+    v8s va[2][C::NDB];
+    read_vt<C>(va[0], vlane);
+    v8bf pb_cur = exp_group(0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int grp = 0; grp < NG; ++grp) {
+        v8bf pb_next = pb_cur;
+        if (grp + 1 < NG) {
+            read_vt<C>(va[(grp + 1) & 1], vlane + (grp + 1) * 16 * C::VS);
+            pb_next = exp_group(grp + 1);
+        }
+#pragma unroll
+        for (int db = 0; db < C::NDB; ++db)
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, va[grp & 1][db]), pb_cur, o[db], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        pb_cur = pb_next;
     }
+    l = l * alpha + (psum[0] + psum[1]);
 }
 
 // ---------------------------------------------------------------------------------------------
-// One phase of Alg. 1: key tiles [jt0, jt1) in format FMT
+// The kernel
 // ---------------------------------------------------------------------------------------------
-template <typename C, int FMT>
-DMA_DEV void run_phase(const uint16_t* __restrict__ qhead, const uint16_t* __restrict__ khead,
-                       const uint16_t* __restrict__ vhead, int it, int jt0, int jt1, float c,
-                       uint8_t* ldsK, uint8_t* ldsKs, uint8_t* ldsV, int tid, int wave, int lane,
-                       float (&m)[C::QB], float (&l)[C::QB], v16f (&o)[C::QB][C::NDB])
-{
-    if (jt0 >= jt1) return;
-    QOperand<C, FMT> qo;
-    load_q<C, FMT>(qo, qhead, it * C::BT + wave * C::QB * 32, lane & 31, lane >> 5, c);
-
-    v4i kreg[C::CPT], vreg[C::CPT];
-    load_tile<C>(kreg, khead + (int64_t)jt0 * C::BT * C::D, tid);
-    load_tile<C>(vreg, vhead + (int64_t)jt0 * C::BT * C::D, tid);
-    for (int jt = jt0; jt < jt1; ++jt) {
-        stage_k<C, FMT>(kreg, ldsK, ldsKs, tid);
-        stage_v<C>(vreg, ldsV, tid);
-        __syncthreads();
-        if (jt + 1 < jt1) {                       // next tile's global loads fly during the compute
-            load_tile<C>(kreg, khead + (int64_t)(jt + 1) * C::BT * C::D, tid);
-            load_tile<C>(vreg, vhead + (int64_t)(jt + 1) * C::BT * C::D, tid);
-        }
-        compute_tile<C, FMT>(qo, ldsK, ldsKs, ldsV, jt == it, wave, lane, c, m, l, o);
-        __syncthreads();
-    }
-}
-
-template <int D, int BT, int NW, int QB, int LO, int HI>
-__global__ void __launch_bounds__(NW * 64)
+template <int D, int BT, int TPW, int LO, int HI>
+__global__ void __launch_bounds__((BT / 32) * TPW * 64, 2)
 dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     const uint16_t* __restrict__ v, float* __restrict__ out,
                     int B, int Hq, int Hkv, int S, int band, float c)
 {
-    using C = Cfg<D, BT, NW, QB>;
-    constexpr int KBYTES = BT * cmax<C::template kstride<LO>(), C::template kstride<HI>()>();
-    __shared__ __attribute__((aligned(16))) uint8_t ldsK[KBYTES];
-    __shared__ __attribute__((aligned(16))) uint8_t ldsKs[BT * 8];
-    __shared__ __attribute__((aligned(16))) uint8_t ldsV[BT * C::VS];
+    using C = Cfg<D, BT, TPW>;
+    constexpr bool TWO = (LO != HI);
+    constexpr int KLO = C::template kbytes<LO>();
+    constexpr int KHI = TWO ? C::template kbytes<HI>() : 16;
+    constexpr int QRLO = C::template qregs<LO>();
+    constexpr int QRHI = TWO ? C::template qregs<HI>() : 1;
+    // LDS: V and the low-format K double-buffered for the pipelined main loop; one buffer for the high format.
+    __shared__ __attribute__((aligned(16))) uint8_t ldsV[2][C::VBYTES];
+    __shared__ __attribute__((aligned(16))) uint8_t ldsKlo[2][KLO];
+    __shared__ __attribute__((aligned(16))) uint8_t ldsKslo[2][C::KSC];
+    __shared__ __attribute__((aligned(16))) uint8_t ldsKhi[KHI];
+    __shared__ __attribute__((aligned(16))) uint8_t ldsKshi[TWO ? C::KSC : 16];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
 
-    // ---- which (batch, query head, query tile): heaviest tiles first; when the (batch, kv head) units
-    // divide over the 8 XCDs, every unit stays on one XCD so its K/V stream is shared in that L2.
-    const int N = S / BT;
+    // ---- which (batch, query head, group of TPW query tiles): heaviest first; when the (batch, kv head)
+    // units divide over the 8 XCDs, every unit stays on one XCD so its K/V stream is shared in that L2.
+    const int N = S / BT;                // logical tiles per sequence (host guarantees N % TPW == 0)
+    const int NG = N / TPW;              // tile groups
     const int group = Hq / Hkv;
     const int units = B * Hkv;
     const int bid = blockIdx.x;
-    int b, hq, it;
+    int b, hq, grp;
     if (units % 8 == 0) {
         const int xcd = bid & 7, idx = bid >> 3;
-        const int per_unit = group * N;
+        const int per_unit = group * NG;
         const int unit = (idx / per_unit) * 8 + xcd, rem = idx % per_unit;
         b = unit / Hkv;
-        hq = (unit % Hkv) * group + rem / N;
-        it = N - 1 - rem % N;
+        hq = (unit % Hkv) * group + rem / NG;
+        grp = NG - 1 - rem % NG;
     } else {
         const int bh = bid % (B * Hq);
-        it = N - 1 - bid / (B * Hq);
+        grp = NG - 1 - bid / (B * Hq);
         b = bh / Hq;
         hq = bh % Hq;
     }
@@ -382,76 +394,138 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     const uint16_t* vhead = v + ((int64_t)b * Hkv + hkv) * S * D;
     float* ohead = out + ((int64_t)b * Hq + hq) * S * D;
 
-    float m[QB], l[QB];
-    v16f o[QB][C::NDB];
+    // ---- this wave's logical tile and its phase boundary (Alg. 1: low tiles [0, lo_end), high [lo_end, it])
+    const int it0 = grp * TPW, last = it0 + TPW - 1;
+    const int it = it0 + wave / C::WPT;
+    const int qrow_in_tile = (wave % C::WPT) * 32;
+    const int qrow = it * BT + qrow_in_tile;
+    const int lo_end = (TWO && band > 0) ? max(0, it + 1 - band) : it + 1;
+    // Key tiles [0, n_main) are Phase 1 and strictly below the diagonal for EVERY wave of the workgroup: the
+    // pipelined main loop.  The remaining band + TPW - 1 (or TPW) tiles run in the tail loop, wave by wave.
+    const int n_main = (TWO && band > 0) ? max(0, it0 + 1 - band) : it0;
+
+    float m = -INFINITY, l = 0.f;         // Alg. 1 starts l at 1; the first rescale factor 2^(-inf) erases it
+    v16f o[C::NDB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        m[qb] = -INFINITY;
-        l[qb] = 0.f;          // Alg. 1 starts l at 1; the first rescale factor 2^(-inf) erases it
-#pragma unroll
-        for (int db = 0; db < C::NDB; ++db) o[qb][db] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    for (int db = 0; db < C::NDB; ++db) o[db] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+    v4i qr_lo[QRLO];
+    int qs_lo = 0;
+    if (lo_end > 0) load_q<C, LO>(qr_lo, qs_lo, qhead, qrow, lane & 31, lane >> 5, c);
+
+    // ---- main loop: tile jt computed out of buffer jt & 1 while tile jt+1 (already in registers) is quantized
+    // into the other buffer and the loads of tile jt+2 start; one barrier per tile
+    if (n_main > 0) {
+        v4i kreg[C::CPT], vreg[C::CPT];
+        load_tile<C>(kreg, khead, tid);
+        load_tile<C>(vreg, vhead, tid);
+        stage_k<C, LO>(kreg, ldsKlo[0], ldsKslo[0], tid);
+        stage_v<C>(vreg, ldsV[0], tid);
+        if (n_main > 1) {
+            load_tile<C>(kreg, khead + (int64_t)BT * D, tid);
+            load_tile<C>(vreg, vhead + (int64_t)BT * D, tid);
+        }
+        __syncthreads();
+        for (int jt = 0; jt < n_main; ++jt) {
+            const int buf = jt & 1;
+            compute_tile<C, LO, false>(qr_lo, qs_lo, ldsKlo[buf], ldsKslo[buf], ldsV[buf], false, qrow_in_tile, lane, c, m, l, o);
+            if (jt + 1 < n_main) {
+                stage_k<C, LO>(kreg, ldsKlo[buf ^ 1], ldsKslo[buf ^ 1], tid);
+                stage_v<C>(vreg, ldsV[buf ^ 1], tid);
+                if (jt + 2 < n_main) {
+                    load_tile<C>(kreg, khead + (int64_t)(jt + 2) * BT * D, tid);
+                    load_tile<C>(vreg, vhead + (int64_t)(jt + 2) * BT * D, tid);
+                }
+            }
+            __syncthreads();
+        }
     }
 
-    // ---- Phase 1 (low format) then Phase 2 (high format, the last `band` key tiles)
-    const int lo_end = max(0, it + 1 - band);
-    if constexpr (LO == HI) {
-        run_phase<C, LO>(qhead, khead, vhead, it, 0, it + 1, c, ldsK, ldsKs, ldsV, tid, wave, lane, m, l, o);
-    } else {
-        run_phase<C, LO>(qhead, khead, vhead, it, 0, lo_end, c, ldsK, ldsKs, ldsV, tid, wave, lane, m, l, o);
-        run_phase<C, HI>(qhead, khead, vhead, it, lo_end, it + 1, c, ldsK, ldsKs, ldsV, tid, wave, lane, m, l, o);
+    // ---- tail: the tiles around the diagonal.  Per wave: skipped (past its diagonal), Phase 1 or Phase 2, masked
+    // on its diagonal tile.  Plain load / quantize / barrier / compute / barrier, buffer 0.
+    {
+        v4i qr_hi[QRHI];
+        int qs_hi = 0;
+        for (int jt = n_main; jt <= last; ++jt) {
+            {
+                v4i kreg[C::CPT], vreg[C::CPT];
+                load_tile<C>(kreg, khead + (int64_t)jt * BT * D, tid);
+                load_tile<C>(vreg, vhead + (int64_t)jt * BT * D, tid);
+                const bool any_lo = !(TWO && band > 0) || jt < max(0, last + 1 - band);   // the group's last tile switches last
+                if (any_lo) stage_k<C, LO>(kreg, ldsKlo[0], ldsKslo[0], tid);
+                if constexpr (TWO) {
+                    if (band > 0) stage_k<C, HI>(kreg, ldsKhi, ldsKshi, tid);                // jt >= n_main: the group's first tile is in Phase 2
+                }
+                stage_v<C>(vreg, ldsV[0], tid);
+            }
+            __syncthreads();
+            if (jt <= it) {
+                if (jt < lo_end) {
+                    compute_tile<C, LO, true>(qr_lo, qs_lo, ldsKlo[0], ldsKslo[0], ldsV[0], jt == it, qrow_in_tile, lane, c, m, l, o);
+                } else if constexpr (TWO) {
+                    if (jt == lo_end) load_q<C, HI>(qr_hi, qs_hi, qhead, qrow, lane & 31, lane >> 5, c);   // Phase 2 starts
+                    compute_tile<C, HI, true>(qr_hi, qs_hi, ldsKhi, ldsKshi, ldsV[0], jt == it, qrow_in_tile, lane, c, m, l, o);
+                }
+            }
+            __syncthreads();
+        }
     }
 
     // ---- O / l
     const int j = lane & 31, g = lane >> 5;
+    const float inv = 1.0f / cross_half_sum(l);
+    float* orow = ohead + (int64_t)(qrow + j) * D;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        const float inv = 1.0f / cross_half_sum(l[qb]);
-        float* orow = ohead + (int64_t)(it * BT + (wave * QB + qb) * 32 + j) * D;
+    for (int db = 0; db < C::NDB; ++db)
 #pragma unroll
-        for (int db = 0; db < C::NDB; ++db)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                v4f val = {o[qb][db][4 * r4] * inv, o[qb][db][4 * r4 + 1] * inv, o[qb][db][4 * r4 + 2] * inv,
-                           o[qb][db][4 * r4 + 3] * inv};
-                *(v4f*)(orow + 32 * db + 8 * r4 + 4 * g) = val;
-            }
-    }
+        for (int r4 = 0; r4 < 4; ++r4) {
+            v4f val = {o[db][4 * r4] * inv, o[db][4 * r4 + 1] * inv, o[db][4 * r4 + 2] * inv, o[db][4 * r4 + 3] * inv};
+            *(v4f*)(orow + 32 * db + 8 * r4 + 4 * g) = val;
+        }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Host side: pick the instance
 // ---------------------------------------------------------------------------------------------
-template <int D, int BT, int NW, int QB, int LO, int HI>
+template <int D, int BT, int TPW, int LO, int HI>
 static int launch_instance(const AttnArgs& a, hipStream_t stream)
 {
+    using C = Cfg<D, BT, TPW>;
     const int N = a.S / BT;
-    const int64_t blocks = (int64_t)a.B * a.Hq * N;
-    if (blocks <= 0 || blocks > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
+    const int64_t blocks = (int64_t)a.B * a.Hq * (N / TPW);
+    if (N % TPW != 0 || blocks <= 0 || blocks > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
     const float c = (float)(1.4426950408889634074 / sqrt((double)D));
-    hipLaunchKernelGGL((dma_attn_fwd_kernel<D, BT, NW, QB, LO, HI>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream,
+    hipLaunchKernelGGL((dma_attn_fwd_kernel<D, BT, TPW, LO, HI>), dim3((unsigned)blocks), dim3(C::T), 0, stream,
                        (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, a.out, a.B, a.Hq, a.Hkv,
                        a.S, a.band, c);
     return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
 }
 
-template <int D, int BT, int NW, int QB>
+template <int D, int BT, int TPW>
 static int launch_formats(const AttnArgs& a, hipStream_t stream)
 {
     const int lo = a.lo_fmt, hi = a.hi_fmt;
     // a.lo_fmt / a.hi_fmt arrive as internal product-path ids (FMT_*).
-    if (lo == FMT_E2M1 && hi == FMT_E4M3_X) return launch_instance<D, BT, NW, QB, FMT_E2M1, FMT_E4M3_X>(a, stream);
-    if (lo == FMT_E2M1 && hi == FMT_E4M3) return launch_instance<D, BT, NW, QB, FMT_E2M1, FMT_E4M3>(a, stream);
-    if (lo == FMT_E2M1 && hi == FMT_E2M1) return launch_instance<D, BT, NW, QB, FMT_E2M1, FMT_E2M1>(a, stream);
-    if (lo == FMT_E4M3_X && hi == FMT_E4M3_X) return launch_instance<D, BT, NW, QB, FMT_E4M3_X, FMT_E4M3_X>(a, stream);
-    if (lo == FMT_E4M3 && hi == FMT_E4M3) return launch_instance<D, BT, NW, QB, FMT_E4M3, FMT_E4M3>(a, stream);
-    if (lo == FMT_BF16 && hi == FMT_BF16) return launch_instance<D, BT, NW, QB, FMT_BF16, FMT_BF16>(a, stream);
+    if (lo == FMT_E2M1 && hi == FMT_E4M3_X) return launch_instance<D, BT, TPW, FMT_E2M1, FMT_E4M3_X>(a, stream);
+    if (lo == FMT_E2M1 && hi == FMT_E4M3) return launch_instance<D, BT, TPW, FMT_E2M1, FMT_E4M3>(a, stream);
+    if (lo == FMT_E2M1 && hi == FMT_E2M1) return launch_instance<D, BT, TPW, FMT_E2M1, FMT_E2M1>(a, stream);
+    if (lo == FMT_E4M3_X && hi == FMT_E4M3_X) return launch_instance<D, BT, TPW, FMT_E4M3_X, FMT_E4M3_X>(a, stream);
+    if (lo == FMT_E4M3 && hi == FMT_E4M3) return launch_instance<D, BT, TPW, FMT_E4M3, FMT_E4M3>(a, stream);
+    if (lo == FMT_BF16 && hi == FMT_BF16) return launch_instance<D, BT, TPW, FMT_BF16, FMT_BF16>(a, stream);
     return DMA_ERR_UNSUPPORTED_;
 }
 
 int launch_attn_fwd(const AttnArgs& a, hipStream_t stream)
 {
-    if (a.D == 128 && a.tile == 128) return launch_formats<128, 128, 4, 1>(a, stream);
-    if (a.D == 64 && a.tile == 64) return launch_formats<64, 64, 2, 1>(a, stream);
+    if (a.D == 128 && a.tile == 128) {
+        // two logical tiles per workgroup (256 query rows share each K/V tile) whenever they pair up
+        if ((a.S / 128) % 2 == 0) return launch_formats<128, 128, 2>(a, stream);
+        return launch_formats<128, 128, 1>(a, stream);
+    }
+    if (a.D == 64 && a.tile == 64) {
+        if ((a.S / 64) % 2 == 0) return launch_formats<64, 64, 2>(a, stream);
+        return launch_formats<64, 64, 1>(a, stream);
+    }
     return DMA_ERR_UNSUPPORTED_;
 }
 

@@ -74,6 +74,25 @@ DMA_DEV float quad_max(float a)
     return fmaxf(a, b);
 }
 
+DMA_DEV unsigned quad_max_u32(unsigned a)
+{
+    unsigned b = (unsigned)__builtin_amdgcn_mov_dpp((int)a, 0xB1, 0xF, 0xF, true);
+    a = max(a, b);
+    b = (unsigned)__builtin_amdgcn_mov_dpp((int)a, 0x4E, 0xF, 0xF, true);
+    return max(a, b);
+}
+
+// Largest magnitude among eight packed bf16, returned as its 15-bit pattern (sign cleared); the
+// patterns of non-negative bf16 order like unsigned integers.  Biased exponent = result >> 7.
+DMA_DEV unsigned amax8_bf16_bits(const v4i& w)
+{
+    typedef unsigned short v2us __attribute__((ext_vector_type(2)));
+    const v2us a0 = __builtin_bit_cast(v2us, w[0] & 0x7fff7fff), a1 = __builtin_bit_cast(v2us, w[1] & 0x7fff7fff);
+    const v2us a2 = __builtin_bit_cast(v2us, w[2] & 0x7fff7fff), a3 = __builtin_bit_cast(v2us, w[3] & 0x7fff7fff);
+    const v2us m = __builtin_elementwise_max(__builtin_elementwise_max(a0, a1), __builtin_elementwise_max(a2, a3));
+    return max((unsigned)m[0], (unsigned)m[1]);
+}
+
 // E8M0 byte of a block with absolute maximum amax >= 0 (Alg. 2 Steps 6-7):
 // clamp(floor(log2 amax) - e_max + 127, 0, 254) == max(biased_exponent(amax) - e_max, 0).
 template <int FMT>
@@ -98,6 +117,22 @@ DMA_DEV int encode8_e2m1(const float (&x)[8], int code)
     r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, x[2], x[3], sc, 1);
     r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, x[4], x[5], sc, 2);
     r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, x[6], x[7], sc, 3);
+    return (int)r;
+}
+
+// The same from eight packed bf16 (no pre-scale): the convert reads the bf16 pairs directly.
+// Each source dword is first pinned into a VGPR of its own: with the source taken straight out of a
+// 128-bit register tuple this compiler emitted the tuple's first register for all four converts.
+DMA_DEV int encode8_e2m1_bf16(const v4i& w, int code)
+{
+    const float sc = cvt_scale_operand(code);
+    int w0 = w[0], w1 = w[1], w2 = w[2], w3 = w[3];
+    asm volatile("" : "+v"(w0), "+v"(w1), "+v"(w2), "+v"(w3));
+    unsigned r = 0;
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(v2bf, w0), sc, 0);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(v2bf, w1), sc, 1);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(v2bf, w2), sc, 2);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(v2bf, w3), sc, 3);
     return (int)r;
 }
 
