@@ -28,6 +28,7 @@ namespace dma {
 template <int A, int B>
 constexpr int cmax() { return A > B ? A : B; }
 
+
 template <int D_, int BT_, int TPW_>
 struct Cfg {
     static constexpr int D = D_, BT = BT_, TPW = TPW_;
@@ -47,9 +48,15 @@ struct Cfg {
     static constexpr int KS4 = D / 2 + 16;       // E2M1 codes
     static constexpr int KS8 = D + 16;           // E4M3 codes
     static constexpr int KSB = 2 * D + 16;       // bf16 keys
-    static constexpr int VS = 2 * D + 64;        // bf16 values (transpose reads)
-    static constexpr int KSC = BT * 8;           // scale bytes of one tile (2 dwords per key)
+    static constexpr int VS = 2 * D;             // bf16 values: dense rows, 16-byte chunks XOR-swizzled (see v_swizzle)
+    static constexpr int KSC = BT * CPR;         // scale bytes of one tile: one per 16-byte chunk (each block's 4 chunks repeat its code)
     static constexpr int VBYTES = BT * VS;
+    static constexpr int VLOADS = VBYTES / 1024; // 1 KiB wave-wide direct-to-LDS loads per tile
+    static constexpr int VLPW = VLOADS / NW;     // ... per wave
+    static_assert(VLOADS % NW == 0, "V tile must split evenly over the waves");
+    // V rows sit densely in LDS (the direct loads write 1 KiB contiguously); so that the transpose reads of four
+    // consecutive keys do not hit the same banks, chunk c of key k is stored at chunk c ^ (4 * v_swizzle(k)).
+    static constexpr int v_swizzle(int key) { return D == 128 ? (key & 3) : ((key >> 1) & 1); }
     template <int FMT>
     static constexpr int kstride() { return FMT == FMT_E2M1 ? KS4 : FMT == FMT_E4M3 ? KS8 : KSB; }
     template <int FMT>
@@ -122,62 +129,80 @@ DMA_DEV void load_q(v4i (&qr)[QR], int& qscale, const uint16_t* __restrict__ qhe
 }
 
 // ---------------------------------------------------------------------------------------------
+// LDS addressing.  All LDS traffic goes through 32-bit byte addresses of the form
+// (one pinned per-lane VGPR) + (compile-time constant), so every access uses the instruction's immediate
+// offset and the loops carry a handful of address registers instead of one per access.
+// ---------------------------------------------------------------------------------------------
+#define DMA_LDS __attribute__((address_space(3)))
+DMA_DEV unsigned pin(unsigned x) { asm volatile("" : "+v"(x)); return x; }
+// Lane / thread index made opaque at the point of use: the address arithmetic that follows is then redone where
+// it is needed (a few integer ops) instead of being hoisted out of the tile loops into long-lived registers.
+DMA_DEV int fresh(int x) { asm volatile("" : "+v"(x)); return x; }
+template <typename T>
+DMA_DEV T lds_read(unsigned addr) { return *(const DMA_LDS T*)(uintptr_t)addr; }
+template <typename T>
+DMA_DEV void lds_write(unsigned addr, T v) { *(DMA_LDS T*)(uintptr_t)addr = v; }
+DMA_DEV v4s lds_read_tr16(unsigned addr) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((DMA_LDS v4s*)(uintptr_t)addr); }
+
+// ---------------------------------------------------------------------------------------------
 // Staging of one key/value tile
 // ---------------------------------------------------------------------------------------------
+// Chunk r of thread tid is 16-byte chunk r * T + tid of the dense tile: key r * (T / CPR) + tid / CPR.
 template <typename C>
-DMA_DEV void load_tile(v4i (&reg)[C::CPT], const uint16_t* __restrict__ base, int tid)
+DMA_DEV void load_tile(v4i (&reg)[C::CPT], const uint16_t* __restrict__ tile, int tid)
 {
+    const uint8_t* base = (const uint8_t*)tile;              // uniform
+    const unsigned lane_off = (unsigned)fresh(tid) * 16u;
 #pragma unroll
-    for (int r = 0; r < C::CPT; ++r) {
-        const int ch = r * C::T + tid;
-        reg[r] = *(const v4i*)(base + (int64_t)ch * 8);          // rows are dense: chunk ch starts at ch * 8
-    }
+    for (int r = 0; r < C::CPT; ++r) reg[r] = *(const v4i*)(base + (size_t)r * C::T * 16 + lane_off);
 }
 
+// K tile from registers into LDS in format FMT.  kdst / ksdst: LDS addresses of the codes and of the scale bytes.
 template <typename C, int FMT>
-DMA_DEV void stage_k(const v4i (&reg)[C::CPT], uint8_t* ldsK, uint8_t* ldsKs, int tid)
+DMA_DEV void stage_k(const v4i (&reg)[C::CPT], unsigned kdst, unsigned ksdst, int tid)
 {
+    constexpr int KPR = C::T / C::CPR;                       // keys per chunk round
+    constexpr int STRIDE = C::template kstride<FMT>();
+    constexpr int CB = (FMT == FMT_E2M1) ? 4 : (FMT == FMT_E4M3) ? 8 : 16;     // bytes per chunk in LDS
+    tid = fresh(tid);
+    const int key0 = tid / C::CPR, dc = tid % C::CPR;
+    const unsigned ka = pin(kdst + key0 * STRIDE + dc * CB);
+    const unsigned sa = pin(ksdst + key0 * C::CPR + dc);      // every lane stores its block's scale: no divergence
 #pragma unroll
     for (int r = 0; r < C::CPT; ++r) {
-        const int ch = r * C::T + tid;
-        const int key = ch / C::CPR, dc = ch % C::CPR;
         if constexpr (FMT == FMT_BF16) {
-            *(v4i*)(ldsK + key * C::KSB + dc * 16) = reg[r];
+            lds_write<v4i>(ka + r * KPR * STRIDE, reg[r]);
         } else if constexpr (FMT == FMT_E2M1) {
             // keys are not pre-scaled: block maximum and converts work on the packed bf16 directly
             const int code = max((int)(quad_max_u32(amax8_bf16_bits(reg[r])) >> 7) - 2, 0);
-            *(int*)(ldsK + key * C::KS4 + dc * 4) = encode8_e2m1_bf16(reg[r], code);
-            if ((dc & 3) == 0) {
-                const int b = dc >> 2;                              // MX block index along D
-                ldsKs[key * 8 + 4 * (b & 1) + (b >> 1)] = (uint8_t)code;
-            }
+            lds_write<int>(ka + r * KPR * STRIDE, encode8_e2m1_bf16(reg[r], code));
+            lds_write<uint8_t>(sa + r * KPR * C::CPR, (uint8_t)code);
         } else {
             float x[8];
             unpack8<false>(reg[r], 1.f, x);
             const float amax = quad_max(amax8(x));
             const int code = e8m0_code<FMT_E4M3>(amax);
             if constexpr (FMT == FMT_E4M3_X) {
-                *(v4i*)(ldsK + key * C::KSB + dc * 16) = quant_dequant8_e4m3(x, code);
+                lds_write<v4i>(ka + r * KPR * STRIDE, quant_dequant8_e4m3(x, code));
             } else {
-                *(v2i*)(ldsK + key * C::KS8 + dc * 8) = encode8_e4m3(x, code);
-                if ((dc & 3) == 0) {
-                    const int b = dc >> 2;
-                    ldsKs[key * 8 + 4 * (b & 1) + (b >> 1)] = (uint8_t)code;
-                }
+                lds_write<v2i>(ka + r * KPR * STRIDE, encode8_e4m3(x, code));
+                lds_write<uint8_t>(sa + r * KPR * C::CPR, (uint8_t)code);
             }
         }
     }
 }
 
+// V tile from registers into LDS, 16-byte chunks swizzled (see Cfg::v_swizzle).
 template <typename C>
-DMA_DEV void stage_v(const v4i (&reg)[C::CPT], uint8_t* ldsV, int tid)
+DMA_DEV void stage_v(const v4i (&reg)[C::CPT], unsigned vdst, int tid)
 {
+    constexpr int KPR = C::T / C::CPR;
+    static_assert(KPR % 4 == 0, "swizzle of a row must not depend on the chunk round");
+    tid = fresh(tid);
+    const int key0 = tid / C::CPR, dc = tid % C::CPR;
+    const unsigned va = pin(vdst + key0 * C::VS + ((dc ^ (4 * C::v_swizzle(key0))) * 16));
 #pragma unroll
-    for (int r = 0; r < C::CPT; ++r) {
-        const int ch = r * C::T + tid;
-        const int key = ch / C::CPR, dc = ch % C::CPR;
-        *(v4i*)(ldsV + key * C::VS + dc * 16) = reg[r];
-    }
+    for (int r = 0; r < C::CPT; ++r) lds_write<v4i>(va + r * KPR * C::VS, reg[r]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -187,65 +212,73 @@ template <int FMT, int H>
 DMA_DEV v16f mfma_mx(const v8i& a, const v8i& b, const v16f& c, int sa, int sb)
 {
     constexpr int code = (FMT == FMT_E2M1) ? 4 : 0;
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, code, code, H, sa, H, sb);
+    // sa: the K-side scale sits in byte 0 of its own dword; sb: byte H of the query scale dword
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, code, code, 0, sa, H, sb);
 }
 
 DMA_DEV v8i widen(const v4i& lo) { return v8i{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0}; }
 DMA_DEV v8i widen(const v4i& lo, const v4i& hi) { return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]}; }
 
-// V^T operands of one group of PV MFMAs: the NDB d-blocks of one 16-key chunk (two transpose reads each).
-template <typename C>
-DMA_DEV void read_vt(v8s (&a)[C::NDB], const uint8_t* vk)
-{
-    typedef __attribute__((address_space(3))) v4s lds_v4s;
-#pragma unroll
-    for (int db = 0; db < C::NDB; ++db) {
-        const v4s a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s*)(vk + 64 * db));
-        const v4s a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s*)(vk + 8 * C::VS + 64 * db));
-        a[db] = v8s{a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-    }
-}
-
+// First half of a key tile for one wave (all of its VALU work): scores S^T, causal mask, new running maximum,
+// rescale of l and O by 2^(m_old - m_new), probabilities P = 2^(S - m) summed into l and rounded to bf16.
+// The result is P^T packed as the B operands of the value part: pb[grp] holds keys 16 grp .. 16 grp + 15.
+// ksrc / kssrc: LDS addresses of the tile's K codes / scale bytes.
 // MAYBE_DIAG = false compiles the mask away (tiles strictly below the diagonal).
 template <typename C, int FMT, bool MAYBE_DIAG, int QR>
-DMA_DEV void compute_tile(const v4i (&qr)[QR], int qscale, const uint8_t* ldsK, const uint8_t* ldsKs,
-                          const uint8_t* ldsV, bool diagonal, int qrow_in_tile, int lane, float c,
-                          float& m, float& l, v16f (&o)[C::NDB])
+DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned kssrc,
+                        bool diagonal, int qrow_in_tile, int lane, float c,
+                        float& m, float& l, v16f (&o)[C::NDB], v8bf (&pb)[2 * C::NKB])
 {
+    lane = fresh(lane);
     const int j = lane & 31, g = lane >> 5;
     v16f s[C::NKB];
+    constexpr int STRIDE = C::template kstride<FMT>();
+    const unsigned ka = pin(ksrc + j * STRIDE + 16 * g);          // the lane's key row of 32-key block 0
 #pragma unroll
     for (int kb = 0; kb < C::NKB; ++kb) s[kb] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
     // ---- S^T = K . Q^T.  Operands are fetched from LDS ahead of the MFMAs that use them.
     if constexpr (FMT == FMT_E2M1) {
-        // every operand of the tile first (NKB * NH 16-byte reads + NKB scale dwords), then the MFMAs, h-major so
-        // that two MFMAs into the same accumulator are NKB instructions apart
-        v4i a[C::NKB][C::NH];
-        int ksc[C::NKB];
+        // operands of two 32-key blocks at a time (2 * NH 16-byte reads + 2 scale dwords) ahead of their MFMAs,
+        // which go h-major so that the two MFMAs into one accumulator are not adjacent
+        // scale of MX block 2h + g of the lane's key: byte 0 of the dword at chunk 4 (2h + g) of the key's scale row
+        const unsigned sa = pin(kssrc + j * C::CPR + 4 * g);
+        static_assert(C::NKB % 2 == 0, "key tile must hold an even number of 32-key blocks");
+        v4i a[2][2][C::NH];
+        int ksc[2][2][C::NH];
+        auto fetch = [&](int pair) {
 #pragma unroll
-        for (int kb = 0; kb < C::NKB; ++kb) {
-            const int key = kb * 32 + j;
-            ksc[kb] = *(const int*)(ldsKs + key * 8 + 4 * g);
+            for (int u = 0; u < 2; ++u) {
+                const int kb = 2 * pair + u;
 #pragma unroll
-            for (int h = 0; h < C::NH; ++h) a[kb][h] = *(const v4i*)(ldsK + key * C::KS4 + 16 * (2 * h + g));
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<C::NH>([&](auto H) {
-            constexpr int h = H;
-            const v8i b = widen(qr[h]);
+                for (int h = 0; h < C::NH; ++h) {
+                    ksc[pair & 1][u][h] = lds_read<int>(sa + kb * 32 * C::CPR + 8 * h);
+                    a[pair & 1][u][h] = lds_read<v4i>(ka + kb * 32 * STRIDE + 32 * h);
+                }
+            }
+        };
+        fetch(0);
 #pragma unroll
-            for (int kb = 0; kb < C::NKB; ++kb) s[kb] = mfma_mx<FMT, h>(widen(a[kb][h]), b, s[kb], ksc[kb], qscale);
-        });
-    } else if constexpr (FMT == FMT_E4M3) {
-#pragma unroll
-        for (int kb = 0; kb < C::NKB; ++kb) {
-            const int key = kb * 32 + j;
-            const int ksc = *(const int*)(ldsKs + key * 8 + 4 * g);
+        for (int pair = 0; pair < C::NKB / 2; ++pair) {
+            if (pair + 1 < C::NKB / 2) fetch(pair + 1);
             static_for<C::NH>([&](auto H) {
                 constexpr int h = H;
-                const v4i lo = *(const v4i*)(ldsK + key * C::KS8 + 64 * h + 16 * g);
-                const v4i hi = *(const v4i*)(ldsK + key * C::KS8 + 64 * h + 32 + 16 * g);
+                const v8i b = widen(qr[h]);
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+                    s[2 * pair + u] = mfma_mx<FMT, h>(widen(a[pair & 1][u][h]), b, s[2 * pair + u], ksc[pair & 1][u][h], qscale);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else if constexpr (FMT == FMT_E4M3) {
+        const unsigned sa = pin(kssrc + j * C::CPR + 4 * g);
+#pragma unroll
+        for (int kb = 0; kb < C::NKB; ++kb) {
+            static_for<C::NH>([&](auto H) {
+                constexpr int h = H;
+                const int ksc = lds_read<int>(sa + kb * 32 * C::CPR + 8 * h);
+                const v4i lo = lds_read<v4i>(ka + kb * 32 * STRIDE + 64 * h);
+                const v4i hi = lds_read<v4i>(ka + kb * 32 * STRIDE + 64 * h + 32);
                 s[kb] = mfma_mx<FMT, h>(widen(lo, hi), widen(qr[2 * h], qr[2 * h + 1]), s[kb], ksc, qscale);
             });
         }
@@ -254,13 +287,12 @@ DMA_DEV void compute_tile(const v4i (&qr)[QR], int qscale, const uint8_t* ldsK, 
         // in flight while the current block multiplies
         v4i a[2][C::NKK];
 #pragma unroll
-        for (int kk = 0; kk < C::NKK; ++kk) a[0][kk] = *(const v4i*)(ldsK + j * C::KSB + 32 * kk + 16 * g);
+        for (int kk = 0; kk < C::NKK; ++kk) a[0][kk] = lds_read<v4i>(ka + 32 * kk);
 #pragma unroll
         for (int kb = 0; kb < C::NKB; ++kb) {
             if (kb + 1 < C::NKB) {
 #pragma unroll
-                for (int kk = 0; kk < C::NKK; ++kk)
-                    a[(kb + 1) & 1][kk] = *(const v4i*)(ldsK + ((kb + 1) * 32 + j) * C::KSB + 32 * kk + 16 * g);
+                for (int kk = 0; kk < C::NKK; ++kk) a[(kb + 1) & 1][kk] = lds_read<v4i>(ka + (kb + 1) * 32 * STRIDE + 32 * kk);
             }
 #pragma unroll
             for (int kk = 0; kk < C::NKK; ++kk)
@@ -300,14 +332,10 @@ DMA_DEV void compute_tile(const v4i (&qr)[QR], int qscale, const uint8_t* ldsK, 
         for (int db = 0; db < C::NDB; ++db) o[db] *= alpha;
     }
 
-    // ---- P = 2^(S - m), row sums, O^T += V^T . P^T, in groups of 16 keys: while the MFMAs of one group run, the
-    // V^T operands of the next group are in flight from LDS and its probabilities are exponentiated
-    const int l16 = lane & 15, q16 = lane >> 4;
-    // transpose read: lane l16 of a 16-lane group points at row (l16 / 4) of a 4-key x 16-column patch
-    const uint8_t* vlane = ldsV + (4 * g + (l16 >> 2)) * C::VS + 2 * (16 * (q16 & 1) + 4 * (l16 & 3));
+    // ---- P = 2^(S - m): row sums from the binary32 values, bf16 (round to nearest even) for the P V product
     float psum[2] = {0.f, 0.f};
-    auto exp_group = [&](int grp) {                 // keys 16 grp .. 16 grp + 15 of the tile -> P^T operand
-        v8bf pb;
+#pragma unroll
+    for (int grp = 0; grp < 2 * C::NKB; ++grp) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const float p0 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t] - mnew);
@@ -315,30 +343,50 @@ DMA_DEV void compute_tile(const v4i (&qr)[QR], int qscale, const uint8_t* ldsK, 
             psum[0] += p0;
             psum[1] += p1;
             const v2bf h2 = __builtin_convertvector(v2f{p0, p1}, v2bf);
-            pb[2 * t] = h2[0];
-            pb[2 * t + 1] = h2[1];
+            pb[grp][2 * t] = h2[0];
+            pb[grp][2 * t + 1] = h2[1];
         }
-        return pb;
+    }
+    l = l * alpha + (psum[0] + psum[1]);
+}
+
+// Second half (all matrix work): O^T += V^T . P^T in groups of 16 keys; the V^T operands of the next group are in
+// flight from LDS while the MFMAs of the current group run.  vsrc: LDS address of the V tile.
+template <typename C>
+DMA_DEV void value_part(unsigned vsrc, int lane, v16f (&o)[C::NDB], const v8bf (&pb)[2 * C::NKB])
+{
+    lane = fresh(lane);
+    const int g = lane >> 5, l16 = lane & 15, q16 = lane >> 4;
+    // Transpose read: lane l16 of a 16-lane group points at row (l16 / 4) of a 4-key x 16-column patch; the row's
+    // 16-byte chunks are swizzled by the row index (the same for every patch: patches start at multiples of 4).
+    // va[db]: the lane's address for d-block db in the tile's first patch; other patches are constant offsets.
+    const unsigned row_off = (4 * g + (l16 >> 2)) * C::VS + 8 * (l16 & 1);
+    unsigned va[C::NDB];
+#pragma unroll
+    for (int db = 0; db < C::NDB; ++db)
+        va[db] = pin(vsrc + row_off + 16 * ((4 * db + 2 * (q16 & 1) + ((l16 & 3) >> 1)) ^ (4 * C::v_swizzle(l16 >> 2))));
+
+    auto read_vt = [&](v8s (&a)[C::NDB], int grp) {             // V^T operands of key group grp (16 keys)
+#pragma unroll
+        for (int db = 0; db < C::NDB; ++db) {
+            const v4s a0 = lds_read_tr16(va[db] + grp * 16 * C::VS);
+            const v4s a1 = lds_read_tr16(va[db] + grp * 16 * C::VS + 8 * C::VS);
+            a[db] = v8s{a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+        }
     };
     constexpr int NG = 2 * C::NKB;
-    v8s va[2][C::NDB];
-    read_vt<C>(va[0], vlane);
-    v8bf pb_cur = exp_group(0);
+    v8s vt[3][C::NDB];                       // operands of groups grp, grp+1 and grp+2 in rotation
+    read_vt(vt[0], 0);
+    if (NG > 1) read_vt(vt[1], 1);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int grp = 0; grp < NG; ++grp) {
-        v8bf pb_next = pb_cur;
-        if (grp + 1 < NG) {
-            read_vt<C>(va[(grp + 1) & 1], vlane + (grp + 1) * 16 * C::VS);
-            pb_next = exp_group(grp + 1);
-        }
+        if (grp + 2 < NG) read_vt(vt[(grp + 2) % 3], grp + 2);
 #pragma unroll
         for (int db = 0; db < C::NDB; ++db)
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, va[grp & 1][db]), pb_cur, o[db], 0, 0, 0);
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vt[grp % 3][db]), pb[grp], o[db], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        pb_cur = pb_next;
     }
-    l = l * alpha + (psum[0] + psum[1]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -353,15 +401,24 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     using C = Cfg<D, BT, TPW>;
     constexpr bool TWO = (LO != HI);
     constexpr int KLO = C::template kbytes<LO>();
-    constexpr int KHI = TWO ? C::template kbytes<HI>() : 16;
+    constexpr int KHI = TWO ? C::template kbytes<HI>() : 0;
     constexpr int QRLO = C::template qregs<LO>();
     constexpr int QRHI = TWO ? C::template qregs<HI>() : 1;
-    // LDS: V and the low-format K double-buffered for the pipelined main loop; one buffer for the high format.
-    __shared__ __attribute__((aligned(16))) uint8_t ldsV[2][C::VBYTES];
-    __shared__ __attribute__((aligned(16))) uint8_t ldsKlo[2][KLO];
-    __shared__ __attribute__((aligned(16))) uint8_t ldsKslo[2][C::KSC];
-    __shared__ __attribute__((aligned(16))) uint8_t ldsKhi[KHI];
-    __shared__ __attribute__((aligned(16))) uint8_t ldsKshi[TWO ? C::KSC : 16];
+    // LDS map (bytes): V and the low-format K (+ scale bytes) double-buffered for the pipelined main loop, one buffer
+    // for the high format.
+    constexpr int OFF_V = 0;
+    constexpr int OFF_KLO = OFF_V + 2 * C::VBYTES;
+    constexpr int OFF_KSLO = OFF_KLO + 2 * KLO;
+    constexpr int OFF_KHI = OFF_KSLO + 2 * C::KSC;
+    constexpr int OFF_KSHI = OFF_KHI + KHI;
+    constexpr int LDS_TOTAL = OFF_KSHI + (TWO ? C::KSC : 0);
+    static_assert(LDS_TOTAL <= 160 * 1024, "LDS budget of one CU");
+    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_TOTAL];
+    const unsigned lds0 = (unsigned)(uintptr_t)(DMA_LDS uint8_t*)lds;
+    auto v_at = [&](int buf) { return lds0 + OFF_V + buf * C::VBYTES; };
+    auto klo_at = [&](int buf) { return lds0 + OFF_KLO + buf * KLO; };
+    auto kslo_at = [&](int buf) { return lds0 + OFF_KSLO + buf * C::KSC; };
+    const unsigned khi_at = lds0 + OFF_KHI, kshi_at = lds0 + OFF_KSHI;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -409,34 +466,40 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
 #pragma unroll
     for (int db = 0; db < C::NDB; ++db) o[db] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-    v4i qr_lo[QRLO];
-    int qs_lo = 0;
-    if (lo_end > 0) load_q<C, LO>(qr_lo, qs_lo, qhead, qrow, lane & 31, lane >> 5, c);
 
-    // ---- main loop: tile jt computed out of buffer jt & 1 while tile jt+1 (already in registers) is quantized
-    // into the other buffer and the loads of tile jt+2 start; one barrier per tile
+    // ---- main loop.  Tile t lives in LDS buffer t & 1; one barrier per tile.  At the top of step t the K and V
+    // tiles t+1 (loaded into registers during step t-1) go into the other buffer (K quantized on the way) and the
+    // loads of tiles t+2 start; then the wave computes tile t.  (Direct global-to-LDS loads are not used for V: the
+    // compiler orders every later LDS access behind them with a full vmcnt(0) wait, which exposes the memory latency.)
+    // (On this GPU the MFMA pipe and the floating-point VALU of a SIMD do not run concurrently, so the two waves
+    // of a SIMD are only there to hide LDS and memory latency, not to overlap matrix and softmax work.)
     if (n_main > 0) {
+        v8bf pb[2 * C::NKB];
+        v4i qr_lo[QRLO];
+        int qs_lo = 0;
+        load_q<C, LO>(qr_lo, qs_lo, qhead, qrow, lane & 31, lane >> 5, c);
         v4i kreg[C::CPT], vreg[C::CPT];
         load_tile<C>(kreg, khead, tid);
         load_tile<C>(vreg, vhead, tid);
-        stage_k<C, LO>(kreg, ldsKlo[0], ldsKslo[0], tid);
-        stage_v<C>(vreg, ldsV[0], tid);
+        stage_k<C, LO>(kreg, klo_at(0), kslo_at(0), tid);
+        stage_v<C>(vreg, v_at(0), tid);
         if (n_main > 1) {
             load_tile<C>(kreg, khead + (int64_t)BT * D, tid);
             load_tile<C>(vreg, vhead + (int64_t)BT * D, tid);
         }
         __syncthreads();
-        for (int jt = 0; jt < n_main; ++jt) {
-            const int buf = jt & 1;
-            compute_tile<C, LO, false>(qr_lo, qs_lo, ldsKlo[buf], ldsKslo[buf], ldsV[buf], false, qrow_in_tile, lane, c, m, l, o);
-            if (jt + 1 < n_main) {
-                stage_k<C, LO>(kreg, ldsKlo[buf ^ 1], ldsKslo[buf ^ 1], tid);
-                stage_v<C>(vreg, ldsV[buf ^ 1], tid);
-                if (jt + 2 < n_main) {
-                    load_tile<C>(kreg, khead + (int64_t)(jt + 2) * BT * D, tid);
-                    load_tile<C>(vreg, vhead + (int64_t)(jt + 2) * BT * D, tid);
+        for (int t = 0; t < n_main; ++t) {
+            const int buf = t & 1;
+            if (t + 1 < n_main) {
+                stage_k<C, LO>(kreg, klo_at(buf ^ 1), kslo_at(buf ^ 1), tid);
+                stage_v<C>(vreg, v_at(buf ^ 1), tid);
+                if (t + 2 < n_main) {
+                    load_tile<C>(kreg, khead + (int64_t)(t + 2) * BT * D, tid);
+                    load_tile<C>(vreg, vhead + (int64_t)(t + 2) * BT * D, tid);
                 }
             }
+            score_part<C, LO, false>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), false, qrow_in_tile, lane, c, m, l, o, pb);
+            value_part<C>(v_at(buf), lane, o, pb);
             __syncthreads();
         }
     }
@@ -452,19 +515,27 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                 load_tile<C>(kreg, khead + (int64_t)jt * BT * D, tid);
                 load_tile<C>(vreg, vhead + (int64_t)jt * BT * D, tid);
                 const bool any_lo = !(TWO && band > 0) || jt < max(0, last + 1 - band);   // the group's last tile switches last
-                if (any_lo) stage_k<C, LO>(kreg, ldsKlo[0], ldsKslo[0], tid);
+                if (any_lo) stage_k<C, LO>(kreg, klo_at(0), kslo_at(0), tid);
                 if constexpr (TWO) {
-                    if (band > 0) stage_k<C, HI>(kreg, ldsKhi, ldsKshi, tid);                // jt >= n_main: the group's first tile is in Phase 2
+                    if (band > 0) stage_k<C, HI>(kreg, khi_at, kshi_at, tid);                // jt >= n_main: the group's first tile is in Phase 2
                 }
-                stage_v<C>(vreg, ldsV[0], tid);
+                stage_v<C>(vreg, v_at(0), tid);
             }
             __syncthreads();
             if (jt <= it) {
+                v8bf pb[2 * C::NKB];
                 if (jt < lo_end) {
-                    compute_tile<C, LO, true>(qr_lo, qs_lo, ldsKlo[0], ldsKslo[0], ldsV[0], jt == it, qrow_in_tile, lane, c, m, l, o);
+                    // the low-format query operand is rebuilt here rather than kept alive from the main loop: its
+                    // registers would otherwise be reserved through the register-hungry Phase 2 code as well
+                    v4i qr_t[QRLO];
+                    int qs_t = 0;
+                    load_q<C, LO>(qr_t, qs_t, qhead, qrow, lane & 31, lane >> 5, c);
+                    score_part<C, LO, true>(qr_t, qs_t, klo_at(0), kslo_at(0), jt == it, qrow_in_tile, lane, c, m, l, o, pb);
+                    value_part<C>(v_at(0), lane, o, pb);
                 } else if constexpr (TWO) {
                     if (jt == lo_end) load_q<C, HI>(qr_hi, qs_hi, qhead, qrow, lane & 31, lane >> 5, c);   // Phase 2 starts
-                    compute_tile<C, HI, true>(qr_hi, qs_hi, ldsKhi, ldsKshi, ldsV[0], jt == it, qrow_in_tile, lane, c, m, l, o);
+                    score_part<C, HI, true>(qr_hi, qs_hi, khi_at, kshi_at, jt == it, qrow_in_tile, lane, c, m, l, o, pb);
+                    value_part<C>(v_at(0), lane, o, pb);
                 }
             }
             __syncthreads();
