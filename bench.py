@@ -29,6 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 --pmc runs summarised in profiles/ (FETCH_SIZE + WRITE_SIZE,
 # scaled by the same counters on a copy kernel of known size); None where not measured.
 MEASURED_TRAFFIC_BYTES = {}
+COPY_CALIBRATION_BYTES = 1 << 29      # dma_diag_copy reads and writes this many bytes once per run
 
 
 def tile_counts(w, band):
@@ -140,6 +141,13 @@ def main():
     torch.cuda.synchronize()
     quant_s = ev0.elapsed_time(ev1) * 1e-3 / 10
     quant_bytes = qd.numel() * (2 + 0.5 + 1 + 2 / 32)
+
+    # one plain copy of known size, untimed: the reference dispatch for scaling FETCH_SIZE / WRITE_SIZE under rocprofv3
+    csrc = torch.empty(COPY_CALIBRATION_BYTES, dtype=torch.uint8, device="cuda")
+    cdst = torch.empty_like(csrc)
+    binding.dma_diag_copy(csrc, cdst)
+    torch.cuda.synchronize()
+    del csrc, cdst
 
     rec = {
         "metric": METRIC,

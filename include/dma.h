@@ -115,6 +115,11 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out,
 /* Device scratch the forward needs beyond its inputs and output: always 0. */
 size_t dma_attn_fwd_workspace_bytes(int B, int Hq, int Hkv, int S, int D);
 
+/* Diagnostic, not part of the method: plain device-to-device copy kernel (16 bytes per lane, no reuse) of `bytes`
+ * bytes (a multiple of 16; src, dst 16-byte aligned, device, non-overlapping).  Its exactly known traffic (bytes read +
+ * bytes written) is what the HBM byte counters of a profiler run are scaled by. */
+int dma_diag_copy(const void* src, void* dst, int64_t bytes, void* stream);
+
 /* Static, NUL-terminated description of a return code. */
 const char* dma_error_string(int code);
 

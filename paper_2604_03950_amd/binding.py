@@ -17,7 +17,7 @@ FMT_MXFP8_E4M3 = 1
 FMT_MXFP4_E2M1 = 2
 
 EXPORTS = ("dma_mx_quantize", "dma_mx_quantize_dual", "dma_attn_fwd", "dma_attn_fwd_ex",
-           "dma_attn_fwd_workspace_bytes", "dma_error_string", "dma_version")
+           "dma_attn_fwd_workspace_bytes", "dma_diag_copy", "dma_error_string", "dma_version")
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdma_mi355x.so")
 _lib = None
@@ -56,6 +56,8 @@ def load() -> ctypes.CDLL:
         L.dma_attn_fwd_ex.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(AttnOpts), vp]
         L.dma_attn_fwd_workspace_bytes.restype = ctypes.c_size_t
         L.dma_attn_fwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+        L.dma_diag_copy.restype = ci
+        L.dma_diag_copy.argtypes = [vp, vp, i64, vp]
         L.dma_error_string.restype = ctypes.c_char_p
         L.dma_error_string.argtypes = [ci]
         L.dma_version.restype = ci
@@ -138,6 +140,16 @@ def dma_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, diag_band
     if rc:
         raise DmaError(rc, "dma_attn_fwd")
     return out
+
+
+def dma_diag_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    """Plain copy kernel over the bytes of two equally sized contiguous GPU tensors (counter calibration)."""
+    n = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != n or not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("dma_diag_copy: need two contiguous GPU tensors of equal byte size")
+    rc = load().dma_diag_copy(src.data_ptr(), dst.data_ptr(), n, _stream())
+    if rc:
+        raise DmaError(rc, "dma_diag_copy")
 
 
 def bits_to_bf16_tensor(bits, device="cuda") -> torch.Tensor:

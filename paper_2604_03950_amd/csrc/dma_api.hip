@@ -95,6 +95,14 @@ int dma_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, 
 
 size_t dma_attn_fwd_workspace_bytes(int, int, int, int, int) { return 0; }
 
+int dma_diag_copy(const void* src, void* dst, int64_t bytes, void* stream)
+{
+    if (bytes < 0 || bytes % 16 != 0) return DMA_ERR_INVALID_ARG;
+    if (bytes == 0) return DMA_OK;
+    if (!src || !dst || !aligned16(src) || !aligned16(dst)) return DMA_ERR_INVALID_ARG;
+    return dma::launch_diag_copy(src, dst, bytes, (hipStream_t)stream);
+}
+
 const char* dma_error_string(int code)
 {
     switch (code) {

@@ -283,23 +283,30 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
             });
         }
     } else {
-        // bf16 MFMA (unquantized, or MXFP8 decoded exactly): NKK k=16 steps per 32-key block, next block's operands
-        // in flight while the current block multiplies
-        v4i a[2][C::NKK];
+        // bf16 MFMA (unquantized, or MXFP8 decoded exactly): NKK k=16 steps per 32-key block, in units of UK steps;
+        // the next unit's operands are in flight while the current unit multiplies
+        constexpr int UK = 4, UPB = C::NKK / UK, NU = C::NKB * UPB;
+        static_assert(C::NKK % UK == 0, "head dimension must be a multiple of 64");
+        v4i a[2][UK];
+        auto fetch = [&](int u) {
 #pragma unroll
-        for (int kk = 0; kk < C::NKK; ++kk) a[0][kk] = lds_read<v4i>(ka + 32 * kk);
+            for (int i = 0; i < UK; ++i)
+                a[u & 1][i] = lds_read<v4i>(ka + (u / UPB) * 32 * STRIDE + 32 * ((u % UPB) * UK + i));
+        };
+        fetch(0);
 #pragma unroll
-        for (int kb = 0; kb < C::NKB; ++kb) {
-            if (kb + 1 < C::NKB) {
+        for (int u = 0; u < NU; ++u) {
+            if (u + 1 < NU) fetch(u + 1);
+            const int kb = u / UPB;
 #pragma unroll
-                for (int kk = 0; kk < C::NKK; ++kk) a[(kb + 1) & 1][kk] = lds_read<v4i>(ka + (kb + 1) * 32 * STRIDE + 32 * kk);
-            }
-#pragma unroll
-            for (int kk = 0; kk < C::NKK; ++kk)
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a[kb & 1][kk]),
-                                                                __builtin_bit_cast(v8bf, qr[kk]), s[kb], 0, 0, 0);
-            if constexpr (FMT == FMT_BF16) s[kb] *= c;      // unquantized operands: the softmax factor multiplies the score
+            for (int i = 0; i < UK; ++i)
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a[u & 1][i]),
+                                                                __builtin_bit_cast(v8bf, qr[(u % UPB) * UK + i]), s[kb], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (FMT == FMT_BF16) {                 // unquantized operands: the softmax factor multiplies the score
+#pragma unroll
+            for (int kb = 0; kb < C::NKB; ++kb) s[kb] *= c;
         }
     }
 
@@ -507,8 +514,6 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     // ---- tail: the tiles around the diagonal.  Per wave: skipped (past its diagonal), Phase 1 or Phase 2, masked
     // on its diagonal tile.  Plain load / quantize / barrier / compute / barrier, buffer 0.
     {
-        v4i qr_hi[QRHI];
-        int qs_hi = 0;
         for (int jt = n_main; jt <= last; ++jt) {
             {
                 v4i kreg[C::CPT], vreg[C::CPT];
@@ -533,7 +538,10 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                     score_part<C, LO, true>(qr_t, qs_t, klo_at(0), kslo_at(0), jt == it, qrow_in_tile, lane, c, m, l, o, pb);
                     value_part<C>(v_at(0), lane, o, pb);
                 } else if constexpr (TWO) {
-                    if (jt == lo_end) load_q<C, HI>(qr_hi, qs_hi, qhead, qrow, lane & 31, lane >> 5, c);   // Phase 2 starts
+                    // Phase 2: the high-precision query operand is rebuilt per tile as well (at most `band` times)
+                    v4i qr_hi[QRHI];
+                    int qs_hi = 0;
+                    load_q<C, HI>(qr_hi, qs_hi, qhead, qrow, lane & 31, lane >> 5, c);
                     score_part<C, HI, true>(qr_hi, qs_hi, khi_at, kshi_at, jt == it, qrow_in_tile, lane, c, m, l, o, pb);
                     value_part<C>(v_at(0), lane, o, pb);
                 }

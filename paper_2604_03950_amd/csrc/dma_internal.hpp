@@ -16,6 +16,8 @@ constexpr int DMA_ERR_HIP_ = -3;
 int launch_mx_quantize(const void* x, int64_t rows, int D, int mode, int is_query, void* c4, void* s4,
                        void* c8, void* s8, hipStream_t stream);
 
+int launch_diag_copy(const void* src, void* dst, int64_t bytes, hipStream_t stream);
+
 struct AttnArgs {
     const void* q;
     const void* k;

@@ -66,6 +66,25 @@ static int launch_mode(const void* x, int64_t rows, int D, int is_query, void* c
     return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
 }
 
+// Plain copy, 16 bytes per lane: the reference kernel for calibrating HBM traffic counters.
+__global__ void __launch_bounds__(QUANT_THREADS)
+diag_copy_kernel(const v4i* __restrict__ src, v4i* __restrict__ dst, int64_t n_chunks)
+{
+    const int64_t i = (int64_t)blockIdx.x * QUANT_THREADS + threadIdx.x;
+    if (i < n_chunks) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+int launch_diag_copy(const void* src, void* dst, int64_t bytes, hipStream_t stream)
+{
+    const int64_t n_chunks = bytes / 16;
+    if (n_chunks == 0) return DMA_OK_;
+    const int64_t blocks = (n_chunks + QUANT_THREADS - 1) / QUANT_THREADS;
+    if (blocks > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
+    hipLaunchKernelGGL(diag_copy_kernel, dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream, (const v4i*)src,
+                       (v4i*)dst, n_chunks);
+    return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
+}
+
 int launch_mx_quantize(const void* x, int64_t rows, int D, int mode, int is_query, void* c4, void* s4,
                        void* c8, void* s8, hipStream_t stream)
 {
