@@ -247,3 +247,38 @@ def test_attn_gqa_32k_sampled(dma, oracle):
     q, k, v = wl.generate(w)
     rows = wl.sample_rows(w, [0, 1, 127, 255], [(0, 0), (0, 17)], 128, seed=w.seed + 1)
     run_case(dma, oracle, w, q, k, v, w.band, "e2m1", "e4m3", rows=rows, explicit_tile=False)
+
+
+def test_attn_batched_4k_band_sweep(dma, oracle):
+    """Config 4 (B=8, 32 heads, S=4096): diagonal band 0, 1, 2, 4, 8 on the same inputs, sampled rows; the error
+    against the unquantized fp64 attention is printed (more high-precision tiles -> closer)."""
+    w = wl.CONFIGS["batched_4k"]
+    q, k, v = wl.generate(w)
+    qd, kd, vd = to_gpu(dma, q, k, v)
+    rows = oracle.sort_rows(wl.sample_rows(w, [0, 15, 31], [(0, 0), (3, 7), (7, 31)], 64, seed=w.seed + 1))
+    ref = oracle.ref_attn_rows(q, k, v, rows)
+    for band in (0, 1, 2, 4, 8):
+        out = dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()[rows[:, 0], rows[:, 1], rows[:, 2]]
+        want = oracle.dma_attn_rows(q, k, v, rows, tile=128, band=band)
+        check_out(got, want, f"{w.name} band={band}")
+        print(f"    vs unquantized fp64: rmse {float(np.sqrt(np.mean((got - ref) ** 2))):.4f}", flush=True)
+
+
+def test_attn_heavy_tail_16k_modes(dma, oracle):
+    """Config 5 (S=16384, 40 query heads on 8 kv heads, Student-t inputs): all-MXFP8, all-MXFP4, DMA band 2 and the
+    unquantized bf16 baseline kernel of the same library, sampled rows."""
+    w = wl.CONFIGS["heavy_tail_16k"]
+    q, k, v = wl.generate(w)
+    rows = wl.sample_rows(w, [0, 64, 127], [(0, 0), (0, 39)], 64, seed=w.seed + 1)
+    for band, lo, hi in ((0, "e4m3", "e4m3"), (0, "e2m1", "e2m1"), (2, "e2m1", "e4m3"), (0, "bf16", "bf16")):
+        run_case(dma, oracle, w, q, k, v, band, lo, hi, rows=rows, explicit_tile=False)
+
+
+def test_attn_odd_tile_count(dma, oracle):
+    """An odd number of query tiles uses the one-tile-per-workgroup instance."""
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=384, Hq=3, Hkv=3)
+    q, k, v = wl.generate(w)
+    for band, lo, hi in ((2, "e2m1", "e4m3"), (0, "e2m1", "e2m1")):
+        run_case(dma, oracle, w, q, k, v, band, lo, hi)
