@@ -227,15 +227,19 @@ DMA_DEV v8i widen(const v4i& lo, const v4i& hi) { return v8i{lo[0], lo[1], lo[2]
 template <typename C, int FMT, bool MAYBE_DIAG, int QR>
 DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned kssrc,
                         bool diagonal, int qrow_in_tile, int lane, float c,
-                        float& m, float& l, v16f (&o)[C::NDB], v8bf (&pb)[2 * C::NKB])
+                        float& m, float& mfloor, float& l, v16f (&o)[C::NDB], v8bf (&pb)[2 * C::NKB])
 {
     lane = fresh(lane);
     const int j = lane & 31, g = lane >> 5;
     v16f s[C::NKB];
     constexpr int STRIDE = C::template kstride<FMT>();
     const unsigned ka = pin(ksrc + j * STRIDE + 16 * g);          // the lane's key row of 32-key block 0
+    // The accumulators start at -m (the running maximum so far), so the products arrive as S - m and the
+    // subtraction of the maximum costs nothing in the common case of a maximum that does not move.
+    const float acc0 = (FMT == FMT_BF16) ? 0.f : -m;
 #pragma unroll
-    for (int kb = 0; kb < C::NKB; ++kb) s[kb] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    for (int kb = 0; kb < C::NKB; ++kb)
+        s[kb] = v16f{acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0};
 
     // ---- S^T = K . Q^T.  Operands are fetched from LDS ahead of the MFMAs that use them.
     if constexpr (FMT == FMT_E2M1) {
@@ -306,7 +310,9 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
         }
         if constexpr (FMT == FMT_BF16) {                 // unquantized operands: the softmax factor multiplies the score
 #pragma unroll
-            for (int kb = 0; kb < C::NKB; ++kb) s[kb] *= c;
+            for (int kb = 0; kb < C::NKB; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[kb][r] = __builtin_fmaf(s[kb][r], c, -m);
         }
     }
 
@@ -324,19 +330,23 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
         }
     }
 
-    // ---- online softmax in base 2: running maximum and rescale factor
+    // ---- online softmax in base 2.  s holds S - m.  delta = how far the row maximum moves (>= 0; on the first tile
+    // of a row, where m is only the arbitrary start value 0, any sign: mfloor is -inf there and 0 afterwards).
     float mx = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < C::NKB; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-    mx = cross_half_max(mx);
-    const float mnew = fmaxf(m, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+    const float delta = fmaxf(cross_half_max(mx), mfloor);
+    const float mnew = m + delta;
+    const float alpha = __builtin_amdgcn_exp2f(fminf(m - mnew, 0.f));     // first tile: l and O are 0, any finite factor does
     m = mnew;
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {      // skipped when no row of the wave moved its maximum
+    mfloor = 0.f;
+    if (__builtin_amdgcn_ballot_w64(delta != 0.0f) != 0) {      // skipped when no row of the wave moved its maximum
 #pragma unroll
         for (int db = 0; db < C::NDB; ++db) o[db] *= alpha;
+#pragma unroll
+        for (int kb = 0; kb < C::NKB; ++kb) s[kb] -= delta;
     }
 
     // ---- P = 2^(S - m): row sums from the binary32 values, bf16 (round to nearest even) for the P V product
@@ -345,8 +355,8 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
     for (int grp = 0; grp < 2 * C::NKB; ++grp) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const float p0 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t] - mnew);
-            const float p1 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t + 1] - mnew);
+            const float p0 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t]);
+            const float p1 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t + 1]);
             psum[0] += p0;
             psum[1] += p1;
             const v2bf h2 = __builtin_convertvector(v2f{p0, p1}, v2bf);
@@ -468,7 +478,10 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     // pipelined main loop.  The remaining band + TPW - 1 (or TPW) tiles run in the tail loop, wave by wave.
     const int n_main = (TWO && band > 0) ? max(0, it0 + 1 - band) : it0;
 
-    float m = -INFINITY, l = 0.f;         // Alg. 1 starts l at 1; the first rescale factor 2^(-inf) erases it
+    // Running maximum m and sum l (Alg. 1 starts m at -inf and l at 1, and the first rescale factor 2^(-inf) erases
+    // that l).  Here m starts at 0 with l = 0 and mfloor = -inf marks "no tile seen yet": the first tile then sets m to
+    // its row maximum whatever the sign, which gives the same m, l and O as Alg. 1 after that tile.
+    float m = 0.f, mfloor = -INFINITY, l = 0.f;
     v16f o[C::NDB];
 #pragma unroll
     for (int db = 0; db < C::NDB; ++db) o[db] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -505,7 +518,7 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                     load_tile<C>(vreg, vhead + (int64_t)(t + 2) * BT * D, tid);
                 }
             }
-            score_part<C, LO, false>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), false, qrow_in_tile, lane, c, m, l, o, pb);
+            score_part<C, LO, false>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), false, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
             value_part<C>(v_at(buf), lane, o, pb);
             __syncthreads();
         }
@@ -535,14 +548,14 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                     v4i qr_t[QRLO];
                     int qs_t = 0;
                     load_q<C, LO>(qr_t, qs_t, qhead, qrow, lane & 31, lane >> 5, c);
-                    score_part<C, LO, true>(qr_t, qs_t, klo_at(0), kslo_at(0), jt == it, qrow_in_tile, lane, c, m, l, o, pb);
+                    score_part<C, LO, true>(qr_t, qs_t, klo_at(0), kslo_at(0), jt == it, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
                     value_part<C>(v_at(0), lane, o, pb);
                 } else if constexpr (TWO) {
                     // Phase 2: the high-precision query operand is rebuilt per tile as well (at most `band` times)
                     v4i qr_hi[QRHI];
                     int qs_hi = 0;
                     load_q<C, HI>(qr_hi, qs_hi, qhead, qrow, lane & 31, lane >> 5, c);
-                    score_part<C, HI, true>(qr_hi, qs_hi, khi_at, kshi_at, jt == it, qrow_in_tile, lane, c, m, l, o, pb);
+                    score_part<C, HI, true>(qr_hi, qs_hi, khi_at, kshi_at, jt == it, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
                     value_part<C>(v_at(0), lane, o, pb);
                 }
             }
