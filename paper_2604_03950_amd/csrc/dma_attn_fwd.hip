@@ -236,10 +236,9 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
     const unsigned ka = pin(ksrc + j * STRIDE + 16 * g);          // the lane's key row of 32-key block 0
     // The accumulators start at -m (the running maximum so far), so the products arrive as S - m and the
     // subtraction of the maximum costs nothing in the common case of a maximum that does not move.
+    // (One register tuple holds the start value; the first MFMA of every 32-key block reads it as its C operand.)
     const float acc0 = (FMT == FMT_BF16) ? 0.f : -m;
-#pragma unroll
-    for (int kb = 0; kb < C::NKB; ++kb)
-        s[kb] = v16f{acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0};
+    const v16f sinit = {acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0};
 
     // ---- S^T = K . Q^T.  Operands are fetched from LDS ahead of the MFMAs that use them.
     if constexpr (FMT == FMT_E2M1) {
@@ -270,7 +269,7 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
                 const v8i b = widen(qr[h]);
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
-                    s[2 * pair + u] = mfma_mx<FMT, h>(widen(a[pair & 1][u][h]), b, s[2 * pair + u], ksc[pair & 1][u][h], qscale);
+                    s[2 * pair + u] = mfma_mx<FMT, h>(widen(a[pair & 1][u][h]), b, h == 0 ? sinit : s[2 * pair + u], ksc[pair & 1][u][h], qscale);
             });
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -283,7 +282,7 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
                 const int ksc = lds_read<int>(sa + kb * 32 * C::CPR + 8 * h);
                 const v4i lo = lds_read<v4i>(ka + kb * 32 * STRIDE + 64 * h);
                 const v4i hi = lds_read<v4i>(ka + kb * 32 * STRIDE + 64 * h + 32);
-                s[kb] = mfma_mx<FMT, h>(widen(lo, hi), widen(qr[2 * h], qr[2 * h + 1]), s[kb], ksc, qscale);
+                s[kb] = mfma_mx<FMT, h>(widen(lo, hi), widen(qr[2 * h], qr[2 * h + 1]), h == 0 ? sinit : s[kb], ksc, qscale);
             });
         }
     } else {
@@ -305,7 +304,8 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
 #pragma unroll
             for (int i = 0; i < UK; ++i)
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a[u & 1][i]),
-                                                                __builtin_bit_cast(v8bf, qr[(u % UPB) * UK + i]), s[kb], 0, 0, 0);
+                                                                __builtin_bit_cast(v8bf, qr[(u % UPB) * UK + i]),
+                                                                (u % UPB == 0 && i == 0) ? sinit : s[kb], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         if constexpr (FMT == FMT_BF16) {                 // unquantized operands: the softmax factor multiplies the score
@@ -409,6 +409,21 @@ DMA_DEV void value_part(unsigned vsrc, int lane, v16f (&o)[C::NDB], const v8bf (
 // ---------------------------------------------------------------------------------------------
 // The kernel
 // ---------------------------------------------------------------------------------------------
+// K and V of one key tile from registers into LDS for a tile of the region around the diagonal: the low format if some
+// wave of the workgroup is still in Phase 1 there, the high format (the group's first tile is in Phase 2 from n_main on).
+template <typename C, int LO, int HI>
+DMA_DEV void stage_band_tile(const v4i (&kreg)[C::CPT], const v4i (&vreg)[C::CPT], int jt, int last, int band,
+                             unsigned klo, unsigned kslo, unsigned khi, unsigned kshi, unsigned vdst, int tid)
+{
+    constexpr bool TWO = (LO != HI);
+    const bool any_lo = !(TWO && band > 0) || jt < max(0, last + 1 - band);      // the group's last tile switches last
+    if (any_lo) stage_k<C, LO>(kreg, klo, kslo, tid);
+    if constexpr (TWO) {
+        if (band > 0) stage_k<C, HI>(kreg, khi, kshi, tid);
+    }
+    stage_v<C>(vreg, vdst, tid);
+}
+
 template <int D, int BT, int TPW, int LO, int HI>
 __global__ void __launch_bounds__((BT / 32) * TPW * 64, 2)
 dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
@@ -422,14 +437,18 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     constexpr int QRLO = C::template qregs<LO>();
     constexpr int QRHI = TWO ? C::template qregs<HI>() : 1;
     // LDS map (bytes): V and the low-format K (+ scale bytes) double-buffered for the pipelined main loop, one buffer
-    // for the high format.
+    // for the high format.  The output transpose of the epilogue reuses the same memory.
     constexpr int OFF_V = 0;
     constexpr int OFF_KLO = OFF_V + 2 * C::VBYTES;
     constexpr int OFF_KSLO = OFF_KLO + 2 * KLO;
     constexpr int OFF_KHI = OFF_KSLO + 2 * C::KSC;
     constexpr int OFF_KSHI = OFF_KHI + KHI;
-    constexpr int LDS_TOTAL = OFF_KSHI + (TWO ? C::KSC : 0);
+    constexpr int EPI_COLS = 64;                         // output columns per epilogue pass
+    constexpr int EPI_STRIDE = EPI_COLS * 4 + 16;        // bytes per staged output row (padded against bank conflicts)
+    constexpr int EPI_WAVE = 32 * EPI_STRIDE;
+    constexpr int LDS_TOTAL = cmax<OFF_KSHI + (TWO ? C::KSC : 0), C::NW * EPI_WAVE>();
     static_assert(LDS_TOTAL <= 160 * 1024, "LDS budget of one CU");
+    static_assert(D % EPI_COLS == 0, "epilogue works on 64-column slabs");
     __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_TOTAL];
     const unsigned lds0 = (unsigned)(uintptr_t)(DMA_LDS uint8_t*)lds;
     auto v_at = [&](int buf) { return lds0 + OFF_V + buf * C::VBYTES; };
@@ -441,151 +460,205 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
 
-    // ---- which (batch, query head, group of TPW query tiles): heaviest first; when the (batch, kv head)
-    // units divide over the 8 XCDs, every unit stays on one XCD so its K/V stream is shared in that L2.
+    // ---- static schedule.  The grid is one workgroup per CU; a work item is (batch, query head, group of TPW query
+    // tiles) and costs about 2 * grp + 2 key-tile steps.  Items are ranked heaviest first and dealt to the workgroups
+    // in boustrophedon order (round 0: worker 0, 1, ..., W-1; round 1: W-1, ..., 0; ...), which gives every worker
+    // the same load to within the lightest items, without atomics and whatever order the hardware starts workgroups
+    // in.  When the (batch, kv head) units divide over the 8 XCDs (workgroup i runs on XCD i % 8), each XCD keeps its
+    // own units, so the K/V stream of a unit stays in one L2.
     const int N = S / BT;                // logical tiles per sequence (host guarantees N % TPW == 0)
     const int NG = N / TPW;              // tile groups
     const int group = Hq / Hkv;
     const int units = B * Hkv;
-    const int bid = blockIdx.x;
-    int b, hq, grp;
-    if (units % 8 == 0) {
-        const int xcd = bid & 7, idx = bid >> 3;
-        const int per_unit = group * NG;
-        const int unit = (idx / per_unit) * 8 + xcd, rem = idx % per_unit;
-        b = unit / Hkv;
-        hq = (unit % Hkv) * group + rem / NG;
-        grp = NG - 1 - rem % NG;
-    } else {
-        const int bh = bid % (B * Hq);
-        grp = NG - 1 - bid / (B * Hq);
-        b = bh / Hq;
-        hq = bh % Hq;
-    }
-    const int hkv = hq / group;
-    const uint16_t* qhead = q + ((int64_t)b * Hq + hq) * S * D;
-    const uint16_t* khead = k + ((int64_t)b * Hkv + hkv) * S * D;
-    const uint16_t* vhead = v + ((int64_t)b * Hkv + hkv) * S * D;
-    float* ohead = out + ((int64_t)b * Hq + hq) * S * D;
+    const bool by_xcd = (units % 8 == 0) && (gridDim.x % 8 == 0);
+    const int xcd = by_xcd ? (int)(blockIdx.x & 7) : 0;
+    const int slot = by_xcd ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int workers = by_xcd ? (int)(gridDim.x >> 3) : (int)gridDim.x;
+    const int heads_x = by_xcd ? (units / 8) * group : B * Hq;       // query heads ranked together
+    const int items = heads_x * NG;
 
-    // ---- this wave's logical tile and its phase boundary (Alg. 1: low tiles [0, lo_end), high [lo_end, it])
-    const int it0 = grp * TPW, last = it0 + TPW - 1;
-    const int it = it0 + wave / C::WPT;
-    const int qrow_in_tile = (wave % C::WPT) * 32;
-    const int qrow = it * BT + qrow_in_tile;
-    const int lo_end = (TWO && band > 0) ? max(0, it + 1 - band) : it + 1;
-    // Key tiles [0, n_main) are Phase 1 and strictly below the diagonal for EVERY wave of the workgroup: the
-    // pipelined main loop.  The remaining band + TPW - 1 (or TPW) tiles run in the tail loop, wave by wave.
-    const int n_main = (TWO && band > 0) ? max(0, it0 + 1 - band) : it0;
+    for (int round = 0;; ++round) {
+        const int pos = round * workers + ((round & 1) ? workers - 1 - slot : slot);
+        if (pos >= items) break;
+        const int grp = NG - 1 - pos / heads_x;
+        const int hx = pos % heads_x;
+        const int unit = by_xcd ? (hx / group) * 8 + xcd : hx / group;
+        const int b = unit / Hkv;
+        const int hkv = unit % Hkv;
+        const int hq = hkv * group + hx % group;
+        const uint16_t* qhead = q + ((int64_t)b * Hq + hq) * S * D;
+        const uint16_t* khead = k + ((int64_t)b * Hkv + hkv) * S * D;
+        const uint16_t* vhead = v + ((int64_t)b * Hkv + hkv) * S * D;
+        float* ohead = out + ((int64_t)b * Hq + hq) * S * D;
 
-    // Running maximum m and sum l (Alg. 1 starts m at -inf and l at 1, and the first rescale factor 2^(-inf) erases
-    // that l).  Here m starts at 0 with l = 0 and mfloor = -inf marks "no tile seen yet": the first tile then sets m to
-    // its row maximum whatever the sign, which gives the same m, l and O as Alg. 1 after that tile.
-    float m = 0.f, mfloor = -INFINITY, l = 0.f;
-    v16f o[C::NDB];
+        // ---- this wave's logical tile and its phase boundary (Alg. 1: low tiles [0, lo_end), high [lo_end, it])
+        const int it0 = grp * TPW, last = it0 + TPW - 1;
+        const int it = it0 + wave / C::WPT;
+        const int qrow_in_tile = (wave % C::WPT) * 32;
+        const int qrow = it * BT + qrow_in_tile;
+        const int lo_end = (TWO && band > 0) ? max(0, it + 1 - band) : it + 1;
+        // Key tiles [0, n_main) are Phase 1 and strictly below the diagonal for EVERY wave of the workgroup: the
+        // main loop.  The remaining band + TPW - 1 (or TPW) tiles run in the band loop, wave by wave.
+        const int n_main = (TWO && band > 0) ? max(0, it0 + 1 - band) : it0;
+
+        // Running maximum m and sum l (Alg. 1 starts m at -inf and l at 1, and the first rescale factor 2^(-inf) erases
+        // that l).  Here m starts at 0 with l = 0 and mfloor = -inf marks "no tile seen yet": the first tile then sets m to
+        // its row maximum whatever the sign, which gives the same m, l and O as Alg. 1 after that tile.
+        float m = 0.f, mfloor = -INFINITY, l = 0.f;
+        v16f o[C::NDB];
 #pragma unroll
-    for (int db = 0; db < C::NDB; ++db) o[db] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        for (int db = 0; db < C::NDB; ++db) o[db] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-
-    // ---- main loop.  Tile t lives in LDS buffer t & 1; one barrier per tile.  At the top of step t the K and V
-    // tiles t+1 (loaded into registers during step t-1) go into the other buffer (K quantized on the way) and the
-    // loads of tiles t+2 start; then the wave computes tile t.  (Direct global-to-LDS loads are not used for V: the
-    // compiler orders every later LDS access behind them with a full vmcnt(0) wait, which exposes the memory latency.)
-    // (On this GPU the MFMA pipe and the floating-point VALU of a SIMD do not run concurrently, so the two waves
-    // of a SIMD are only there to hide LDS and memory latency, not to overlap matrix and softmax work.)
-    if (n_main > 0) {
+        // ---- prologue: key tile 0 and the query operand (all loads in flight together), tile 0 into LDS buffer 0.
+        // Invariant from here on: the K/V registers hold the tile after the one staged last, if the main loop needs it.
+        v4i kreg[C::CPT], vreg[C::CPT];
         v8bf pb[2 * C::NKB];
         v4i qr_lo[QRLO];
         int qs_lo = 0;
-        load_q<C, LO>(qr_lo, qs_lo, qhead, qrow, lane & 31, lane >> 5, c);
-        v4i kreg[C::CPT], vreg[C::CPT];
         load_tile<C>(kreg, khead, tid);
         load_tile<C>(vreg, vhead, tid);
-        stage_k<C, LO>(kreg, klo_at(0), kslo_at(0), tid);
-        stage_v<C>(vreg, v_at(0), tid);
-        if (n_main > 1) {
+        load_q<C, LO>(qr_lo, qs_lo, qhead, qrow, lane & 31, lane >> 5, c);
+        if (n_main > 0) {
+            stage_k<C, LO>(kreg, klo_at(0), kslo_at(0), tid);
+            stage_v<C>(vreg, v_at(0), tid);
+        } else {
+            stage_band_tile<C, LO, HI>(kreg, vreg, 0, last, band, klo_at(0), kslo_at(0), khi_at, kshi_at, v_at(0), tid);
+        }
+        if (n_main >= 1) {
             load_tile<C>(kreg, khead + (int64_t)BT * D, tid);
             load_tile<C>(vreg, vhead + (int64_t)BT * D, tid);
         }
         __syncthreads();
+
+        // ---- main loop.  Tile t lives in LDS buffer t & 1; one barrier per tile.  At the top of step t the K and V
+        // tiles t+1 (loaded into registers during step t-1) go into the other buffer (K quantized on the way) and the
+        // loads of tile t+2 start; then the wave computes tile t.  The last step stages the first tile of the band loop.
+        // (Direct global-to-LDS loads are not used for V: the compiler orders every later LDS access behind them with
+        // a full vmcnt(0) wait, which exposes the memory latency.  On this GPU the MFMA pipe and the floating-point
+        // VALU of a SIMD do not run concurrently, so the two waves of a SIMD are only there to hide LDS and memory
+        // latency, not to overlap matrix and softmax work.)
         for (int t = 0; t < n_main; ++t) {
             const int buf = t & 1;
             if (t + 1 < n_main) {
                 stage_k<C, LO>(kreg, klo_at(buf ^ 1), kslo_at(buf ^ 1), tid);
                 stage_v<C>(vreg, v_at(buf ^ 1), tid);
-                if (t + 2 < n_main) {
-                    load_tile<C>(kreg, khead + (int64_t)(t + 2) * BT * D, tid);
-                    load_tile<C>(vreg, vhead + (int64_t)(t + 2) * BT * D, tid);
-                }
+            } else {
+                stage_band_tile<C, LO, HI>(kreg, vreg, t + 1, last, band, klo_at(buf ^ 1), kslo_at(buf ^ 1), khi_at, kshi_at,
+                                           v_at(buf ^ 1), tid);
+            }
+            if (t + 2 <= n_main) {
+                load_tile<C>(kreg, khead + (int64_t)(t + 2) * BT * D, tid);
+                load_tile<C>(vreg, vhead + (int64_t)(t + 2) * BT * D, tid);
             }
             score_part<C, LO, false>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), false, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
             value_part<C>(v_at(buf), lane, o, pb);
             __syncthreads();
         }
-    }
 
-    // ---- tail: the tiles around the diagonal.  Per wave: skipped (past its diagonal), Phase 1 or Phase 2, masked
-    // on its diagonal tile.  Plain load / quantize / barrier / compute / barrier, buffer 0.
-    {
-        for (int jt = n_main; jt <= last; ++jt) {
-            {
-                v4i kreg[C::CPT], vreg[C::CPT];
-                load_tile<C>(kreg, khead + (int64_t)jt * BT * D, tid);
-                load_tile<C>(vreg, vhead + (int64_t)jt * BT * D, tid);
-                const bool any_lo = !(TWO && band > 0) || jt < max(0, last + 1 - band);   // the group's last tile switches last
-                if (any_lo) stage_k<C, LO>(kreg, klo_at(0), kslo_at(0), tid);
-                if constexpr (TWO) {
-                    if (band > 0) stage_k<C, HI>(kreg, khi_at, kshi_at, tid);                // jt >= n_main: the group's first tile is in Phase 2
-                }
-                stage_v<C>(vreg, v_at(0), tid);
+        // ---- band loop: the tiles around the diagonal.  Per wave: skipped (past its diagonal), Phase 1 or Phase 2,
+        // masked on its diagonal tile.  Tile jt is in LDS (V and low-format K in buffer jt & 1, high-format K in its
+        // single buffer) when an iteration starts; the loads of tile jt+1 are issued between the score and the value
+        // part, when few registers are live, and staged after the barrier that ends the iteration.
+        {
+            v4i qr_hi[QRHI];
+            int qs_hi = 0;
+            if constexpr (TWO) {
+                if (band > 0) load_q<C, HI>(qr_hi, qs_hi, qhead, qrow, lane & 31, lane >> 5, c);
             }
-            __syncthreads();
-            if (jt <= it) {
-                v8bf pb[2 * C::NKB];
-                if (jt < lo_end) {
-                    // the low-format query operand is rebuilt here rather than kept alive from the main loop: its
-                    // registers would otherwise be reserved through the register-hungry Phase 2 code as well
-                    v4i qr_t[QRLO];
-                    int qs_t = 0;
-                    load_q<C, LO>(qr_t, qs_t, qhead, qrow, lane & 31, lane >> 5, c);
-                    score_part<C, LO, true>(qr_t, qs_t, klo_at(0), kslo_at(0), jt == it, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
-                    value_part<C>(v_at(0), lane, o, pb);
-                } else if constexpr (TWO) {
-                    // Phase 2: the high-precision query operand is rebuilt per tile as well (at most `band` times)
-                    v4i qr_hi[QRHI];
-                    int qs_hi = 0;
-                    load_q<C, HI>(qr_hi, qs_hi, qhead, qrow, lane & 31, lane >> 5, c);
-                    score_part<C, HI, true>(qr_hi, qs_hi, khi_at, kshi_at, jt == it, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
-                    value_part<C>(v_at(0), lane, o, pb);
+            for (int jt = n_main; jt <= last; ++jt) {
+                const int buf = jt & 1;
+                const bool active = jt <= it;
+                if (active) {
+                    if (jt < lo_end) {
+                        score_part<C, LO, true>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), jt == it, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
+                    } else if constexpr (TWO) {
+                        score_part<C, HI, true>(qr_hi, qs_hi, khi_at, kshi_at, jt == it, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
+                    }
+                }
+                if (jt < last) {
+                    load_tile<C>(kreg, khead + (int64_t)(jt + 1) * BT * D, tid);
+                    load_tile<C>(vreg, vhead + (int64_t)(jt + 1) * BT * D, tid);
+                }
+                if (active) value_part<C>(v_at(buf), lane, o, pb);
+                __syncthreads();
+                if (jt < last) {
+                    stage_band_tile<C, LO, HI>(kreg, vreg, jt + 1, last, band, klo_at(buf ^ 1), kslo_at(buf ^ 1), khi_at, kshi_at,
+                                               v_at(buf ^ 1), tid);
+                    __syncthreads();
                 }
             }
-            __syncthreads();
         }
-    }
 
-    // ---- O / l
-    const int j = lane & 31, g = lane >> 5;
-    const float inv = 1.0f / cross_half_sum(l);
-    float* orow = ohead + (int64_t)(qrow + j) * D;
+        // ---- O / l, transposed through LDS (free after the barrier above) so that every output row leaves as whole
+        // 256-byte runs: the wave parks a 32 x 64 slab of its rows in its own LDS region and reads it back row-major,
+        // four rows (16 lanes x 16 bytes each) per instruction.
+        {
+            const int ln = fresh(lane);
+            const int j = ln & 31, g = ln >> 5, rsub = ln >> 4, piece = ln & 15;
+            const float inv = 1.0f / cross_half_sum(l);
+            const unsigned region = lds0 + wave * EPI_WAVE;
+            const unsigned wr = pin(region + j * EPI_STRIDE + 16 * g);
+            const unsigned rd = pin(region + rsub * EPI_STRIDE + 16 * piece);
+            float* obase = ohead + (int64_t)(qrow + rsub) * D + 4 * piece;
 #pragma unroll
-    for (int db = 0; db < C::NDB; ++db)
+            for (int slab = 0; slab < D / EPI_COLS; ++slab) {
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            v4f val = {o[db][4 * r4] * inv, o[db][4 * r4 + 1] * inv, o[db][4 * r4 + 2] * inv, o[db][4 * r4 + 3] * inv};
-            *(v4f*)(orow + 32 * db + 8 * r4 + 4 * g) = val;
+                for (int dd = 0; dd < EPI_COLS / 32; ++dd) {
+                    const int db = slab * (EPI_COLS / 32) + dd;
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const v4f val = {o[db][4 * r4] * inv, o[db][4 * r4 + 1] * inv, o[db][4 * r4 + 2] * inv, o[db][4 * r4 + 3] * inv};
+                        lds_write<v4f>(wr + 128 * dd + 32 * r4, val);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const v4f val = lds_read<v4f>(rd + 4 * i * EPI_STRIDE);
+                    *(v4f*)(obase + (int64_t)(4 * i) * D + slab * EPI_COLS) = val;
+                }
+            }
         }
+        __syncthreads();                  // the next item's staging overwrites the epilogue regions
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Host side: pick the instance
 // ---------------------------------------------------------------------------------------------
+// Number of compute units of the current device (cached per device).
+static int compute_units()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 template <int D, int BT, int TPW, int LO, int HI>
 static int launch_instance(const AttnArgs& a, hipStream_t stream)
 {
     using C = Cfg<D, BT, TPW>;
     const int N = a.S / BT;
-    const int64_t blocks = (int64_t)a.B * a.Hq * (N / TPW);
-    if (N % TPW != 0 || blocks <= 0 || blocks > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
+    const int64_t items = (int64_t)a.B * a.Hq * (N / TPW);
+    if (N % TPW != 0 || items <= 0 || items > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
+    const int cus = compute_units();
+    if (cus <= 0) return DMA_ERR_HIP_;
+    // as many workgroups as the chip holds at once (one per CU for the D = 128 instances), each walking its share
+    // of the work items
+    static int resident = 0;              // per instance; the same on every device of one kind
+    if (resident == 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dma_attn_fwd_kernel<D, BT, TPW, LO, HI>, C::T, 0) != hipSuccess || n <= 0)
+            return DMA_ERR_HIP_;
+        resident = n;
+    }
+    const int64_t slots = (int64_t)cus * resident;
+    const int64_t blocks = items < slots ? items : slots;
     const float c = (float)(1.4426950408889634074 / sqrt((double)D));
     hipLaunchKernelGGL((dma_attn_fwd_kernel<D, BT, TPW, LO, HI>), dim3((unsigned)blocks), dim3(C::T), 0, stream,
                        (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, a.out, a.B, a.Hq, a.Hkv,
