@@ -428,7 +428,7 @@ template <int D, int BT, int TPW, int LO, int HI>
 __global__ void __launch_bounds__((BT / 32) * TPW * 64, 2)
 dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     const uint16_t* __restrict__ v, float* __restrict__ out,
-                    int B, int Hq, int Hkv, int S, int band, float c)
+                    int B, int Hq, int Hkv, int S, int band, float c, int head_block)
 {
     using C = Cfg<D, BT, TPW>;
     constexpr bool TWO = (LO != HI);
@@ -461,10 +461,11 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     const int lane = tid & 63;
 
     // ---- static schedule.  The grid is one workgroup per CU; a work item is (batch, query head, group of TPW query
-    // tiles) and costs about 2 * grp + 2 key-tile steps.  Items are ranked heaviest first and dealt to the workgroups
-    // in boustrophedon order (round 0: worker 0, 1, ..., W-1; round 1: W-1, ..., 0; ...), which gives every worker
-    // the same load to within the lightest items, without atomics and whatever order the hardware starts workgroups
-    // in.  When the (batch, kv head) units divide over the 8 XCDs (workgroup i runs on XCD i % 8), each XCD keeps its
+    // tiles) and costs about 2 * grp + 2 key-tile steps.  Items are ranked heaviest first within blocks of
+    // `head_block` query heads and dealt to the workgroups in boustrophedon order (round 0: worker 0, 1, ..., W-1;
+    // round 1: W-1, ..., 0; ...), which gives every worker the same load to within the lightest items, without
+    // atomics and whatever order the hardware starts workgroups in; a block is an even number of rounds (or
+    // everything), so the workers move from block to block together and share few K/V streams at a time.  When the (batch, kv head) units divide over the 8 XCDs (workgroup i runs on XCD i % 8), each XCD keeps its
     // own units, so the K/V stream of a unit stays in one L2.
     const int N = S / BT;                // logical tiles per sequence (host guarantees N % TPW == 0)
     const int NG = N / TPW;              // tile groups
@@ -480,8 +481,9 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     for (int round = 0;; ++round) {
         const int pos = round * workers + ((round & 1) ? workers - 1 - slot : slot);
         if (pos >= items) break;
-        const int grp = NG - 1 - pos / heads_x;
-        const int hx = pos % heads_x;
+        const int blk = pos / (head_block * NG), within = pos % (head_block * NG);
+        const int grp = NG - 1 - within / head_block;
+        const int hx = blk * head_block + within % head_block;
         const int unit = by_xcd ? (hx / group) * 8 + xcd : hx / group;
         const int b = unit / Hkv;
         const int hkv = unit % Hkv;
@@ -546,11 +548,11 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                 stage_band_tile<C, LO, HI>(kreg, vreg, t + 1, last, band, klo_at(buf ^ 1), kslo_at(buf ^ 1), khi_at, kshi_at,
                                            v_at(buf ^ 1), tid);
             }
-            if (t + 2 <= n_main) {
-                load_tile<C>(kreg, khead + (int64_t)(t + 2) * BT * D, tid);
-                load_tile<C>(vreg, vhead + (int64_t)(t + 2) * BT * D, tid);
-            }
+            // K of tile t+2 is requested before the score part, V after it: the two bursts of requests (every wave of the
+            // workgroup issues them at the same point) are half as long, and the score part has 16 registers more
+            if (t + 2 <= n_main) load_tile<C>(kreg, khead + (int64_t)(t + 2) * BT * D, tid);
             score_part<C, LO, false>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), false, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
+            if (t + 2 <= n_main) load_tile<C>(vreg, vhead + (int64_t)(t + 2) * BT * D, tid);
             value_part<C>(v_at(buf), lane, o, pb);
             __syncthreads();
         }
@@ -660,9 +662,17 @@ static int launch_instance(const AttnArgs& a, hipStream_t stream)
     const int64_t slots = (int64_t)cus * resident;
     const int64_t blocks = items < slots ? items : slots;
     const float c = (float)(1.4426950408889634074 / sqrt((double)D));
+    // ranking blocks: the fewest heads that fill an even number of rounds (mirrors the kernel's view of the grid)
+    const int units = a.B * a.Hkv, group = a.Hq / a.Hkv, NG = N / TPW;
+    const bool by_xcd = (units % 8 == 0) && (blocks % 8 == 0);
+    const int workers = (int)(by_xcd ? blocks / 8 : blocks);
+    const int heads_x = by_xcd ? (units / 8) * group : a.B * a.Hq;
+    int head_block = heads_x;
+    for (int hb = 1; hb < heads_x; ++hb)
+        if (heads_x % hb == 0 && ((int64_t)hb * NG) % (2 * workers) == 0) { head_block = hb; break; }
     hipLaunchKernelGGL((dma_attn_fwd_kernel<D, BT, TPW, LO, HI>), dim3((unsigned)blocks), dim3(C::T), 0, stream,
                        (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, a.out, a.B, a.Hq, a.Hkv,
-                       a.S, a.band, c);
+                       a.S, a.band, c, head_block);
     return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
 }
 
