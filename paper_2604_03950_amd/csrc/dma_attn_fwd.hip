@@ -67,48 +67,54 @@ struct Cfg {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Query operand of a wave: its 32 rows in MFMA B-operand layout for format FMT, held in `qr`
-// (scaled MFMA formats also fill `qscale`: byte h = E8M0 of block 2h + g of the lane's row).
+// Query operand of a wave: its 32 rows in MFMA B-operand layout.  Lane (j, g) = (lane % 32, lane / 32) owns row j and
+// the MX blocks 2h + g (h < NH) of that row: raw[4h + t] is the 16-byte chunk t of block 2h + g, i.e. elements
+// 32 (2h + g) + 8t + [0, 8).  Every format's operand is made from these registers, so one set of loads serves both
+// precisions and every block maximum is lane-local:
+//   scaled MFMA (k = 64 per step h): block 2h + g is exactly the lane's share of step h;
+//   bf16 MFMA (k = 16 per step kk = 4h + t): the lane's 8 elements of step kk are chunk t of block 2h + g -- a
+//   permutation of the head dimension against the instruction's natural order, which the K side mirrors (see score_part).
 // ---------------------------------------------------------------------------------------------
-template <typename C, int FMT, int QR>
-DMA_DEV void load_q(v4i (&qr)[QR], int& qscale, const uint16_t* __restrict__ qhead, int row0, int j, int g, float c)
+template <typename C>
+DMA_DEV void load_q_raw(v4i (&raw)[C::NKK], const uint16_t* __restrict__ qhead, int row0, int j, int g)
 {
-    const uint16_t* rowp = qhead + (int64_t)(row0 + j) * C::D;
+    const uint16_t* rowp = qhead + (int64_t)(row0 + j) * C::D + 32 * g;
+#pragma unroll
+    for (int h = 0; h < C::NH; ++h)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) raw[4 * h + t] = *(const v4i*)(rowp + 64 * h + 8 * t);
+}
+
+// qr / qscale from raw (scaled MFMA formats fill `qscale`: byte h = E8M0 of block 2h + g of the lane's row).
+template <typename C, int FMT, int QR>
+DMA_DEV void make_q(v4i (&qr)[QR], int& qscale, const v4i (&raw)[C::NKK], float c)
+{
     qscale = 0;
     if constexpr (FMT == FMT_BF16) {
 #pragma unroll
-        for (int kk = 0; kk < C::NKK; ++kk) qr[kk] = *(const v4i*)(rowp + 16 * kk + 8 * g);
-    } else if constexpr (FMT == FMT_E4M3_X) {
-        // The lane holds elements 16kk + 8g + [0, 8): MX block b = kk / 2 is spread over both half-waves.
-#pragma unroll
-        for (int b = 0; b < C::NKK / 2; ++b) {
-            float x0[8], x1[8];
-            unpack8<true>(*(const v4i*)(rowp + 32 * b + 8 * g), c, x0);
-            unpack8<true>(*(const v4i*)(rowp + 32 * b + 16 + 8 * g), c, x1);
-            const float amax = cross_half_max(fmaxf(amax8(x0), amax8(x1)));
-            const int code = e8m0_code<FMT_E4M3>(amax);
-            qr[2 * b] = quant_dequant8_e4m3(x0, code);
-            qr[2 * b + 1] = quant_dequant8_e4m3(x1, code);
-        }
+        for (int kk = 0; kk < C::NKK; ++kk) qr[kk] = raw[kk];
     } else {
         static_for<C::NH>([&](auto H) {
             constexpr int h = H;
-            const v4i* src = (const v4i*)(rowp + 32 * (2 * h + g));     // the lane's whole MX block
             float x[4][8];
             float amax = 0.f;
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                unpack8<true>(src[t], c, x[t]);
+                unpack8<true>(raw[4 * h + t], c, x[t]);
                 amax = fmaxf(amax, amax8(x[t]));
             }
             const int code = e8m0_code<FMT>(amax);
-            qscale |= code << (8 * h);
-            if constexpr (FMT == FMT_E2M1) {
+            if constexpr (FMT == FMT_E4M3_X) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) qr[4 * h + t] = quant_dequant8_e4m3(x[t], code);
+            } else if constexpr (FMT == FMT_E2M1) {
+                qscale |= code << (8 * h);
                 v4i r;
 #pragma unroll
                 for (int t = 0; t < 4; ++t) r[t] = encode8_e2m1(x[t], code);
                 qr[h] = r;
             } else {
+                qscale |= code << (8 * h);
                 int r[8];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
@@ -224,16 +230,18 @@ DMA_DEV v8i widen(const v4i& lo, const v4i& hi) { return v8i{lo[0], lo[1], lo[2]
 // The result is P^T packed as the B operands of the value part: pb[grp] holds keys 16 grp .. 16 grp + 15.
 // ksrc / kssrc: LDS addresses of the tile's K codes / scale bytes.
 // MAYBE_DIAG = false compiles the mask away (tiles strictly below the diagonal).
-template <typename C, int FMT, bool MAYBE_DIAG, int QR>
+// after_mfma() runs between the matrix part and the softmax part (the caller's global loads go there).
+template <typename C, int FMT, bool MAYBE_DIAG, int QR, typename F>
 DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned kssrc,
                         bool diagonal, int qrow_in_tile, int lane, float c,
-                        float& m, float& mfloor, float& l, v16f (&o)[C::NDB], v8bf (&pb)[2 * C::NKB])
+                        float& m, float& mfloor, float& l, v16f (&o)[C::NDB], v8bf (&pb)[2 * C::NKB], F&& after_mfma)
 {
     lane = fresh(lane);
     const int j = lane & 31, g = lane >> 5;
     v16f s[C::NKB];
     constexpr int STRIDE = C::template kstride<FMT>();
-    const unsigned ka = pin(ksrc + j * STRIDE + 16 * g);          // the lane's key row of 32-key block 0
+    // the lane's key row of 32-key block 0; the bf16 MFMA paths read the head dimension in the query operand's order
+    const unsigned ka = pin(ksrc + j * STRIDE + (uses_bf16_mfma(FMT) ? 64 : 16) * g);
     // The accumulators start at -m (the running maximum so far), so the products arrive as S - m and the
     // subtraction of the maximum costs nothing in the common case of a maximum that does not move.
     // (One register tuple holds the start value; the first MFMA of every 32-key block reads it as its C operand.)
@@ -287,14 +295,15 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
         }
     } else {
         // bf16 MFMA (unquantized, or MXFP8 decoded exactly): NKK k=16 steps per 32-key block, in units of UK steps;
-        // the next unit's operands are in flight while the current unit multiplies
+        // the next unit's operands are in flight while the current unit multiplies.  Step kk = 4h + t multiplies the
+        // lane's chunk t of MX block 2h + g (see load_q_raw): byte 128 h + 64 g + 16 t of the key's bf16 row.
         constexpr int UK = 4, UPB = C::NKK / UK, NU = C::NKB * UPB;
         static_assert(C::NKK % UK == 0, "head dimension must be a multiple of 64");
         v4i a[2][UK];
         auto fetch = [&](int u) {
 #pragma unroll
             for (int i = 0; i < UK; ++i)
-                a[u & 1][i] = lds_read<v4i>(ka + (u / UPB) * 32 * STRIDE + 32 * ((u % UPB) * UK + i));
+                a[u & 1][i] = lds_read<v4i>(ka + (u / UPB) * 32 * STRIDE + 16 * ((u % UPB) * UK + i) + 64 * (((u % UPB) * UK + i) / 4));
         };
         fetch(0);
 #pragma unroll
@@ -315,6 +324,8 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
                 for (int r = 0; r < 16; ++r) s[kb][r] = __builtin_fmaf(s[kb][r], c, -m);
         }
     }
+
+    after_mfma();
 
     // ---- causal mask on the tile that straddles the diagonal: key > query -> -inf
     if constexpr (MAYBE_DIAG) {
@@ -436,17 +447,18 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     constexpr int KHI = TWO ? C::template kbytes<HI>() : 0;
     constexpr int QRLO = C::template qregs<LO>();
     constexpr int QRHI = TWO ? C::template qregs<HI>() : 1;
-    // LDS map (bytes): V and the low-format K (+ scale bytes) double-buffered for the pipelined main loop, one buffer
-    // for the high format.  The output transpose of the epilogue reuses the same memory.
+    // LDS map (bytes): V, the low-format K and the high-format K (each + scale bytes) double-buffered for the pipelined
+    // tile loops.  The output transpose of the epilogue reuses the same memory.
     constexpr int OFF_V = 0;
     constexpr int OFF_KLO = OFF_V + 2 * C::VBYTES;
     constexpr int OFF_KSLO = OFF_KLO + 2 * KLO;
     constexpr int OFF_KHI = OFF_KSLO + 2 * C::KSC;
-    constexpr int OFF_KSHI = OFF_KHI + KHI;
+    constexpr bool HI_SCALES = TWO && !uses_bf16_mfma(HI);   // the decoded-to-bf16 high format carries no scale bytes
+    constexpr int OFF_KSHI = OFF_KHI + 2 * KHI;
     constexpr int EPI_COLS = 64;                         // output columns per epilogue pass
     constexpr int EPI_STRIDE = EPI_COLS * 4 + 16;        // bytes per staged output row (padded against bank conflicts)
     constexpr int EPI_WAVE = 32 * EPI_STRIDE;
-    constexpr int LDS_TOTAL = cmax<OFF_KSHI + (TWO ? C::KSC : 0), C::NW * EPI_WAVE>();
+    constexpr int LDS_TOTAL = cmax<OFF_KSHI + (HI_SCALES ? 2 * C::KSC : 0), C::NW * EPI_WAVE>();
     static_assert(LDS_TOTAL <= 160 * 1024, "LDS budget of one CU");
     static_assert(D % EPI_COLS == 0, "epilogue works on 64-column slabs");
     __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_TOTAL];
@@ -454,7 +466,8 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     auto v_at = [&](int buf) { return lds0 + OFF_V + buf * C::VBYTES; };
     auto klo_at = [&](int buf) { return lds0 + OFF_KLO + buf * KLO; };
     auto kslo_at = [&](int buf) { return lds0 + OFF_KSLO + buf * C::KSC; };
-    const unsigned khi_at = lds0 + OFF_KHI, kshi_at = lds0 + OFF_KSHI;
+    auto khi_at = [&](int buf) { return lds0 + OFF_KHI + buf * KHI; };
+    auto kshi_at = [&](int buf) { return lds0 + OFF_KSHI + (HI_SCALES ? buf * C::KSC : 0); };
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -511,84 +524,84 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
 #pragma unroll
         for (int db = 0; db < C::NDB; ++db) o[db] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-        // ---- prologue: key tile 0 and the query operand (all loads in flight together), tile 0 into LDS buffer 0.
-        // Invariant from here on: the K/V registers hold the tile after the one staged last, if the main loop needs it.
+        // ---- prologue: key tile 0 and the query operands (all loads in flight together), tile 0 into LDS buffer 0.
+        // Invariant from here on: the K/V registers hold the tile after the one staged last, if there is one.
         v4i kreg[C::CPT], vreg[C::CPT];
         v8bf pb[2 * C::NKB];
-        v4i qr_lo[QRLO];
-        int qs_lo = 0;
-        load_tile<C>(kreg, khead, tid);
-        load_tile<C>(vreg, vhead, tid);
-        load_q<C, LO>(qr_lo, qs_lo, qhead, qrow, lane & 31, lane >> 5, c);
+        v4i qr_lo[QRLO], qr_hi[QRHI];
+        int qs_lo = 0, qs_hi = 0;
+        {
+            v4i qraw[C::NKK];
+            load_q_raw<C>(qraw, qhead, qrow, fresh(lane) & 31, fresh(lane) >> 5);
+            load_tile<C>(kreg, khead, tid);
+            load_tile<C>(vreg, vhead, tid);
+            __builtin_amdgcn_sched_barrier(0);           // every request is out before the first result is needed
+            make_q<C, LO>(qr_lo, qs_lo, qraw, c);
+            if constexpr (TWO) {
+                if (band > 0) make_q<C, HI>(qr_hi, qs_hi, qraw, c);
+            }
+        }
         if (n_main > 0) {
             stage_k<C, LO>(kreg, klo_at(0), kslo_at(0), tid);
             stage_v<C>(vreg, v_at(0), tid);
         } else {
-            stage_band_tile<C, LO, HI>(kreg, vreg, 0, last, band, klo_at(0), kslo_at(0), khi_at, kshi_at, v_at(0), tid);
+            stage_band_tile<C, LO, HI>(kreg, vreg, 0, last, band, klo_at(0), kslo_at(0), khi_at(0), kshi_at(0), v_at(0), tid);
         }
-        if (n_main >= 1) {
+        if (1 <= last) {
             load_tile<C>(kreg, khead + (int64_t)BT * D, tid);
             load_tile<C>(vreg, vhead + (int64_t)BT * D, tid);
         }
         __syncthreads();
 
-        // ---- main loop.  Tile t lives in LDS buffer t & 1; one barrier per tile.  At the top of step t the K and V
+        // ---- tile loops.  Tile t lives in LDS buffer t & 1; one barrier per tile.  At the top of step t the K and V
         // tiles t+1 (loaded into registers during step t-1) go into the other buffer (K quantized on the way) and the
-        // loads of tile t+2 start; then the wave computes tile t.  The last step stages the first tile of the band loop.
+        // loads of tile t+2 start; then the wave computes tile t.
         // (Direct global-to-LDS loads are not used for V: the compiler orders every later LDS access behind them with
         // a full vmcnt(0) wait, which exposes the memory latency.  On this GPU the MFMA pipe and the floating-point
         // VALU of a SIMD do not run concurrently, so the two waves of a SIMD are only there to hide LDS and memory
         // latency, not to overlap matrix and softmax work.)
+        // K of tile t+2 is requested in the middle of the score part (after its MFMAs), V after it: the two bursts of
+        // requests (every wave of the workgroup issues them at about the same point) are half as long, and the matrix
+        // part of the score has 32 registers more.
+        //
+        // Main loop: the tiles that are Phase 1 and below the diagonal for every wave.
         for (int t = 0; t < n_main; ++t) {
             const int buf = t & 1;
             if (t + 1 < n_main) {
                 stage_k<C, LO>(kreg, klo_at(buf ^ 1), kslo_at(buf ^ 1), tid);
                 stage_v<C>(vreg, v_at(buf ^ 1), tid);
             } else {
-                stage_band_tile<C, LO, HI>(kreg, vreg, t + 1, last, band, klo_at(buf ^ 1), kslo_at(buf ^ 1), khi_at, kshi_at,
-                                           v_at(buf ^ 1), tid);
+                stage_band_tile<C, LO, HI>(kreg, vreg, t + 1, last, band, klo_at(buf ^ 1), kslo_at(buf ^ 1), khi_at(buf ^ 1),
+                                           kshi_at(buf ^ 1), v_at(buf ^ 1), tid);
             }
-            // K of tile t+2 is requested before the score part, V after it: the two bursts of requests (every wave of the
-            // workgroup issues them at the same point) are half as long, and the score part has 16 registers more
-            if (t + 2 <= n_main) load_tile<C>(kreg, khead + (int64_t)(t + 2) * BT * D, tid);
-            score_part<C, LO, false>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), false, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
-            if (t + 2 <= n_main) load_tile<C>(vreg, vhead + (int64_t)(t + 2) * BT * D, tid);
+            score_part<C, LO, false>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), false, qrow_in_tile, lane, c, m, mfloor, l, o, pb,
+                                     [&] { if (t + 2 <= last) load_tile<C>(kreg, khead + (int64_t)(t + 2) * BT * D, tid); });
+            if (t + 2 <= last) load_tile<C>(vreg, vhead + (int64_t)(t + 2) * BT * D, tid);
             value_part<C>(v_at(buf), lane, o, pb);
             __syncthreads();
         }
 
-        // ---- band loop: the tiles around the diagonal.  Per wave: skipped (past its diagonal), Phase 1 or Phase 2,
-        // masked on its diagonal tile.  Tile jt is in LDS (V and low-format K in buffer jt & 1, high-format K in its
-        // single buffer) when an iteration starts; the loads of tile jt+1 are issued between the score and the value
-        // part, when few registers are live, and staged after the barrier that ends the iteration.
-        {
-            v4i qr_hi[QRHI];
-            int qs_hi = 0;
-            if constexpr (TWO) {
-                if (band > 0) load_q<C, HI>(qr_hi, qs_hi, qhead, qrow, lane & 31, lane >> 5, c);
-            }
-            for (int jt = n_main; jt <= last; ++jt) {
-                const int buf = jt & 1;
-                const bool active = jt <= it;
-                if (active) {
-                    if (jt < lo_end) {
-                        score_part<C, LO, true>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), jt == it, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
-                    } else if constexpr (TWO) {
-                        score_part<C, HI, true>(qr_hi, qs_hi, khi_at, kshi_at, jt == it, qrow_in_tile, lane, c, m, mfloor, l, o, pb);
-                    }
-                }
-                if (jt < last) {
-                    load_tile<C>(kreg, khead + (int64_t)(jt + 1) * BT * D, tid);
-                    load_tile<C>(vreg, vhead + (int64_t)(jt + 1) * BT * D, tid);
-                }
-                if (active) value_part<C>(v_at(buf), lane, o, pb);
-                __syncthreads();
-                if (jt < last) {
-                    stage_band_tile<C, LO, HI>(kreg, vreg, jt + 1, last, band, klo_at(buf ^ 1), kslo_at(buf ^ 1), khi_at, kshi_at,
-                                               v_at(buf ^ 1), tid);
-                    __syncthreads();
+        // Band loop: the tiles around the diagonal, same pipeline.  Per wave a tile is skipped (past the wave's
+        // diagonal), Phase 1 or Phase 2, and masked on the wave's diagonal tile.
+        for (int jt = n_main; jt <= last; ++jt) {
+            const int buf = jt & 1;
+            const bool active = jt <= it;
+            if (jt < last)
+                stage_band_tile<C, LO, HI>(kreg, vreg, jt + 1, last, band, klo_at(buf ^ 1), kslo_at(buf ^ 1), khi_at(buf ^ 1),
+                                           kshi_at(buf ^ 1), v_at(buf ^ 1), tid);
+            if (active) {
+                if (jt < lo_end) {
+                    score_part<C, LO, true>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), jt == it, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
+                } else if constexpr (TWO) {
+                    score_part<C, HI, true>(qr_hi, qs_hi, khi_at(buf), kshi_at(buf), jt == it, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
                 }
             }
+            if (jt + 2 <= last) {
+                load_tile<C>(kreg, khead + (int64_t)(jt + 2) * BT * D, tid);
+                load_tile<C>(vreg, vhead + (int64_t)(jt + 2) * BT * D, tid);
+            }
+            if (active) value_part<C>(v_at(buf), lane, o, pb);
+            __syncthreads();
         }
 
         // ---- O / l, transposed through LDS (free after the barrier above) so that every output row leaves as whole
