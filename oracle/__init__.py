@@ -17,6 +17,7 @@ import numpy as np
 FMT_BF16 = 0
 FMT_E4M3 = 1
 FMT_E2M1 = 2
+FMT_E5M2 = 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dma_oracle.c")
@@ -53,6 +54,10 @@ def lib() -> ctypes.CDLL:
         L.oracle_e4m3_decode.argtypes = [ctypes.c_uint8]
         L.oracle_e4m3_encode.restype = ctypes.c_uint8
         L.oracle_e4m3_encode.argtypes = [ctypes.c_double, ctypes.c_int]
+        L.oracle_e5m2_decode.restype = ctypes.c_double
+        L.oracle_e5m2_decode.argtypes = [ctypes.c_uint8]
+        L.oracle_e5m2_encode.restype = ctypes.c_uint8
+        L.oracle_e5m2_encode.argtypes = [ctypes.c_double, ctypes.c_int]
         L.oracle_e8m0_from_amax.restype = ctypes.c_uint8
         L.oracle_e8m0_from_amax.argtypes = [ctypes.c_float, ctypes.c_int]
         L.oracle_query_prescale.restype = ctypes.c_float
@@ -65,9 +70,17 @@ def lib() -> ctypes.CDLL:
         L.oracle_dma_attn_rows.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_int, ctypes.c_int, ctypes.c_int, i64p, ctypes.c_int64, f32p]
+        L.oracle_dma_attn_rows_ex.restype = ctypes.c_int
+        L.oracle_dma_attn_rows_ex.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              i64p, ctypes.c_int64, f32p]
         L.oracle_ref_attn_rows.restype = ctypes.c_int
         L.oracle_ref_attn_rows.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_int64, ctypes.c_int, i64p, ctypes.c_int64, f64p]
+        L.oracle_ref_attn_rows_ex.restype = ctypes.c_int
+        L.oracle_ref_attn_rows_ex.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_int64, ctypes.c_int, ctypes.c_int, i64p, ctypes.c_int64, f64p]
         L.oracle_num_threads.restype = ctypes.c_int
         L.oracle_num_threads.argtypes = []
         _lib = L
@@ -118,6 +131,15 @@ def e4m3_decode(code: int) -> float:
     return float(lib().oracle_e4m3_decode(int(code)))
 
 
+def e5m2_encode(y: float) -> int:
+    neg = 1 if np.signbit(y) else 0
+    return int(lib().oracle_e5m2_encode(float(y), neg))
+
+
+def e5m2_decode(code: int) -> float:
+    return float(lib().oracle_e5m2_decode(int(code)))
+
+
 def e8m0_from_amax(amax: float, fmt: int) -> int:
     return int(lib().oracle_e8m0_from_amax(float(np.float32(amax)), int(fmt)))
 
@@ -165,18 +187,20 @@ def sort_rows(rows) -> np.ndarray:
 
 
 def dma_attn_rows(q_bits, k_bits, v_bits, rows, *, tile: int, band: int, hi_fmt: int = FMT_E4M3,
-                  lo_fmt: int = FMT_E2M1, p_round: bool = True) -> np.ndarray:
-    """Diagonal-tiled attention output for the given (b, hq, i) rows -> float32 [n_rows, D]."""
+                  lo_fmt: int = FMT_E2M1, p_round: bool = True, sink: int = 0, causal: bool = True) -> np.ndarray:
+    """Diagonal-tiled attention output for the given (b, hq, i) rows -> float32 [n_rows, D].
+    sink: number of leading key tiles kept in the high format; causal=False: every key tile is visited and the
+    high-precision window is |jt - it| < band."""
     q, k, v = _as_bits(q_bits), _as_bits(k_bits), _as_bits(v_bits)
     B, Hq, S, D = q.shape
     Hkv = k.shape[1]
     assert k.shape == (B, Hkv, S, D) and v.shape == k.shape
     r = np.ascontiguousarray(np.asarray(rows, dtype=np.int64).reshape(-1, 3))
     out = np.empty((r.shape[0], D), dtype=np.float32)
-    _check(lib().oracle_dma_attn_rows(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
-                                      B, Hq, Hkv, S, D, tile, band, hi_fmt, lo_fmt, int(bool(p_round)),
-                                      _p(r, ctypes.c_int64), r.shape[0], _p(out, ctypes.c_float)),
-           "oracle_dma_attn_rows")
+    _check(lib().oracle_dma_attn_rows_ex(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
+                                         B, Hq, Hkv, S, D, tile, band, int(sink), int(bool(causal)), hi_fmt, lo_fmt,
+                                         int(bool(p_round)), _p(r, ctypes.c_int64), r.shape[0],
+                                         _p(out, ctypes.c_float)), "oracle_dma_attn_rows_ex")
     return out
 
 
@@ -191,14 +215,14 @@ def dma_attn(q_bits, k_bits, v_bits, **kw) -> np.ndarray:
     return dma_attn_rows(q_bits, k_bits, v_bits, all_rows(B, Hq, S), **kw).reshape(B, Hq, S, D)
 
 
-def ref_attn_rows(q_bits, k_bits, v_bits, rows) -> np.ndarray:
-    """Exact causal softmax attention of the unquantized inputs, float64 [n_rows, D]."""
+def ref_attn_rows(q_bits, k_bits, v_bits, rows, causal: bool = True) -> np.ndarray:
+    """Exact softmax attention of the unquantized inputs (causal or full), float64 [n_rows, D]."""
     q, k, v = _as_bits(q_bits), _as_bits(k_bits), _as_bits(v_bits)
     B, Hq, S, D = q.shape
     Hkv = k.shape[1]
     r = np.ascontiguousarray(np.asarray(rows, dtype=np.int64).reshape(-1, 3))
     out = np.empty((r.shape[0], D), dtype=np.float64)
-    _check(lib().oracle_ref_attn_rows(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
-                                      B, Hq, Hkv, S, D, _p(r, ctypes.c_int64), r.shape[0],
-                                      _p(out, ctypes.c_double)), "oracle_ref_attn_rows")
+    _check(lib().oracle_ref_attn_rows_ex(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
+                                         B, Hq, Hkv, S, D, int(bool(causal)), _p(r, ctypes.c_int64), r.shape[0],
+                                         _p(out, ctypes.c_double)), "oracle_ref_attn_rows_ex")
     return out

@@ -9,8 +9,8 @@
  * Everything after quantization is done in double.  Each function cites the passage of the
  * paper it follows (section / algorithm / equation / table).
  *
- * Formats: 0 = unquantized bf16, 1 = MXFP8 with E4M3 elements, 2 = MXFP4 with E2M1 elements;
- * MX block = 32 consecutive elements along the head dimension with one E8M0 scale byte
+ * Formats: 0 = unquantized bf16, 1 = MXFP8 with E4M3 elements, 2 = MXFP4 with E2M1 elements,
+ * 3 = MXFP8 with E5M2 elements; MX block = 32 consecutive elements along the head dimension with one E8M0 scale byte
  * (Table "Comparison of representative MXFP data formats"; Sec. 3.1).
  *
  * Readings taken where the paper is silent or inconsistent are listed at each place they are
@@ -24,6 +24,7 @@
 #define ORACLE_FMT_BF16 0
 #define ORACLE_FMT_E4M3 1
 #define ORACLE_FMT_E2M1 2
+#define ORACLE_FMT_E5M2 3
 
 #define ORACLE_OK 0
 #define ORACLE_ERR_ARG (-1)
@@ -127,12 +128,44 @@ uint8_t oracle_e4m3_encode(double y, int negative)
     return (uint8_t)((negative ? 0x80 : 0) | mag);
 }
 
+/* E5M2 decode (Table of MX formats; Sec. 4.2 "Compute shared scale": e_max = 15, i.e. exponent field 30 with
+ * bias 15; field 31 is reserved for infinities and NaN).  E = 0: M * 2^-16.  Else (1 + M/4) * 2^(E-15).
+ * Largest finite magnitude 1.75 * 2^15 = 57344 = code 0x7B. */
+double oracle_e5m2_decode(uint8_t code)
+{
+    int s = (code >> 7) & 1, e = (code >> 2) & 31, m = code & 3;
+    double a = (e == 0) ? ldexp((double)m, -16) : ldexp(1.0 + m / 4.0, e - 15);
+    return s ? -a : a;
+}
+
+/* E5M2 encode of a value already scaled and clamped to [-57344, 57344] (Alg. 2 Step 6 with the
+ * E5M2 bounds).  Reading: as for E4M3, round to nearest, ties to even, with subnormals; the
+ * reserved codes (exponent field 31) are never produced. */
+uint8_t oracle_e5m2_encode(double y, int negative)
+{
+    double a = fabs(y);
+    int mag;
+    if (a < ldexp(1.0, -14)) {
+        mag = (int)nearbyint(ldexp(a, 16));               /* 0..4; 4 is the first normal */
+    } else {
+        int ex;
+        (void)frexp(a, &ex);
+        int e = ex - 1;                                   /* -14 .. 15 */
+        int m = (int)nearbyint(4.0 * (ldexp(a, -e) - 1.0)); /* 0..4 (4 = carry) */
+        if (m == 4) { e += 1; m = 0; }
+        mag = ((e + 15) << 2) | m;
+    }
+    if (mag > 0x7B) mag = 0x7B;
+    return (uint8_t)((negative ? 0x80 : 0) | mag);
+}
+
 /* Exponent of the largest normal number of the element format (Sec. 4.2: 8 for E4M3; for E2M1
  * the largest normal is 6 = 1.5 * 2^2, so 2).  Reading: the MXFP4 copy uses the same E8M0 rule
  * as the MXFP8 copy (text of "Compute shared scale"), not the max/6 rule of Alg. 2 Step 3,
  * which is the NVFP4 flavour. */
-static int fmt_emax(int fmt) { return fmt == ORACLE_FMT_E2M1 ? 2 : 8; }
-static double fmt_maxval(int fmt) { return fmt == ORACLE_FMT_E2M1 ? 6.0 : 448.0; }
+static int fmt_emax(int fmt) { return fmt == ORACLE_FMT_E2M1 ? 2 : fmt == ORACLE_FMT_E5M2 ? 15 : 8; }
+static double fmt_maxval(int fmt) { return fmt == ORACLE_FMT_E2M1 ? 6.0 : fmt == ORACLE_FMT_E5M2 ? 57344.0 : 448.0; }
+static int fmt_is_mx(int fmt) { return fmt == ORACLE_FMT_E4M3 || fmt == ORACLE_FMT_E2M1 || fmt == ORACLE_FMT_E5M2; }
 
 /* E8M0 scale byte of a block whose absolute maximum (a binary32 value) is amax
  * (Alg. 2 Step 6: S_shared = floor(log2 amax) - e_max;  Step 7: clamp(S_shared + 127, 0, 254)).
@@ -193,6 +226,8 @@ static void quantize_row(const uint16_t *x, int D, int fmt, int is_query, uint8_
                 uint8_t cd = oracle_e2m1_encode(y, neg);
                 if (d & 1) codes[d >> 1] = (uint8_t)(codes[d >> 1] | (cd << 4));
                 else       codes[d >> 1] = cd;
+            } else if (fmt == ORACLE_FMT_E5M2) {
+                codes[d] = oracle_e5m2_encode(y, neg);
             } else {
                 codes[d] = oracle_e4m3_encode(y, neg);
             }
@@ -204,7 +239,7 @@ int oracle_mx_quantize(const uint16_t *x, int64_t rows, int D, int fmt, int is_q
                        uint8_t *codes, uint8_t *scales)
 {
     if (!x || !codes || !scales || rows < 0 || D <= 0 || D % 32 != 0) return ORACLE_ERR_ARG;
-    if (fmt != ORACLE_FMT_E4M3 && fmt != ORACLE_FMT_E2M1) return ORACLE_ERR_ARG;
+    if (!fmt_is_mx(fmt)) return ORACLE_ERR_ARG;
     const int64_t cb = (fmt == ORACLE_FMT_E2M1) ? D / 2 : D;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r)
@@ -217,7 +252,7 @@ int oracle_mx_dequantize(const uint8_t *codes, const uint8_t *scales, int64_t ro
                          double *out)
 {
     if (!codes || !scales || !out || rows < 0 || D <= 0 || D % 32 != 0) return ORACLE_ERR_ARG;
-    if (fmt != ORACLE_FMT_E4M3 && fmt != ORACLE_FMT_E2M1) return ORACLE_ERR_ARG;
+    if (!fmt_is_mx(fmt)) return ORACLE_ERR_ARG;
     const int64_t cb = (fmt == ORACLE_FMT_E2M1) ? D / 2 : D;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r) {
@@ -227,6 +262,8 @@ int oracle_mx_dequantize(const uint8_t *codes, const uint8_t *scales, int64_t ro
             if (fmt == ORACLE_FMT_E2M1) {
                 uint8_t b = codes[r * cb + (d >> 1)];
                 e = oracle_e2m1_decode((d & 1) ? (uint8_t)(b >> 4) : (uint8_t)(b & 15));
+            } else if (fmt == ORACLE_FMT_E5M2) {
+                e = oracle_e5m2_decode(codes[r * cb + d]);
             } else {
                 e = oracle_e4m3_decode(codes[r * cb + d]);
             }
@@ -274,9 +311,18 @@ static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, double 
  *   l = alpha*l + sum_j p_j;  O = alpha*O + sum_j p^_j * v_j;  finally O / l (line 12).
  *   Reading: p^_j = p_j rounded to bf16 when p_round != 0 (l sums the unrounded p_j).
  */
+/* Extensions beyond Alg. 1 (both change only which key tiles are visited and in which format):
+ *   sink  : the first `sink` key tiles are high precision for every query tile (Sec. 5.3, table
+ *           of diagonal and sink windows).
+ *   causal == 0 : every key tile is visited, nothing is masked, and the window is the tiles with
+ *           |jt - it| < band (Sec. 4.1, "Compatibility with Non-Causal Attention").
+ *   Reading: the printed tile ranges of the non-causal case mix index bases and the paper gives
+ *   no loop for the sink window; it argues that any order that covers every tile once is valid.
+ *   Here every variant visits the key tiles in ascending order, each in the format the rule
+ *   above gives it; for causal attention without a sink this is exactly Phase 1 then Phase 2. */
 static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const double *kseen_hi,
-                         const uint16_t *v, int64_t i, int D, int tile, int band, int hi_fmt,
-                         int lo_fmt, int p_round, float *out)
+                         const uint16_t *v, int64_t i, int64_t S, int D, int tile, int band, int sink,
+                         int causal, int hi_fmt, int lo_fmt, int p_round, float *out)
 {
     double q_lo[512], q_hi[512], O[512];
     double *s = (double *)malloc(sizeof(double) * (size_t)tile);
@@ -290,8 +336,10 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
     for (int d = 0; d < D; ++d) O[d] = 0.0;
 
     const int64_t it = i / tile;
-    for (int64_t jt = 0; jt <= it; ++jt) {
-        const int use_hi = (it - jt) < (int64_t)band;
+    const int64_t n_tiles = causal ? it + 1 : S / tile;
+    for (int64_t jt = 0; jt < n_tiles; ++jt) {
+        const int64_t dist = (it >= jt) ? it - jt : jt - it;
+        const int use_hi = dist < (int64_t)band || jt < (int64_t)sink;
         const double *qq = use_hi ? q_hi : q_lo;
         const double *kk = use_hi ? kseen_hi : kseen_lo;
         const double sc = use_hi ? sc_hi : sc_lo;
@@ -299,7 +347,7 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
         for (int t = 0; t < tile; ++t) {
             int64_t j = jt * tile + t;
             double acc;
-            if (j > i) {
+            if (causal && j > i) {
                 acc = -INFINITY;
             } else {
                 acc = 0.0;
@@ -316,7 +364,7 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
         for (int d = 0; d < D; ++d) O[d] *= alpha;
         for (int t = 0; t < tile; ++t) {
             int64_t j = jt * tile + t;
-            if (j > i) continue;                       /* p = 2^(-inf) = 0 */
+            if (causal && j > i) continue;             /* p = 2^(-inf) = 0 */
             double p = exp2(s[t] - mnew);
             psum += p;
             double ph = p_round ? oracle_round_to_bf16(p) : p;
@@ -346,17 +394,19 @@ static double *keys_as_seen(const uint16_t *k, int64_t n, int D, int fmt)
  * of `rows`.  tile = B_M = B_N; band = T / B_N (0: every tile low; >= S/tile: every tile high).
  * Rows should be grouped by (b, kv head) for speed; any order is correct.
  */
-int oracle_dma_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq,
-                         int Hkv, int64_t S, int D, int tile, int band, int hi_fmt, int lo_fmt,
-                         int p_round, const int64_t *rows, int64_t n_rows, float *out)
+int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq,
+                            int Hkv, int64_t S, int D, int tile, int band, int sink, int causal,
+                            int hi_fmt, int lo_fmt, int p_round, const int64_t *rows, int64_t n_rows,
+                            float *out)
 {
     if (!q || !k || !v || !out || (!rows && n_rows > 0)) return ORACLE_ERR_ARG;
+    if (sink < 0 || (!causal && S % tile != 0)) return ORACLE_ERR_ARG;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || S <= 0 || D <= 0 || D % 32 != 0 || D > 512)
         return ORACLE_ERR_ARG;
     if (tile <= 0 || band < 0) return ORACLE_ERR_ARG;
     for (int f = 0; f < 2; ++f) {
         int fm = f ? hi_fmt : lo_fmt;
-        if (fm != ORACLE_FMT_BF16 && fm != ORACLE_FMT_E4M3 && fm != ORACLE_FMT_E2M1) return ORACLE_ERR_ARG;
+        if (fm != ORACLE_FMT_BF16 && !fmt_is_mx(fm)) return ORACLE_ERR_ARG;
     }
     for (int64_t r = 0; r < n_rows; ++r) {
         if (rows[3 * r] < 0 || rows[3 * r] >= B || rows[3 * r + 1] < 0 || rows[3 * r + 1] >= Hq ||
@@ -373,6 +423,7 @@ int oracle_dma_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v
             if (rows[3 * r1 + 2] > imax) imax = rows[3 * r1 + 2];
             ++r1;
         }
+        if (!causal) imax = S - 1;
         const uint16_t *kh = k + ((int64_t)b * Hkv + hkv) * S * D;
         const uint16_t *vh = v + ((int64_t)b * Hkv + hkv) * S * D;
         double *klo = keys_as_seen(kh, imax + 1, D, lo_fmt);
@@ -382,7 +433,7 @@ int oracle_dma_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v
         for (int64_t r = r0; r < r1; ++r) {
             const int64_t hq = rows[3 * r + 1], i = rows[3 * r + 2];
             const uint16_t *qrow = q + (((int64_t)b * Hq + hq) * S + i) * D;
-            attn_one_row(qrow, klo, khi, vh, i, D, tile, band, hi_fmt, lo_fmt, p_round, out + r * D);
+            attn_one_row(qrow, klo, khi, vh, i, S, D, tile, band, sink, causal, hi_fmt, lo_fmt, p_round, out + r * D);
         }
         if (khi != klo) free(khi);
         free(klo);
@@ -391,12 +442,22 @@ int oracle_dma_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v
     return ORACLE_OK;
 }
 
+/* Alg. 1 as printed: causal, no sink window. */
+int oracle_dma_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq,
+                         int Hkv, int64_t S, int D, int tile, int band, int hi_fmt, int lo_fmt,
+                         int p_round, const int64_t *rows, int64_t n_rows, float *out)
+{
+    return oracle_dma_attn_rows_ex(q, k, v, B, Hq, Hkv, S, D, tile, band, 0, 1, hi_fmt, lo_fmt, p_round, rows,
+                                   n_rows, out);
+}
+
 /* ------------------------------------------------------------------------------------------ */
-/* Exact causal softmax attention of the unquantized inputs (Sec. 3.2, eq. 1), for reporting   */
-/* the method's own error.  Natural-base softmax of q.k/sqrt(D), two passes, double.           */
+/* Exact softmax attention of the unquantized inputs (Sec. 3.2, eq. 1), causal or not, for      */
+/* reporting the method's own error.  Natural-base softmax of q.k/sqrt(D), two passes, double. */
 /* ------------------------------------------------------------------------------------------ */
-int oracle_ref_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq,
-                         int Hkv, int64_t S, int D, const int64_t *rows, int64_t n_rows, double *out)
+int oracle_ref_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq,
+                            int Hkv, int64_t S, int D, int causal, const int64_t *rows, int64_t n_rows,
+                            double *out)
 {
     if (!q || !k || !v || !out || (!rows && n_rows > 0)) return ORACLE_ERR_ARG;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || S <= 0 || D <= 0) return ORACLE_ERR_ARG;
@@ -414,10 +475,11 @@ int oracle_ref_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v
         const uint16_t *qrow = q + ((b * Hq + hq) * S + i) * D;
         const uint16_t *kh = k + (b * Hkv + hq / group) * S * D;
         const uint16_t *vh = v + (b * Hkv + hq / group) * S * D;
-        double *s = (double *)malloc(sizeof(double) * (size_t)(i + 1));
+        const int64_t jmax = causal ? i : S - 1;        /* last key this row attends to */
+        double *s = (double *)malloc(sizeof(double) * (size_t)(jmax + 1));
         if (!s) { err = 1; continue; }
         double mx = -INFINITY;
-        for (int64_t j = 0; j <= i; ++j) {
+        for (int64_t j = 0; j <= jmax; ++j) {
             double acc = 0.0;
             for (int d = 0; d < D; ++d)
                 acc += (double)oracle_bf16_to_f32(qrow[d]) * (double)oracle_bf16_to_f32(kh[j * D + d]);
@@ -427,7 +489,7 @@ int oracle_ref_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v
         double den = 0.0;
         double *o = out + r * D;
         for (int d = 0; d < D; ++d) o[d] = 0.0;
-        for (int64_t j = 0; j <= i; ++j) {
+        for (int64_t j = 0; j <= jmax; ++j) {
             double p = exp(s[j] - mx);
             den += p;
             for (int d = 0; d < D; ++d) o[d] += p * (double)oracle_bf16_to_f32(vh[j * D + d]);
@@ -436,6 +498,12 @@ int oracle_ref_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v
         free(s);
     }
     return err ? ORACLE_ERR_MEM : ORACLE_OK;
+}
+
+int oracle_ref_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq,
+                         int Hkv, int64_t S, int D, const int64_t *rows, int64_t n_rows, double *out)
+{
+    return oracle_ref_attn_rows_ex(q, k, v, B, Hq, Hkv, S, D, 1, rows, n_rows, out);
 }
 
 /* Number of OpenMP threads the loops above use (for reporting the CPU baseline). */

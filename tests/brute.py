@@ -12,6 +12,10 @@ import numpy as np
 E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
 E4M3_GRID = np.array([(m * 2.0 ** -9) if e == 0 else (1 + m / 8.0) * 2.0 ** (e - 7)
                       for e in range(16) for m in range(8)][:0x7F])
+# E5M2: bias 15, exponent field 31 reserved (infinities / NaN), so 0x7B = 57344 is the largest value.
+E5M2_GRID = np.array([(m * 2.0 ** -16) if e == 0 else (1 + m / 4.0) * 2.0 ** (e - 15)
+                      for e in range(31) for m in range(4)])
+FORMATS = {"e2m1": (E2M1_GRID, 2, 8), "e4m3": (E4M3_GRID, 8, 0x80), "e5m2": (E5M2_GRID, 15, 0x80)}
 
 
 def nearest_code(grid: np.ndarray, a: float) -> int:
@@ -45,7 +49,7 @@ def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
 def quantize_block(x32: np.ndarray, fmt: str):
     """One MX block (32 float32 values, already pre-scaled if a query).
     Returns (scale_byte, codes[32] with sign bit, decoded float64[32])."""
-    grid, emax, signbit = (E2M1_GRID, 2, 8) if fmt == "e2m1" else (E4M3_GRID, 8, 0x80)
+    grid, emax, signbit = FORMATS[fmt]
     amax = float(np.max(np.abs(x32)))
     if amax == 0.0:
         sb = 0
@@ -102,12 +106,13 @@ def round_bf16_nearest_of_two(p: np.ndarray) -> np.ndarray:
     return out
 
 
-def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p_round=True):
+def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p_round=True, sink=0, causal=True):
     """Per-element rewrite of the diagonal-tiled attention for q[Hq,S,D], k,v[Hkv,S,D] (one batch).
 
-    For every (i, j <= i) the score comes from the format of the tile pair (i // tile, j // tile);
-    with p_round the probabilities are formed against the running maximum over key-tile prefixes
-    and rounded to bf16, otherwise it is a plain base-2 row softmax."""
+    For every visible pair (i, j) the score comes from the format of the tile pair (i // tile, j // tile):
+    high when the tiles are closer than `band` or the key tile is one of the first `sink`; with
+    p_round the probabilities are formed against the running maximum over key-tile prefixes and
+    rounded to bf16, otherwise it is a plain base-2 row softmax.  causal=False: every key is visible."""
     Hq, S, D = q_bits.shape
     Hkv = k_bits.shape[0]
     g = Hq // Hkv
@@ -122,34 +127,36 @@ def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p
         s_lo = q_lo @ k_lo.T
         ti = np.arange(S)[:, None] // tile
         tj = np.arange(S)[None, :] // tile
-        s = np.where(ti - tj < band, s_hi, s_lo)
+        s = np.where((np.abs(ti - tj) < band) | (tj < sink), s_hi, s_lo)
         for i in range(S):
-            si = s[i, :i + 1]
+            nk = i + 1 if causal else S                  # keys this row sees
+            si = s[i, :nk]
             if not p_round:
                 p = np.exp2(si - si.max())
-                out[h, i] = (p @ v[h // g, :i + 1]) / p.sum()
+                out[h, i] = (p @ v[h // g, :nk]) / p.sum()
                 continue
-            nt = i // tile + 1
+            nt = (nk + tile - 1) // tile
             # running maximum after each key tile
-            run = np.array([si[:min((t + 1) * tile, i + 1)].max() for t in range(nt)])
-            mj = run[np.arange(i + 1) // tile]           # maximum in force when key j was processed
+            run = np.array([si[:min((t + 1) * tile, nk)].max() for t in range(nt)])
+            mj = run[np.arange(nk) // tile]              # maximum in force when key j was processed
             mfin = run[-1]
             p_at = np.exp2(si - mj)
             p_hat = round_bf16_nearest_of_two(p_at)
             w_num = p_hat * np.exp2(mj - mfin)
             w_den = (p_at * np.exp2(mj - mfin)).sum()
-            out[h, i] = (w_num @ v[h // g, :i + 1]) / w_den
+            out[h, i] = (w_num @ v[h // g, :nk]) / w_den
     return out
 
 
-def softmax_attention_fp64(q, k, v):
-    """Plain causal softmax attention of real-valued q[Hq,S,D], k,v[Hkv,S,D] (doubles)."""
+def softmax_attention_fp64(q, k, v, causal=True):
+    """Plain softmax attention (causal or full) of real-valued q[Hq,S,D], k,v[Hkv,S,D] (doubles)."""
     Hq, S, D = q.shape
     g = Hq // k.shape[0]
     out = np.zeros((Hq, S, D))
     for h in range(Hq):
         s = (q[h] @ k[h // g].T) / np.sqrt(D)
-        s = np.where(np.arange(S)[None, :] > np.arange(S)[:, None], -np.inf, s)
+        if causal:
+            s = np.where(np.arange(S)[None, :] > np.arange(S)[:, None], -np.inf, s)
         p = np.exp(s - s.max(axis=1, keepdims=True))
         out[h] = (p / p.sum(axis=1, keepdims=True)) @ v[h // g]
     return out

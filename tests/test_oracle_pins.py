@@ -340,3 +340,125 @@ def test_error_trend_with_band(oracle):
     assert all(errs[i + 1] <= errs[i] * 1.05 for i in range(len(errs) - 1)), errs
     all8 = oracle.dma_attn_rows(q, k, v, rows, tile=128, band=8)
     assert float(np.sqrt(np.mean((all8 - ref) ** 2))) < 0.5 * errs[0]
+
+
+# ------------------------------------------------------------------ E5M2 (Sec. 4.2: e_max = 15)
+
+def test_e5m2_codes_roundtrip_and_fixed_points(oracle):
+    for code in list(range(0x7C)) + list(range(0x80, 0xFC)):
+        v = oracle.e5m2_decode(code)
+        assert abs(v) == brute.E5M2_GRID[code & 0x7F]
+        assert oracle.e5m2_encode(v) == code
+    assert oracle.e5m2_decode(0x7B) == 57344.0 and oracle.e5m2_encode(57344.0) == 0x7B
+    assert oracle.e5m2_decode(0x3C) == 1.0 and oracle.e5m2_decode(0x04) == 2.0 ** -14
+    assert oracle.e5m2_encode(2.0 ** -16) == 0x01
+    assert oracle.e5m2_encode(2.0 ** -17) == 0x00          # tie between 0 and 2^-16 -> even
+    assert oracle.e5m2_encode(3 * 2.0 ** -17) == 0x02      # tie between codes 1 and 2 -> even
+    assert oracle.e5m2_encode(-(2.0 ** -20)) == 0x80       # negative underflow keeps the sign
+    assert oracle.e5m2_encode(1.125) == 0x3C               # tie 1.0 / 1.25 -> even mantissa
+    assert oracle.e5m2_encode(1.375) == 0x3E               # tie 1.25 / 1.5 -> even mantissa
+    assert oracle.e5m2_encode(1.9) == 0x40                 # rounds up across the binade
+    assert oracle.e5m2_encode(61440.0) == 0x7B             # would round past the top: saturates
+
+
+def test_e5m2_bruteforce_all_bf16(oracle):
+    bits, vals = all_bf16_in(-57344.0, 57344.0)
+    rng = np.random.default_rng(3)
+    idx = np.unique(np.concatenate([rng.choice(len(bits), 6000, replace=False),
+                                    np.flatnonzero(np.abs(vals) >= 2.0 ** -18)[::5]]))
+    for i in idx:
+        b, v = bits[i], vals[i]
+        want = brute.nearest_code(brute.E5M2_GRID, abs(v)) | (0x80 if (b & 0x8000) else 0)
+        assert oracle.e5m2_encode(float(v)) == want, (hex(b), v)
+
+
+def test_e5m2_shared_scale_and_blocks(oracle):
+    for k in (-20, -3, 0, 1, 7, 40):
+        assert oracle.e8m0_from_amax(57344.0 * 2.0 ** k, oracle.FMT_E5M2) == 127 + k
+        assert oracle.e8m0_from_amax(32768.0 * 2.0 ** k, oracle.FMT_E5M2) == 127 + k
+        assert oracle.e8m0_from_amax(32767.0 * 2.0 ** k, oracle.FMT_E5M2) == 126 + k
+    assert oracle.e8m0_from_amax(1.0, oracle.FMT_E5M2) == 112
+    assert oracle.e8m0_from_amax(0.0, oracle.FMT_E5M2) == 0
+    w = wl.CONFIGS["tiny"]
+    q, k, _ = wl.generate(w)
+    for x, is_q in ((q[0, 0, :24], True), (k[0, 1, 100:124], False)):
+        codes, scales = oracle.mx_quantize(x, oracle.FMT_E5M2, is_q)
+        bs, bc, bd = brute.quantize_rows(x, "e5m2", is_q)
+        assert np.array_equal(scales, bs) and np.array_equal(codes, bc)
+        assert np.array_equal(oracle.mx_dequantize(codes, scales, oracle.FMT_E5M2), bd)
+    # 60000 lies in (57344, 65536): scale 127, the element saturates to the largest finite code
+    x = np.zeros((1, 32), dtype=np.float32)
+    x[0, 0] = 60000.0
+    codes, scales = oracle.mx_quantize(wl.f32_to_bf16_bits(x), oracle.FMT_E5M2, False)
+    assert scales[0, 0] == 127 and codes[0, 0] == 0x7B
+
+
+# ------------------------------------------------------------------ sink window and non-causal attention
+
+@pytest.mark.parametrize("band,sink", [(0, 1), (1, 1), (1, 2), (2, 3)])
+@pytest.mark.parametrize("p_round", [False, True])
+def test_sink_window_matches_per_element_rewrite(oracle, tiny, band, sink, p_round):
+    w, q, k, v = tiny
+    got = oracle.dma_attn(q, k, v, tile=w.tile, band=band, sink=sink, p_round=p_round)[0]
+    want = brute.dma_attention(q[0], k[0], v[0], tile=w.tile, band=band, sink=sink, p_round=p_round)
+    assert np.max(np.abs(got - want)) < 2e-6
+
+
+def test_sink_window_limits(oracle, tiny):
+    w, q, k, v = tiny
+    n = w.S // w.tile
+    for band in (0, 1):
+        assert np.array_equal(oracle.dma_attn(q, k, v, tile=w.tile, band=band, sink=0),
+                              oracle.dma_attn(q, k, v, tile=w.tile, band=band))
+    # a sink covering every tile == the high format everywhere, whatever the band
+    all_hi = oracle.dma_attn(q, k, v, tile=w.tile, band=n)
+    assert np.array_equal(all_hi, oracle.dma_attn(q, k, v, tile=w.tile, band=0, sink=n))
+    # sink and band together covering every tile of this 4-tile problem
+    assert np.array_equal(all_hi, oracle.dma_attn(q, k, v, tile=w.tile, band=2, sink=2))
+    # the sink changes something when it is not covered by the band
+    assert not np.array_equal(oracle.dma_attn(q, k, v, tile=w.tile, band=1, sink=1),
+                              oracle.dma_attn(q, k, v, tile=w.tile, band=1))
+
+
+def test_noncausal_reference_and_skeleton_against_sdpa(oracle, tiny):
+    w, q, k, v = tiny
+    tq, tk, tv = (torch.from_numpy(wl.bf16_bits_to_f32(a)).double() for a in (q, k, v))
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=False).numpy()
+    rows = oracle.all_rows(w.B, w.Hq, w.S)
+    got = oracle.ref_attn_rows(q, k, v, rows, causal=False).reshape(w.B, w.Hq, w.S, w.D)
+    assert np.max(np.abs(got - want)) < 1e-12
+    for tile in (32, 64):
+        for band in (0, 2):
+            got = oracle.dma_attn(q, k, v, tile=tile, band=band, hi_fmt=oracle.FMT_BF16, lo_fmt=oracle.FMT_BF16,
+                                  p_round=False, causal=False)
+            assert np.max(np.abs(got - want)) < 2e-6
+
+
+@pytest.mark.parametrize("band,sink", [(0, 0), (1, 0), (2, 0), (1, 1), (3, 0)])
+@pytest.mark.parametrize("p_round", [False, True])
+def test_noncausal_mixed_tiles_match_per_element_rewrite(oracle, tiny, band, sink, p_round):
+    w, q, k, v = tiny
+    got = oracle.dma_attn(q, k, v, tile=w.tile, band=band, sink=sink, p_round=p_round, causal=False)[0]
+    want = brute.dma_attention(q[0], k[0], v[0], tile=w.tile, band=band, sink=sink, p_round=p_round, causal=False)
+    assert np.max(np.abs(got - want)) < 2e-6
+
+
+def test_noncausal_window_is_symmetric(oracle, tiny):
+    """Window |jt - it| < band: with 4 tiles, band 4 covers everything (== all high); band 1 differs from the
+    causal window only by visiting the upper tiles, so the first query tile already sees all keys."""
+    w, q, k, v = tiny
+    n = w.S // w.tile
+    all_hi = oracle.dma_attn(q, k, v, tile=w.tile, band=n, causal=False)
+    assert np.array_equal(all_hi, oracle.dma_attn(q, k, v, tile=w.tile, band=0, hi_fmt=oracle.FMT_E4M3,
+                                                  lo_fmt=oracle.FMT_E4M3, causal=False))
+    vc = np.broadcast_to(v[:, :, :1, :], v.shape).copy()
+    out = oracle.dma_attn(q, k, vc, tile=w.tile, band=1, p_round=False, causal=False)
+    want = np.broadcast_to(wl.bf16_bits_to_f32(vc)[:, :, :1, :], out.shape)
+    assert np.max(np.abs(out - want)) < 1e-6
+
+
+def test_e5m2_high_format_in_attention(oracle, tiny):
+    w, q, k, v = tiny
+    got = oracle.dma_attn(q, k, v, tile=w.tile, band=1, hi_fmt=oracle.FMT_E5M2)[0]
+    want = brute.dma_attention(q[0], k[0], v[0], tile=w.tile, band=1, hi="e5m2")
+    assert np.max(np.abs(got - want)) < 2e-6
