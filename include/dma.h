@@ -35,7 +35,8 @@ enum {
 enum {
     DMA_FMT_BF16 = 0,           /* no quantization: plain bf16 operands */
     DMA_FMT_MXFP8_E4M3 = 1,     /* FP8 E4M3 elements + E8M0 scale per 32 */
-    DMA_FMT_MXFP4_E2M1 = 2      /* FP4 E2M1 elements (two per byte) + E8M0 scale per 32 */
+    DMA_FMT_MXFP4_E2M1 = 2,     /* FP4 E2M1 elements (two per byte) + E8M0 scale per 32 */
+    DMA_FMT_MXFP8_E5M2 = 3      /* FP8 E5M2 elements + E8M0 scale per 32 (Sec. 4.2: e_max = 15) */
 };
 
 /*
@@ -45,14 +46,14 @@ enum {
  *
  *   x_bf16   [rows, D] bf16, device, read only.  16-byte aligned.
  *   rows     >= 0 (0 is a no-op).   D: multiple of 32, 32 <= D <= 1024.
- *   fmt      DMA_FMT_MXFP8_E4M3 or DMA_FMT_MXFP4_E2M1.
+ *   fmt      DMA_FMT_MXFP8_E4M3, DMA_FMT_MXFP8_E5M2 or DMA_FMT_MXFP4_E2M1.
  *   is_query non-zero: every element is first multiplied by log2(e)/sqrt(D) in one binary32
  *            multiplication (Alg. 2 Step 1).
- *   codes_u8 out, device.  E4M3: [rows, D] bytes.  E2M1: [rows, D/2] bytes, element 2t in the low
+ *   codes_u8 out, device.  E4M3, E5M2: [rows, D] bytes.  E2M1: [rows, D/2] bytes, element 2t in the low
  *            nibble and 2t+1 in the high nibble (Alg. 2 Step 5).
  *   scales_u8 out, device, [rows, D/32] bytes: clamp(floor(log2 max|block|) - e_max + 127, 0, 254)
- *            with e_max = 8 (E4M3) or 2 (E2M1) (Alg. 2 Steps 6-7); an all-zero block gives 0.
- *   Element = round-to-nearest-even of x / 2^(scale-127) after clamping to +-448 / +-6; the sign bit
+ *            with e_max = 8 (E4M3), 15 (E5M2) or 2 (E2M1) (Alg. 2 Steps 6-7); an all-zero block gives 0.
+ *   Element = round-to-nearest-even of x / 2^(scale-127) after clamping to +-448 / +-57344 / +-6; the sign bit
  *   is the sign bit of x even when the magnitude rounds to zero.
  */
 int dma_mx_quantize(const void* x_bf16, int64_t rows, int D, int fmt, int is_query,
@@ -70,13 +71,16 @@ int dma_mx_quantize_dual(const void* x_bf16, int64_t rows, int D, int is_query,
  *
  *   q   [B, Hq,  S, D] bf16      k, v [B, Hkv, S, D] bf16      out [B, Hq, S, D] float32
  *   All device, dense, 16-byte aligned.  Hq % Hkv == 0; query head h reads kv head h / (Hq/Hkv).
- *   causal            must be non-zero (the non-causal variant is not built: DMA_ERR_UNSUPPORTED).
- *   diag_band_tiles   b = T / B_N >= 0.  For the query tile `it`, key tile `jt` (jt <= it) is computed
- *                     in hi_fmt iff it - jt < b, otherwise in lo_fmt.  b = 0: every tile in lo_fmt;
- *                     b >= S/tile: every tile in hi_fmt.
+ *   causal            non-zero: Alg. 1 (key tiles jt <= it, keys after the query masked on the diagonal tile).
+ *                     zero: every key tile is visited and nothing is masked (Sec. 4.1, "Compatibility with
+ *                     Non-Causal Attention").
+ *   diag_band_tiles   b = T / B_N >= 0.  For the query tile `it`, key tile `jt` is computed in hi_fmt iff
+ *                     it - jt < b (causal) or |it - jt| < b (non-causal), otherwise in lo_fmt.  b = 0: every
+ *                     tile in lo_fmt; b >= S/tile: every tile in hi_fmt.
  *   hi_fmt, lo_fmt    DMA_FMT_* for the Q K^T product of the tiles in / outside the diagonal band.
- *                     Supported pairs (lo, hi): (E2M1, E4M3), (E2M1, E2M1), (E4M3, E4M3), (BF16, BF16);
- *                     any other pair returns DMA_ERR_UNSUPPORTED.
+ *                     Supported pairs (lo, hi): (E2M1, E4M3), (E2M1, E5M2), (E2M1, E2M1), (E4M3, E4M3),
+ *                     (E5M2, E5M2), (BF16, BF16); any other pair returns DMA_ERR_UNSUPPORTED.
+ *   Key tiles are visited in ascending order in every variant.
  *   The logical tile is B_M = B_N = 128 for dma_attn_fwd; D must be 128 and S a multiple of 128.
  *
  *   Per key tile: scores in base 2 (the factor log2(e)/sqrt(D) is folded into Q before quantization;
@@ -92,7 +96,8 @@ int dma_attn_fwd(const void* q, const void* k, const void* v, void* out,
 /* Options for dma_attn_fwd_ex.  Zero-initialise, then set fields. */
 typedef struct dma_attn_opts {
     int tile;             /* logical tile B_M = B_N: 128 (with D = 128) or 64 (with D = 64); 0 = 128 */
-    int sink_tiles;       /* must be 0 (a high-precision sink window is not built) */
+    int sink_tiles;       /* >= 0: the first sink_tiles key tiles are computed in hi_fmt for every query tile (Sec. 5.3,
+                             the sink window of the diagonal/sink table); 0 = Alg. 1 as printed */
     int pv_fmt;           /* must be DMA_FMT_BF16 (V and P stay 16-bit, as in Alg. 1) */
     int per_token_scale;  /* must be 0 (Alg. 2 Step 2 is the identity on this path) */
     int fp8_mfma;         /* how MXFP8 tiles form Q K^T.

@@ -74,7 +74,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_dma_attn_rows_ex.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                              i64p, ctypes.c_int64, f32p]
+                                              i64p, ctypes.c_int64, f32p, f32p]
         L.oracle_ref_attn_rows.restype = ctypes.c_int
         L.oracle_ref_attn_rows.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_int64, ctypes.c_int, i64p, ctypes.c_int64, f64p]
@@ -187,21 +187,26 @@ def sort_rows(rows) -> np.ndarray:
 
 
 def dma_attn_rows(q_bits, k_bits, v_bits, rows, *, tile: int, band: int, hi_fmt: int = FMT_E4M3,
-                  lo_fmt: int = FMT_E2M1, p_round: bool = True, sink: int = 0, causal: bool = True) -> np.ndarray:
+                  lo_fmt: int = FMT_E2M1, p_round: bool = True, sink: int = 0, causal: bool = True,
+                  with_slack: bool = False):
     """Diagonal-tiled attention output for the given (b, hq, i) rows -> float32 [n_rows, D].
     sink: number of leading key tiles kept in the high format; causal=False: every key tile is visited and the
-    high-precision window is |jt - it| < band."""
+    high-precision window is |jt - it| < band.  with_slack: also return, per output element, how far the
+    value can move when probabilities that lie within binary32 score noise of a bf16 rounding midpoint round
+    the other way (see attn_one_row in dma_oracle.c)."""
     q, k, v = _as_bits(q_bits), _as_bits(k_bits), _as_bits(v_bits)
     B, Hq, S, D = q.shape
     Hkv = k.shape[1]
     assert k.shape == (B, Hkv, S, D) and v.shape == k.shape
     r = np.ascontiguousarray(np.asarray(rows, dtype=np.int64).reshape(-1, 3))
     out = np.empty((r.shape[0], D), dtype=np.float32)
+    slack = np.zeros((r.shape[0], D), dtype=np.float32) if with_slack else None
     _check(lib().oracle_dma_attn_rows_ex(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
                                          B, Hq, Hkv, S, D, tile, band, int(sink), int(bool(causal)), hi_fmt, lo_fmt,
                                          int(bool(p_round)), _p(r, ctypes.c_int64), r.shape[0],
-                                         _p(out, ctypes.c_float)), "oracle_dma_attn_rows_ex")
-    return out
+                                         _p(out, ctypes.c_float), _p(slack, ctypes.c_float) if with_slack else None),
+           "oracle_dma_attn_rows_ex")
+    return (out, slack) if with_slack else out
 
 
 def all_rows(B: int, Hq: int, S: int) -> np.ndarray:

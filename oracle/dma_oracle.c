@@ -320,11 +320,19 @@ static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, double 
  *   no loop for the sink window; it argues that any order that covers every tile once is valid.
  *   Here every variant visits the key tiles in ascending order, each in the format the rule
  *   above gives it; for causal attention without a sink this is exactly Phase 1 then Phase 2. */
+/* Rounding slack (optional output, for the parity tests).  Rounding p to bf16 is a decision taken on
+ * a floating-point value; an implementation that forms the score in binary32 sees a p that differs
+ * from the double-precision p by about p * ln2 * |ds|, |ds| a few binary32 units of the score's
+ * magnitude, and legitimately rounds the other way when p lies that close to the midpoint of two
+ * bf16 numbers.  Such a flip moves the numerator of output d by one bf16 spacing of p times v_jd and
+ * leaves l alone.  slack[d] = sum over the keys whose p lies within 2^-20 * (|s_j| + |m| + 1) * ln2 * p
+ * of a midpoint of (spacing_j * |v_jd|), carried through the rescaling like O, divided by l: the most
+ * the output can move through flips that binary32 scores can cause. */
 static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const double *kseen_hi,
                          const uint16_t *v, int64_t i, int64_t S, int D, int tile, int band, int sink,
-                         int causal, int hi_fmt, int lo_fmt, int p_round, float *out)
+                         int causal, int hi_fmt, int lo_fmt, int p_round, float *out, float *slack)
 {
-    double q_lo[512], q_hi[512], O[512];
+    double q_lo[512], q_hi[512], O[512], SL[512];
     double *s = (double *)malloc(sizeof(double) * (size_t)tile);
     row_as_seen(qrow, D, lo_fmt, 1, q_lo);
     row_as_seen(qrow, D, hi_fmt, 1, q_hi);
@@ -333,7 +341,7 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
     const double sc_hi = (hi_fmt == ORACLE_FMT_BF16) ? c : 1.0;
 
     double m = -INFINITY, l = 1.0;
-    for (int d = 0; d < D; ++d) O[d] = 0.0;
+    for (int d = 0; d < D; ++d) { O[d] = 0.0; SL[d] = 0.0; }
 
     const int64_t it = i / tile;
     const int64_t n_tiles = causal ? it + 1 : S / tile;
@@ -361,7 +369,7 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
         const double mnew = (tmax > m) ? tmax : m;
         const double alpha = exp2(m - mnew);
         double psum = 0.0;
-        for (int d = 0; d < D; ++d) O[d] *= alpha;
+        for (int d = 0; d < D; ++d) { O[d] *= alpha; SL[d] *= alpha; }
         for (int t = 0; t < tile; ++t) {
             int64_t j = jt * tile + t;
             if (causal && j > i) continue;             /* p = 2^(-inf) = 0 */
@@ -370,11 +378,25 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
             double ph = p_round ? oracle_round_to_bf16(p) : p;
             const uint16_t *vr = v + j * D;
             for (int d = 0; d < D; ++d) O[d] += ph * (double)oracle_bf16_to_f32(vr[d]);
+            if (slack && p_round && p > 0.0) {
+                int ex;
+                (void)frexp(p, &ex);
+                int quantum = (ex - 1) - 7;
+                if (quantum < -133) quantum = -133;
+                const double sp = ldexp(1.0, quantum);                 /* spacing of bf16 numbers at p */
+                const double r = p / sp;
+                const double dist = fabs(r - floor(r) - 0.5) * sp;     /* distance of p to the nearest midpoint */
+                const double eps = ldexp(fabs(s[t]) + fabs(mnew) + 1.0, -20) * 0.6931471805599453 * p;
+                if (dist <= eps)
+                    for (int d = 0; d < D; ++d) SL[d] += sp * fabs((double)oracle_bf16_to_f32(vr[d]));
+            }
         }
         l = alpha * l + psum;
         m = mnew;
     }
     for (int d = 0; d < D; ++d) out[d] = (float)(O[d] / l);
+    if (slack)
+        for (int d = 0; d < D; ++d) slack[d] = (float)(SL[d] / l);
     free(s);
 }
 
@@ -397,7 +419,7 @@ static double *keys_as_seen(const uint16_t *k, int64_t n, int D, int fmt)
 int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq,
                             int Hkv, int64_t S, int D, int tile, int band, int sink, int causal,
                             int hi_fmt, int lo_fmt, int p_round, const int64_t *rows, int64_t n_rows,
-                            float *out)
+                            float *out, float *slack)
 {
     if (!q || !k || !v || !out || (!rows && n_rows > 0)) return ORACLE_ERR_ARG;
     if (sink < 0 || (!causal && S % tile != 0)) return ORACLE_ERR_ARG;
@@ -433,7 +455,8 @@ int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t
         for (int64_t r = r0; r < r1; ++r) {
             const int64_t hq = rows[3 * r + 1], i = rows[3 * r + 2];
             const uint16_t *qrow = q + (((int64_t)b * Hq + hq) * S + i) * D;
-            attn_one_row(qrow, klo, khi, vh, i, S, D, tile, band, sink, causal, hi_fmt, lo_fmt, p_round, out + r * D);
+            attn_one_row(qrow, klo, khi, vh, i, S, D, tile, band, sink, causal, hi_fmt, lo_fmt, p_round, out + r * D,
+                         slack ? slack + r * D : NULL);
         }
         if (khi != klo) free(khi);
         free(klo);
@@ -448,7 +471,7 @@ int oracle_dma_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v
                          int p_round, const int64_t *rows, int64_t n_rows, float *out)
 {
     return oracle_dma_attn_rows_ex(q, k, v, B, Hq, Hkv, S, D, tile, band, 0, 1, hi_fmt, lo_fmt, p_round, rows,
-                                   n_rows, out);
+                                   n_rows, out, NULL);
 }
 
 /* ------------------------------------------------------------------------------------------ */

@@ -15,6 +15,7 @@ import torch
 FMT_BF16 = 0
 FMT_MXFP8_E4M3 = 1
 FMT_MXFP4_E2M1 = 2
+FMT_MXFP8_E5M2 = 3
 
 EXPORTS = ("dma_mx_quantize", "dma_mx_quantize_dual", "dma_attn_fwd", "dma_attn_fwd_ex",
            "dma_attn_fwd_workspace_bytes", "dma_diag_copy", "dma_error_string", "dma_version")
@@ -119,9 +120,10 @@ def dma_mx_quantize_dual(x: torch.Tensor, is_query: bool, out=None):
 
 def dma_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, diag_band_tiles: int,
                  hi_fmt: int = FMT_MXFP8_E4M3, lo_fmt: int = FMT_MXFP4_E2M1, causal: bool = True,
-                 tile: int | None = None, fp8_mfma: bool = False, out: torch.Tensor | None = None) -> torch.Tensor:
-    """q [B,Hq,S,D], k/v [B,Hkv,S,D] bf16 -> out [B,Hq,S,D] float32.  With tile=None and fp8_mfma=False
-    this is dma_attn_fwd (logical tile 128); otherwise dma_attn_fwd_ex with those options."""
+                 tile: int | None = None, fp8_mfma: bool = False, sink_tiles: int = 0,
+                 out: torch.Tensor | None = None) -> torch.Tensor:
+    """q [B,Hq,S,D], k/v [B,Hkv,S,D] bf16 -> out [B,Hq,S,D] float32.  With tile=None, fp8_mfma=False and
+    sink_tiles=0 this is dma_attn_fwd (logical tile 128); otherwise dma_attn_fwd_ex with those options."""
     B, Hq, S, D = q.shape
     Hkv = k.shape[1]
     if k.shape != (B, Hkv, S, D) or v.shape != k.shape:
@@ -131,10 +133,10 @@ def dma_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, diag_band
     args = [_dev(q, torch.bfloat16, "q"), _dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v"),
             _dev(out, torch.float32, "out"), B, Hq, Hkv, S, D, int(bool(causal)), int(diag_band_tiles),
             int(hi_fmt), int(lo_fmt)]
-    if tile is None and not fp8_mfma:
+    if tile is None and not fp8_mfma and not sink_tiles:
         rc = load().dma_attn_fwd(*args, _stream())
     else:
-        opts = AttnOpts(tile=int(tile or 0), sink_tiles=0, pv_fmt=FMT_BF16, per_token_scale=0,
+        opts = AttnOpts(tile=int(tile or 0), sink_tiles=int(sink_tiles), pv_fmt=FMT_BF16, per_token_scale=0,
                         fp8_mfma=int(bool(fp8_mfma)))
         rc = load().dma_attn_fwd_ex(*args, ctypes.byref(opts), _stream())
     if rc:

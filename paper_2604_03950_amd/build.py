@@ -12,7 +12,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdma_mi355x.so")
 SOURCES = ["dma_api.hip", "dma_quantize.hip", "dma_attn_fwd.hip"]
-HEADERS = ["dma_device.hpp", "dma_internal.hpp", os.path.join("..", "..", "include", "dma.h")]
+HEADERS = ["dma_device.hpp", "dma_internal.hpp", "dma_attn_kernel.hpp", os.path.join("..", "..", "include", "dma.h")]
+# (low, high) format pairs of the fused forward, as product-path ids of dma_device.hpp: dma_attn_inst.hip is compiled
+# once per pair (the list mirrors the declarations in dma_attn_fwd.hip)
+ATTN_PAIRS = [(2, 3), (2, 1), (2, 4), (2, 2), (3, 3), (1, 1), (4, 4), (0, 0)]
+MAX_PARALLEL = 8
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -34,23 +38,28 @@ def build(force: bool = True, verbose: bool = False) -> str:
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     headers = [os.path.join(CSRC, h) for h in HEADERS]
-    procs, objs = [], []
-    for s in SOURCES:
+    jobs, objs = [], []
+    units = [(s, s.replace(".hip", ".o"), []) for s in SOURCES]
+    units += [("dma_attn_inst.hip", f"dma_attn_inst_{lo}_{hi}.o", [f"-DDMA_LO={lo}", f"-DDMA_HI={hi}"]) for lo, hi in ATTN_PAIRS]
+    for s, o, defs in units:
         src = os.path.join(CSRC, s)
-        obj = os.path.join(objdir, s.replace(".hip", ".o"))
+        obj = os.path.join(objdir, o)
         objs.append(obj)
         if force or _stale(obj, [src] + headers):
-            cmd = ["hipcc"] + HIPCC_FLAGS + ["-c", src, "-o", obj]
+            cmd = ["hipcc"] + HIPCC_FLAGS + defs + ["-c", src, "-o", obj]
             if verbose:
                 cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
-            procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+            jobs.append((o, cmd))
     failed = False
-    for s, p in procs:
-        out, _ = p.communicate()
-        lines = [ln for ln in out.splitlines() if "packed-fp32-ops" not in ln]
-        if p.returncode != 0 or verbose:
-            print(f"--- {s}\n" + "\n".join(lines), file=sys.stderr)
-        failed |= p.returncode != 0
+    while jobs:
+        batch, jobs = jobs[:MAX_PARALLEL], jobs[MAX_PARALLEL:]
+        procs = [(o, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)) for o, cmd in batch]
+        for o, p in procs:
+            out, _ = p.communicate()
+            lines = [ln for ln in out.splitlines() if "packed-fp32-ops" not in ln]
+            if p.returncode != 0 or verbose:
+                print(f"--- {o}\n" + "\n".join(lines), file=sys.stderr)
+            failed |= p.returncode != 0
     if failed:
         raise RuntimeError("hipcc failed")
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, check=True)

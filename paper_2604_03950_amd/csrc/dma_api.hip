@@ -6,7 +6,7 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-bool valid_fmt(int f) { return f == DMA_FMT_BF16 || f == DMA_FMT_MXFP8_E4M3 || f == DMA_FMT_MXFP4_E2M1; }
+bool valid_fmt(int f) { return f == DMA_FMT_BF16 || f == DMA_FMT_MXFP8_E4M3 || f == DMA_FMT_MXFP4_E2M1 || f == DMA_FMT_MXFP8_E5M2; }
 
 // rows == 0 is a no-op that never looks at the pointers (an empty tensor has none).
 int check_quant_common(const void* x, int64_t rows, int D)
@@ -29,15 +29,15 @@ int dma_mx_quantize(const void* x_bf16, int64_t rows, int D, int fmt, int is_que
 {
     int rc = check_quant_common(x_bf16, rows, D);
     if (rc != DMA_OK) return rc;
-    if (fmt != DMA_FMT_MXFP8_E4M3 && fmt != DMA_FMT_MXFP4_E2M1) return DMA_ERR_INVALID_ARG;
+    if (fmt != DMA_FMT_MXFP8_E4M3 && fmt != DMA_FMT_MXFP4_E2M1 && fmt != DMA_FMT_MXFP8_E5M2) return DMA_ERR_INVALID_ARG;
     if (rows == 0) return DMA_OK;
     if (!codes_u8 || !scales_u8) return DMA_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(codes_u8) & 7u) != 0) return DMA_ERR_INVALID_ARG;
     if (fmt == DMA_FMT_MXFP4_E2M1)
         return dma::launch_mx_quantize(x_bf16, rows, D, 2, is_query != 0, codes_u8, scales_u8, nullptr, nullptr,
                                        (hipStream_t)stream);
-    return dma::launch_mx_quantize(x_bf16, rows, D, 1, is_query != 0, nullptr, nullptr, codes_u8, scales_u8,
-                                   (hipStream_t)stream);
+    return dma::launch_mx_quantize(x_bf16, rows, D, fmt == DMA_FMT_MXFP8_E5M2 ? 4 : 1, is_query != 0, nullptr, nullptr,
+                                   codes_u8, scales_u8, (hipStream_t)stream);
 }
 
 int dma_mx_quantize_dual(const void* x_bf16, int64_t rows, int D, int is_query, void* codes_lo_u8,
@@ -65,15 +65,17 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return DMA_ERR_INVALID_ARG;
     int tile = 128;
     int fp8_mfma = 0;
+    int sink = 0;
     if (opts) {
         if (opts->fp8_mfma != 0 && opts->fp8_mfma != 1) return DMA_ERR_INVALID_ARG;
         fp8_mfma = opts->fp8_mfma;
         if (opts->tile != 0) tile = opts->tile;
         if (opts->tile < 0) return DMA_ERR_INVALID_ARG;
-        if (opts->sink_tiles != 0 || opts->per_token_scale != 0) return DMA_ERR_UNSUPPORTED;
+        if (opts->sink_tiles < 0) return DMA_ERR_INVALID_ARG;
+        sink = opts->sink_tiles;
+        if (opts->per_token_scale != 0) return DMA_ERR_UNSUPPORTED;
         if (opts->pv_fmt != DMA_FMT_BF16) return DMA_ERR_UNSUPPORTED;
     }
-    if (!causal) return DMA_ERR_UNSUPPORTED;
     if (S % tile != 0) return DMA_ERR_UNSUPPORTED;
     if ((int64_t)B * Hq * S * D > (int64_t)1 << 40) return DMA_ERR_UNSUPPORTED;
     dma::AttnArgs a;
@@ -81,9 +83,14 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
     a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.S = S; a.D = D;
     a.tile = tile;
     a.band = diag_band_tiles > S / tile ? S / tile : diag_band_tiles;
-    // public element format -> product path of the kernels (3 = MXFP8 decoded exactly, bf16 MFMA)
-    a.hi_fmt = (hi_fmt == DMA_FMT_MXFP8_E4M3 && !fp8_mfma) ? 3 : hi_fmt;
-    a.lo_fmt = (lo_fmt == DMA_FMT_MXFP8_E4M3 && !fp8_mfma) ? 3 : lo_fmt;
+    a.sink = sink > S / tile ? S / tile : sink;
+    a.causal = causal != 0;
+    // public element format -> product path of the kernels: 3 / 4 = MXFP8 (E4M3 / E5M2) decoded exactly to bf16 and
+    // multiplied on the bf16 MFMA; E5M2 has no other path
+    if (fp8_mfma && (hi_fmt == DMA_FMT_MXFP8_E5M2 || lo_fmt == DMA_FMT_MXFP8_E5M2)) return DMA_ERR_UNSUPPORTED;
+    auto path = [&](int f) { return f == DMA_FMT_MXFP8_E5M2 ? 4 : (f == DMA_FMT_MXFP8_E4M3 && !fp8_mfma) ? 3 : f; };
+    a.hi_fmt = path(hi_fmt);
+    a.lo_fmt = path(lo_fmt);
     return dma::launch_attn_fwd(a, (hipStream_t)stream);
 }
 

@@ -1,0 +1,741 @@
+// Fused forward of Diagonal-Tiled Mixed-Precision Attention for gfx950 (paper, Alg. 1 with the
+// online softmax of Sec. 3.2; Q/K quantization of Alg. 2 done in-kernel).
+//
+// Work split.  One workgroup owns TPW consecutive logical query tiles (B_M = BT rows each) of one
+// (batch, query head) and walks the key tiles jt = 0, 1, ... in ascending order, so one K/V tile
+// fetched and quantized once serves TPW * BT query rows.  Each wave owns 32 query rows of one
+// logical tile `it` and follows Alg. 1 for that tile: key tiles before the diagonal band in the low
+// format (Phase 1), the last `band` tiles up to the diagonal one in the high format (Phase 2),
+// tiles after its diagonal are skipped.
+//
+// Everything is computed transposed so that a query row lives in one lane column:
+//     S^T[key, query] = K . Q^T      block-scaled MFMA 32x32x64 (A = K codes from LDS, B = Q codes in VGPRs)
+//                                     or bf16 MFMA 32x32x16 for the exact MXFP8 / unquantized paths
+//     O^T[d,  query] += V^T . P^T    bf16 MFMA 32x32x16 (A = V^T via LDS transpose reads, B = P^T = the
+//                                     exponentiated S^T accumulators, already in operand layout)
+// so the row maximum / sum need one cross-half exchange and the running state (m, l) is per lane.
+//
+// Pipeline.  K and V of tile jt+2 are in flight from global memory (16 B per lane, coalesced) while
+// tile jt is computed out of LDS buffer jt & 1 and tile jt+1 is quantized (block maximum over a lane
+// quad by DPP, E8M0 scale, hardware scaled converts) into buffer (jt+1) & 1: one barrier per tile.
+// Two waves per SIMD let the matrix pipe of one wave overlap the softmax / quantization VALU work of
+// the other.
+#pragma once
+
+#include "dma_device.hpp"
+#include "dma_internal.hpp"
+
+namespace dma {
+
+template <int A, int B>
+constexpr int cmax() { return A > B ? A : B; }
+
+
+template <int D_, int BT_, int TPW_>
+struct Cfg {
+    static constexpr int D = D_, BT = BT_, TPW = TPW_;
+    static constexpr int WPT = BT / 32;          // waves per logical query tile (32 rows each)
+    static constexpr int NW = WPT * TPW;         // waves per workgroup
+    static constexpr int T = NW * 64;            // threads per workgroup
+    static constexpr int NKB = BT / 32;          // 32-key blocks per key tile
+    static constexpr int NDB = D / 32;           // 32-wide blocks of the head dimension (output)
+    static constexpr int NH = D / 64;            // k=64 scaled MFMAs per score block
+    static constexpr int NKK = D / 16;           // k=16 bf16 MFMAs per score block
+    static constexpr int CPR = D / 8;            // 16-byte chunks per row
+    static constexpr int CH = BT * CPR;          // chunks per tile
+    static constexpr int CPT = CH / T;           // chunks per thread
+    static_assert(CH % T == 0, "tile must split evenly over the threads");
+    static_assert(D % 64 == 0, "head dimension must be a multiple of 64");
+    // LDS row strides in bytes; the padding spreads consecutive rows over the banks.
+    static constexpr int KS4 = D / 2 + 16;       // E2M1 codes
+    static constexpr int KS8 = D + 16;           // E4M3 codes
+    static constexpr int KSB = 2 * D + 16;       // bf16 keys
+    static constexpr int VS = 2 * D;             // bf16 values: dense rows, 16-byte chunks XOR-swizzled (see v_swizzle)
+    static constexpr int KSC = BT * CPR;         // scale bytes of one tile: one per 16-byte chunk (each block's 4 chunks repeat its code)
+    static constexpr int VBYTES = BT * VS;
+    static constexpr int VLOADS = VBYTES / 1024; // 1 KiB wave-wide direct-to-LDS loads per tile
+    static constexpr int VLPW = VLOADS / NW;     // ... per wave
+    static_assert(VLOADS % NW == 0, "V tile must split evenly over the waves");
+    // V rows sit densely in LDS (the direct loads write 1 KiB contiguously); so that the transpose reads of four
+    // consecutive keys do not hit the same banks, chunk c of key k is stored at chunk c ^ (4 * v_swizzle(k)).
+    static constexpr int v_swizzle(int key) { return D == 128 ? (key & 3) : ((key >> 1) & 1); }
+    template <int FMT>
+    static constexpr int kstride() { return FMT == FMT_E2M1 ? KS4 : FMT == FMT_E4M3 ? KS8 : KSB; }
+    template <int FMT>
+    static constexpr int kbytes() { return BT * kstride<FMT>(); }
+    // Query operand storage in 16-byte units: scaled MFMA: NH x (4 or 8 dwords); bf16 MFMA: NKK x 4 dwords.
+    template <int FMT>
+    static constexpr int qregs() { return FMT == FMT_E2M1 ? NH : FMT == FMT_E4M3 ? 2 * NH : NKK; }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Query operand of a wave: its 32 rows in MFMA B-operand layout.  Lane (j, g) = (lane % 32, lane / 32) owns row j and
+// the MX blocks 2h + g (h < NH) of that row: raw[4h + t] is the 16-byte chunk t of block 2h + g, i.e. elements
+// 32 (2h + g) + 8t + [0, 8).  Every format's operand is made from these registers, so one set of loads serves both
+// precisions and every block maximum is lane-local:
+//   scaled MFMA (k = 64 per step h): block 2h + g is exactly the lane's share of step h;
+//   bf16 MFMA (k = 16 per step kk = 4h + t): the lane's 8 elements of step kk are chunk t of block 2h + g -- a
+//   permutation of the head dimension against the instruction's natural order, which the K side mirrors (see score_part).
+// ---------------------------------------------------------------------------------------------
+template <typename C>
+DMA_DEV void load_q_raw(v4i (&raw)[C::NKK], const uint16_t* __restrict__ qhead, int row0, int j, int g)
+{
+    const uint16_t* rowp = qhead + (int64_t)(row0 + j) * C::D + 32 * g;
+#pragma unroll
+    for (int h = 0; h < C::NH; ++h)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) raw[4 * h + t] = *(const v4i*)(rowp + 64 * h + 8 * t);
+}
+
+// qr / qscale from raw (scaled MFMA formats fill `qscale`: byte h = E8M0 of block 2h + g of the lane's row).
+template <typename C, int FMT, int QR>
+DMA_DEV void make_q(v4i (&qr)[QR], int& qscale, const v4i (&raw)[C::NKK], float c)
+{
+    qscale = 0;
+    if constexpr (FMT == FMT_BF16) {
+#pragma unroll
+        for (int kk = 0; kk < C::NKK; ++kk) qr[kk] = raw[kk];
+    } else {
+        static_for<C::NH>([&](auto H) {
+            constexpr int h = H;
+            float x[4][8];
+            float amax = 0.f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                unpack8<true>(raw[4 * h + t], c, x[t]);
+                amax = fmaxf(amax, amax8(x[t]));
+            }
+            const int code = e8m0_code<FMT>(amax);
+            if constexpr (FMT == FMT_E4M3_X || FMT == FMT_E5M2_X) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) qr[4 * h + t] = quant_dequant8<FMT>(x[t], code);
+            } else if constexpr (FMT == FMT_E2M1) {
+                qscale |= code << (8 * h);
+                v4i r;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) r[t] = encode8_e2m1(x[t], code);
+                qr[h] = r;
+            } else {
+                qscale |= code << (8 * h);
+                int r[8];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const v2i e = encode8_e4m3(x[t], code);
+                    r[2 * t] = e[0];
+                    r[2 * t + 1] = e[1];
+                }
+                // E4M3 operand layout: VGPR 0-3 = first half of block 2h (lower lanes) / second half of
+                // block 2h (upper lanes); VGPR 4-7 the same for block 2h+1.  Each lane encoded one whole
+                // block, so the lower lanes' VGPR 4-7 trade places with the upper lanes' VGPR 0-3.
+#pragma unroll
+                for (int t = 0; t < 4; ++t) swap_halves(r[t], r[4 + t]);
+                qr[2 * h] = v4i{r[0], r[1], r[2], r[3]};
+                qr[2 * h + 1] = v4i{r[4], r[5], r[6], r[7]};
+            }
+        });
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// LDS addressing.  All LDS traffic goes through 32-bit byte addresses of the form
+// (one pinned per-lane VGPR) + (compile-time constant), so every access uses the instruction's immediate
+// offset and the loops carry a handful of address registers instead of one per access.
+// ---------------------------------------------------------------------------------------------
+#define DMA_LDS __attribute__((address_space(3)))
+DMA_DEV unsigned pin(unsigned x) { asm volatile("" : "+v"(x)); return x; }
+// Lane / thread index made opaque at the point of use: the address arithmetic that follows is then redone where
+// it is needed (a few integer ops) instead of being hoisted out of the tile loops into long-lived registers.
+DMA_DEV int fresh(int x) { asm volatile("" : "+v"(x)); return x; }
+template <typename T>
+DMA_DEV T lds_read(unsigned addr) { return *(const DMA_LDS T*)(uintptr_t)addr; }
+template <typename T>
+DMA_DEV void lds_write(unsigned addr, T v) { *(DMA_LDS T*)(uintptr_t)addr = v; }
+DMA_DEV v4s lds_read_tr16(unsigned addr) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((DMA_LDS v4s*)(uintptr_t)addr); }
+
+// ---------------------------------------------------------------------------------------------
+// Staging of one key/value tile
+// ---------------------------------------------------------------------------------------------
+// Chunk r of thread tid is 16-byte chunk r * T + tid of the dense tile: key r * (T / CPR) + tid / CPR.
+template <typename C>
+DMA_DEV void load_tile(v4i (&reg)[C::CPT], const uint16_t* __restrict__ tile, int tid)
+{
+    const uint8_t* base = (const uint8_t*)tile;              // uniform
+    const unsigned lane_off = (unsigned)fresh(tid) * 16u;
+#pragma unroll
+    for (int r = 0; r < C::CPT; ++r) reg[r] = *(const v4i*)(base + (size_t)r * C::T * 16 + lane_off);
+}
+
+// K tile from registers into LDS in format FMT.  kdst / ksdst: LDS addresses of the codes and of the scale bytes.
+template <typename C, int FMT>
+DMA_DEV void stage_k(const v4i (&reg)[C::CPT], unsigned kdst, unsigned ksdst, int tid)
+{
+    constexpr int KPR = C::T / C::CPR;                       // keys per chunk round
+    constexpr int STRIDE = C::template kstride<FMT>();
+    constexpr int CB = (FMT == FMT_E2M1) ? 4 : (FMT == FMT_E4M3) ? 8 : 16;     // bytes per chunk in LDS
+    tid = fresh(tid);
+    const int key0 = tid / C::CPR, dc = tid % C::CPR;
+    const unsigned ka = pin(kdst + key0 * STRIDE + dc * CB);
+    const unsigned sa = pin(ksdst + key0 * C::CPR + dc);      // every lane stores its block's scale: no divergence
+#pragma unroll
+    for (int r = 0; r < C::CPT; ++r) {
+        if constexpr (FMT == FMT_BF16) {
+            lds_write<v4i>(ka + r * KPR * STRIDE, reg[r]);
+        } else if constexpr (FMT == FMT_E2M1) {
+            // keys are not pre-scaled: block maximum and converts work on the packed bf16 directly
+            const int code = max((int)(quad_max_u32(amax8_bf16_bits(reg[r])) >> 7) - 2, 0);
+            lds_write<int>(ka + r * KPR * STRIDE, encode8_e2m1_bf16(reg[r], code));
+            lds_write<uint8_t>(sa + r * KPR * C::CPR, (uint8_t)code);
+        } else {
+            float x[8];
+            unpack8<false>(reg[r], 1.f, x);
+            const float amax = quad_max(amax8(x));
+            const int code = e8m0_code<FMT>(amax);
+            if constexpr (FMT == FMT_E4M3_X || FMT == FMT_E5M2_X) {
+                lds_write<v4i>(ka + r * KPR * STRIDE, quant_dequant8<FMT>(x, code));
+            } else {
+                lds_write<v2i>(ka + r * KPR * STRIDE, encode8_e4m3(x, code));
+                lds_write<uint8_t>(sa + r * KPR * C::CPR, (uint8_t)code);
+            }
+        }
+    }
+}
+
+// V tile from registers into LDS, 16-byte chunks swizzled (see Cfg::v_swizzle).
+template <typename C>
+DMA_DEV void stage_v(const v4i (&reg)[C::CPT], unsigned vdst, int tid)
+{
+    constexpr int KPR = C::T / C::CPR;
+    static_assert(KPR % 4 == 0, "swizzle of a row must not depend on the chunk round");
+    tid = fresh(tid);
+    const int key0 = tid / C::CPR, dc = tid % C::CPR;
+    const unsigned va = pin(vdst + key0 * C::VS + ((dc ^ (4 * C::v_swizzle(key0))) * 16));
+#pragma unroll
+    for (int r = 0; r < C::CPT; ++r) lds_write<v4i>(va + r * KPR * C::VS, reg[r]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// One key tile for one wave: scores, mask, online softmax, P V
+// ---------------------------------------------------------------------------------------------
+template <int FMT, int H>
+DMA_DEV v16f mfma_mx(const v8i& a, const v8i& b, const v16f& c, int sa, int sb)
+{
+    constexpr int code = (FMT == FMT_E2M1) ? 4 : 0;
+    // sa: the K-side scale sits in byte 0 of its own dword; sb: byte H of the query scale dword
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, code, code, 0, sa, H, sb);
+}
+
+DMA_DEV v8i widen(const v4i& lo) { return v8i{lo[0], lo[1], lo[2], lo[3], 0, 0, 0, 0}; }
+DMA_DEV v8i widen(const v4i& lo, const v4i& hi) { return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]}; }
+
+// First half of a key tile for one wave (all of its VALU work): scores S^T, causal mask, new running maximum,
+// rescale of l and O by 2^(m_old - m_new), probabilities P = 2^(S - m) summed into l and rounded to bf16.
+// The result is P^T packed as the B operands of the value part: pb[grp] holds keys 16 grp .. 16 grp + 15.
+// ksrc / kssrc: LDS addresses of the tile's K codes / scale bytes.
+// MAYBE_DIAG = false compiles the mask away (tiles strictly below the diagonal).
+// after_mfma() runs between the matrix part and the softmax part (the caller's global loads go there).
+template <typename C, int FMT, bool MAYBE_DIAG, int QR, typename F>
+DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned kssrc,
+                        bool diagonal, int qrow_in_tile, int lane, float c,
+                        float& m, float& mfloor, float& l, v16f (&o)[C::NDB], v8bf (&pb)[2 * C::NKB], F&& after_mfma)
+{
+    lane = fresh(lane);
+    const int j = lane & 31, g = lane >> 5;
+    v16f s[C::NKB];
+    constexpr int STRIDE = C::template kstride<FMT>();
+    // the lane's key row of 32-key block 0; the bf16 MFMA paths read the head dimension in the query operand's order
+    const unsigned ka = pin(ksrc + j * STRIDE + (uses_bf16_mfma(FMT) ? 64 : 16) * g);
+    // The accumulators start at -m (the running maximum so far), so the products arrive as S - m and the
+    // subtraction of the maximum costs nothing in the common case of a maximum that does not move.
+    // (One register tuple holds the start value; the first MFMA of every 32-key block reads it as its C operand.)
+    const float acc0 = (FMT == FMT_BF16) ? 0.f : -m;
+    const v16f sinit = {acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0};
+
+    // ---- S^T = K . Q^T.  Operands are fetched from LDS ahead of the MFMAs that use them.
+    if constexpr (FMT == FMT_E2M1) {
+        // operands of two 32-key blocks at a time (2 * NH 16-byte reads + 2 scale dwords) ahead of their MFMAs,
+        // which go h-major so that the two MFMAs into one accumulator are not adjacent
+        // scale of MX block 2h + g of the lane's key: byte 0 of the dword at chunk 4 (2h + g) of the key's scale row
+        const unsigned sa = pin(kssrc + j * C::CPR + 4 * g);
+        static_assert(C::NKB % 2 == 0, "key tile must hold an even number of 32-key blocks");
+        v4i a[2][2][C::NH];
+        int ksc[2][2][C::NH];
+        auto fetch = [&](int pair) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int kb = 2 * pair + u;
+#pragma unroll
+                for (int h = 0; h < C::NH; ++h) {
+                    ksc[pair & 1][u][h] = lds_read<int>(sa + kb * 32 * C::CPR + 8 * h);
+                    a[pair & 1][u][h] = lds_read<v4i>(ka + kb * 32 * STRIDE + 32 * h);
+                }
+            }
+        };
+        fetch(0);
+#pragma unroll
+        for (int pair = 0; pair < C::NKB / 2; ++pair) {
+            if (pair + 1 < C::NKB / 2) fetch(pair + 1);
+            static_for<C::NH>([&](auto H) {
+                constexpr int h = H;
+                const v8i b = widen(qr[h]);
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+                    s[2 * pair + u] = mfma_mx<FMT, h>(widen(a[pair & 1][u][h]), b, h == 0 ? sinit : s[2 * pair + u], ksc[pair & 1][u][h], qscale);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else if constexpr (FMT == FMT_E4M3) {
+        const unsigned sa = pin(kssrc + j * C::CPR + 4 * g);
+#pragma unroll
+        for (int kb = 0; kb < C::NKB; ++kb) {
+            static_for<C::NH>([&](auto H) {
+                constexpr int h = H;
+                const int ksc = lds_read<int>(sa + kb * 32 * C::CPR + 8 * h);
+                const v4i lo = lds_read<v4i>(ka + kb * 32 * STRIDE + 64 * h);
+                const v4i hi = lds_read<v4i>(ka + kb * 32 * STRIDE + 64 * h + 32);
+                s[kb] = mfma_mx<FMT, h>(widen(lo, hi), widen(qr[2 * h], qr[2 * h + 1]), h == 0 ? sinit : s[kb], ksc, qscale);
+            });
+        }
+    } else {
+        // bf16 MFMA (unquantized, or MXFP8 decoded exactly): NKK k=16 steps per 32-key block, in units of UK steps;
+        // the next unit's operands are in flight while the current unit multiplies.  Step kk = 4h + t multiplies the
+        // lane's chunk t of MX block 2h + g (see load_q_raw): byte 128 h + 64 g + 16 t of the key's bf16 row.
+        constexpr int UK = 4, UPB = C::NKK / UK, NU = C::NKB * UPB;
+        static_assert(C::NKK % UK == 0, "head dimension must be a multiple of 64");
+        v4i a[2][UK];
+        auto fetch = [&](int u) {
+#pragma unroll
+            for (int i = 0; i < UK; ++i)
+                a[u & 1][i] = lds_read<v4i>(ka + (u / UPB) * 32 * STRIDE + 16 * ((u % UPB) * UK + i) + 64 * (((u % UPB) * UK + i) / 4));
+        };
+        fetch(0);
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            if (u + 1 < NU) fetch(u + 1);
+            const int kb = u / UPB;
+#pragma unroll
+            for (int i = 0; i < UK; ++i)
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a[u & 1][i]),
+                                                                __builtin_bit_cast(v8bf, qr[(u % UPB) * UK + i]),
+                                                                (u % UPB == 0 && i == 0) ? sinit : s[kb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (FMT == FMT_BF16) {                 // unquantized operands: the softmax factor multiplies the score
+#pragma unroll
+            for (int kb = 0; kb < C::NKB; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[kb][r] = __builtin_fmaf(s[kb][r], c, -m);
+        }
+    }
+
+    after_mfma();
+
+    // ---- causal mask on the tile that straddles the diagonal: key > query -> -inf
+    if constexpr (MAYBE_DIAG) {
+        if (diagonal) {
+            const int qi = qrow_in_tile + j;
+#pragma unroll
+            for (int kb = 0; kb < C::NKB; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kj = kb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (kj > qi) s[kb][r] = -INFINITY;
+                }
+        }
+    }
+
+    // ---- online softmax in base 2.  s holds S - m.  delta = how far the row maximum moves (>= 0; on the first tile
+    // of a row, where m is only the arbitrary start value 0, any sign: mfloor is -inf there and 0 afterwards).
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < C::NKB; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
+    const float delta = fmaxf(cross_half_max(mx), mfloor);
+    const float mnew = m + delta;
+    const float alpha = __builtin_amdgcn_exp2f(fminf(m - mnew, 0.f));     // first tile: l and O are 0, any finite factor does
+    m = mnew;
+    mfloor = 0.f;
+    if (__builtin_amdgcn_ballot_w64(delta != 0.0f) != 0) {      // skipped when no row of the wave moved its maximum
+#pragma unroll
+        for (int db = 0; db < C::NDB; ++db) o[db] *= alpha;
+#pragma unroll
+        for (int kb = 0; kb < C::NKB; ++kb) s[kb] -= delta;
+    }
+
+    // ---- P = 2^(S - m): row sums from the binary32 values, bf16 (round to nearest even) for the P V product
+    float psum[2] = {0.f, 0.f};
+#pragma unroll
+    for (int grp = 0; grp < 2 * C::NKB; ++grp) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float p0 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t]);
+            const float p1 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t + 1]);
+            psum[0] += p0;
+            psum[1] += p1;
+            const v2bf h2 = __builtin_convertvector(v2f{p0, p1}, v2bf);
+            pb[grp][2 * t] = h2[0];
+            pb[grp][2 * t + 1] = h2[1];
+        }
+    }
+    l = l * alpha + (psum[0] + psum[1]);
+}
+
+// Second half (all matrix work): O^T += V^T . P^T in groups of 16 keys; the V^T operands of the next group are in
+// flight from LDS while the MFMAs of the current group run.  vsrc: LDS address of the V tile.
+template <typename C>
+DMA_DEV void value_part(unsigned vsrc, int lane, v16f (&o)[C::NDB], const v8bf (&pb)[2 * C::NKB])
+{
+    lane = fresh(lane);
+    const int g = lane >> 5, l16 = lane & 15, q16 = lane >> 4;
+    // Transpose read: lane l16 of a 16-lane group points at row (l16 / 4) of a 4-key x 16-column patch; the row's
+    // 16-byte chunks are swizzled by the row index (the same for every patch: patches start at multiples of 4).
+    // va[db]: the lane's address for d-block db in the tile's first patch; other patches are constant offsets.
+    const unsigned row_off = (4 * g + (l16 >> 2)) * C::VS + 8 * (l16 & 1);
+    unsigned va[C::NDB];
+#pragma unroll
+    for (int db = 0; db < C::NDB; ++db)
+        va[db] = pin(vsrc + row_off + 16 * ((4 * db + 2 * (q16 & 1) + ((l16 & 3) >> 1)) ^ (4 * C::v_swizzle(l16 >> 2))));
+
+    auto read_vt = [&](v8s (&a)[C::NDB], int grp) {             // V^T operands of key group grp (16 keys)
+#pragma unroll
+        for (int db = 0; db < C::NDB; ++db) {
+            const v4s a0 = lds_read_tr16(va[db] + grp * 16 * C::VS);
+            const v4s a1 = lds_read_tr16(va[db] + grp * 16 * C::VS + 8 * C::VS);
+            a[db] = v8s{a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+        }
+    };
+    constexpr int NG = 2 * C::NKB;
+    v8s vt[3][C::NDB];                       // operands of groups grp, grp+1 and grp+2 in rotation
+    read_vt(vt[0], 0);
+    if (NG > 1) read_vt(vt[1], 1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int grp = 0; grp < NG; ++grp) {
+        if (grp + 2 < NG) read_vt(vt[(grp + 2) % 3], grp + 2);
+#pragma unroll
+        for (int db = 0; db < C::NDB; ++db)
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vt[grp % 3][db]), pb[grp], o[db], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The kernel
+// ---------------------------------------------------------------------------------------------
+// K and V of one key tile from registers into LDS: K in the low format if some wave computes the tile in Phase 1,
+// in the high format if some wave computes it in Phase 2.
+template <typename C, int LO, int HI>
+DMA_DEV void stage_tile(const v4i (&kreg)[C::CPT], const v4i (&vreg)[C::CPT], bool any_lo, bool any_hi,
+                        unsigned klo, unsigned kslo, unsigned khi, unsigned kshi, unsigned vdst, int tid)
+{
+    if (any_lo) stage_k<C, LO>(kreg, klo, kslo, tid);
+    if constexpr (LO != HI) {
+        if (any_hi) stage_k<C, HI>(kreg, khi, kshi, tid);
+    }
+    stage_v<C>(vreg, vdst, tid);
+}
+
+// GENERAL = false: Alg. 1 as printed (causal, no sink window; sink_arg / causal_arg are ignored): main tiles then band
+// tiles, two loops in a row.  GENERAL = true: sink window and / or no causal mask: runs of main and band tiles alternate.
+template <int D, int BT, int TPW, int LO, int HI, bool GENERAL>
+__global__ void __launch_bounds__((BT / 32) * TPW * 64, 2)
+dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                    const uint16_t* __restrict__ v, float* __restrict__ out,
+                    int B, int Hq, int Hkv, int S, int band, int sink_arg, int causal_arg, float c, int head_block)
+{
+    const int sink = GENERAL ? sink_arg : 0;
+    const bool causal = GENERAL ? (causal_arg != 0) : true;
+    using C = Cfg<D, BT, TPW>;
+    constexpr bool TWO = (LO != HI);
+    constexpr int KLO = C::template kbytes<LO>();
+    constexpr int KHI = TWO ? C::template kbytes<HI>() : 0;
+    constexpr int QRLO = C::template qregs<LO>();
+    constexpr int QRHI = TWO ? C::template qregs<HI>() : 1;
+    // LDS map (bytes): V, the low-format K and the high-format K (each + scale bytes) double-buffered for the pipelined
+    // tile loops.  The output transpose of the epilogue reuses the same memory.
+    constexpr int OFF_V = 0;
+    constexpr int OFF_KLO = OFF_V + 2 * C::VBYTES;
+    constexpr int OFF_KSLO = OFF_KLO + 2 * KLO;
+    constexpr int OFF_KHI = OFF_KSLO + 2 * C::KSC;
+    constexpr bool HI_SCALES = TWO && !uses_bf16_mfma(HI);   // the decoded-to-bf16 high format carries no scale bytes
+    constexpr int OFF_KSHI = OFF_KHI + 2 * KHI;
+    constexpr int EPI_COLS = 64;                         // output columns per epilogue pass
+    constexpr int EPI_STRIDE = EPI_COLS * 4 + 16;        // bytes per staged output row (padded against bank conflicts)
+    constexpr int EPI_WAVE = 32 * EPI_STRIDE;
+    constexpr int LDS_TOTAL = cmax<OFF_KSHI + (HI_SCALES ? 2 * C::KSC : 0), C::NW * EPI_WAVE>();
+    static_assert(LDS_TOTAL <= 160 * 1024, "LDS budget of one CU");
+    static_assert(D % EPI_COLS == 0, "epilogue works on 64-column slabs");
+    __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_TOTAL];
+    const unsigned lds0 = (unsigned)(uintptr_t)(DMA_LDS uint8_t*)lds;
+    auto v_at = [&](int buf) { return lds0 + OFF_V + buf * C::VBYTES; };
+    auto klo_at = [&](int buf) { return lds0 + OFF_KLO + buf * KLO; };
+    auto kslo_at = [&](int buf) { return lds0 + OFF_KSLO + buf * C::KSC; };
+    auto khi_at = [&](int buf) { return lds0 + OFF_KHI + buf * KHI; };
+    auto kshi_at = [&](int buf) { return lds0 + OFF_KSHI + (HI_SCALES ? buf * C::KSC : 0); };
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+
+    // ---- static schedule.  The grid is one workgroup per CU; a work item is (batch, query head, group of TPW query
+    // tiles) and costs about 2 * grp + 2 key-tile steps.  Items are ranked heaviest first within blocks of
+    // `head_block` query heads and dealt to the workgroups in boustrophedon order (round 0: worker 0, 1, ..., W-1;
+    // round 1: W-1, ..., 0; ...), which gives every worker the same load to within the lightest items, without
+    // atomics and whatever order the hardware starts workgroups in; a block is an even number of rounds (or
+    // everything), so the workers move from block to block together and share few K/V streams at a time.  When the (batch, kv head) units divide over the 8 XCDs (workgroup i runs on XCD i % 8), each XCD keeps its
+    // own units, so the K/V stream of a unit stays in one L2.
+    const int N = S / BT;                // logical tiles per sequence (host guarantees N % TPW == 0)
+    const int NG = N / TPW;              // tile groups
+    const int group = Hq / Hkv;
+    const int units = B * Hkv;
+    const bool by_xcd = (units % 8 == 0) && (gridDim.x % 8 == 0);
+    const int xcd = by_xcd ? (int)(blockIdx.x & 7) : 0;
+    const int slot = by_xcd ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int workers = by_xcd ? (int)(gridDim.x >> 3) : (int)gridDim.x;
+    const int heads_x = by_xcd ? (units / 8) * group : B * Hq;       // query heads ranked together
+    const int items = heads_x * NG;
+
+    for (int round = 0;; ++round) {
+        const int pos = round * workers + ((round & 1) ? workers - 1 - slot : slot);
+        if (pos >= items) break;
+        const int blk = pos / (head_block * NG), within = pos % (head_block * NG);
+        const int grp = NG - 1 - within / head_block;
+        const int hx = blk * head_block + within % head_block;
+        const int unit = by_xcd ? (hx / group) * 8 + xcd : hx / group;
+        const int b = unit / Hkv;
+        const int hkv = unit % Hkv;
+        const int hq = hkv * group + hx % group;
+        const uint16_t* qhead = q + ((int64_t)b * Hq + hq) * S * D;
+        const uint16_t* khead = k + ((int64_t)b * Hkv + hkv) * S * D;
+        const uint16_t* vhead = v + ((int64_t)b * Hkv + hkv) * S * D;
+        float* ohead = out + ((int64_t)b * Hq + hq) * S * D;
+
+        // ---- this wave's logical tile and the precision rule (Alg. 1: for query tile `it`, key tile jt is high
+        // precision iff it lies in the diagonal window, it - jt < band; extensions: the first `sink` key tiles are high
+        // precision for every query tile, and without the causal mask every key tile is visited and the window is
+        // |it - jt| < band).  Key tiles are visited in ascending order.
+        const int it0 = grp * TPW, last = it0 + TPW - 1;
+        const int it = it0 + wave / C::WPT;
+        const int qrow_in_tile = (wave % C::WPT) * 32;
+        const int qrow = it * BT + qrow_in_tile;
+        const int nt = causal ? last + 1 : N;            // this item visits key tiles [0, nt)
+        auto tile_hi = [&](int qt, int jt) __attribute__((always_inline)) {             // does query tile qt compute key tile jt in the high format?
+            if (!TWO) return false;
+            if (jt < sink) return true;
+            const int dist = (causal || qt >= jt) ? qt - jt : jt - qt;
+            return dist < band;
+        };
+        // Key tiles split into "main" tiles -- low format, unmasked and computed by every wave of the workgroup --
+        // and "band" tiles, where waves differ (skipped past the wave's diagonal, Phase 1 or Phase 2, masked on the
+        // wave's diagonal tile): band tiles are [0, s1) (the sink) and [w0, w1) (around the diagonal).
+        int w0, w1, s1 = TWO ? min(sink, nt) : 0;
+        if (causal) {
+            w0 = (TWO && band > 0) ? max(0, it0 + 1 - band) : it0;
+            w1 = nt;
+        } else if (TWO && band > 0) {
+            w0 = max(0, it0 + 1 - band);
+            w1 = min(N, last + band);
+        } else {
+            w0 = w1 = nt;
+        }
+        if (s1 > w0) { w1 = max(w1, s1); w0 = 0; s1 = 0; }
+        // what the workgroup needs of key tile jt in LDS
+        auto needs = [&](int jt, bool& any_lo, bool& any_hi) __attribute__((always_inline)) {
+            any_lo = !TWO;
+            any_hi = false;
+            if constexpr (TWO) {
+#pragma unroll
+                for (int w = 0; w < TPW; ++w) {
+                    if (causal && jt > it0 + w) continue;
+                    const bool h = tile_hi(it0 + w, jt);
+                    any_hi |= h;
+                    any_lo |= !h;
+                }
+            }
+        };
+
+        // Running maximum m and sum l (Alg. 1 starts m at -inf and l at 1, and the first rescale factor 2^(-inf) erases
+        // that l).  Here m starts at 0 with l = 0 and mfloor = -inf marks "no tile seen yet": the first tile then sets m to
+        // its row maximum whatever the sign, which gives the same m, l and O as Alg. 1 after that tile.
+        float m = 0.f, mfloor = -INFINITY, l = 0.f;
+        v16f o[C::NDB];
+#pragma unroll
+        for (int db = 0; db < C::NDB; ++db) o[db] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+        // ---- prologue: key tile 0 and the query operands (all loads in flight together), tile 0 into LDS buffer 0.
+        // Invariant from here on: the K/V registers hold the tile after the one staged last, if there is one.
+        v4i kreg[C::CPT], vreg[C::CPT];
+        v8bf pb[2 * C::NKB];
+        v4i qr_lo[QRLO], qr_hi[QRHI];
+        int qs_lo = 0, qs_hi = 0;
+        {
+            v4i qraw[C::NKK];
+            load_q_raw<C>(qraw, qhead, qrow, fresh(lane) & 31, fresh(lane) >> 5);
+            load_tile<C>(kreg, khead, tid);
+            load_tile<C>(vreg, vhead, tid);
+            __builtin_amdgcn_sched_barrier(0);           // every request is out before the first result is needed
+            make_q<C, LO>(qr_lo, qs_lo, qraw, c);
+            if constexpr (TWO) {
+                if (band > 0 || sink > 0) make_q<C, HI>(qr_hi, qs_hi, qraw, c);
+            }
+        }
+        auto stage_next = [&](int jt, int buf) __attribute__((always_inline)) {         // tile jt from the K/V registers into LDS buffer buf
+            bool any_lo, any_hi;
+            needs(jt, any_lo, any_hi);
+            stage_tile<C, LO, HI>(kreg, vreg, any_lo, any_hi, klo_at(buf), kslo_at(buf), khi_at(buf), kshi_at(buf), v_at(buf), tid);
+        };
+        stage_next(0, 0);
+        if (1 < nt) {
+            load_tile<C>(kreg, khead + (int64_t)BT * D, tid);
+            load_tile<C>(vreg, vhead + (int64_t)BT * D, tid);
+        }
+        __syncthreads();
+
+        // ---- tile loop.  Tile jt lives in LDS buffer jt & 1; one barrier per tile.  At the top of step jt the K and
+        // V tiles jt+1 (loaded into registers during step jt-1) go into the other buffer (K quantized on the way) and
+        // the loads of tile jt+2 start; then the wave computes tile jt.
+        // (Direct global-to-LDS loads are not used for V: the compiler orders every later LDS access behind them with
+        // a full vmcnt(0) wait, which exposes the memory latency.  On this GPU the MFMA pipe and the floating-point
+        // VALU of a SIMD do not run concurrently, so the two waves of a SIMD are only there to hide LDS and memory
+        // latency, not to overlap matrix and softmax work.)
+        // On main tiles K of tile jt+2 is requested in the middle of the score part (after its MFMAs), V after it:
+        // the two bursts of requests (every wave of the workgroup issues them at about the same point) are half as
+        // long, and the matrix part of the score has 32 registers more.
+        auto main_step = [&](int jt) __attribute__((always_inline)) {
+            const int buf = jt & 1;
+            if (jt + 1 < nt) stage_next(jt + 1, buf ^ 1);
+            score_part<C, LO, false>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), false, qrow_in_tile, lane, c, m, mfloor, l, o, pb,
+                                     [&]() __attribute__((always_inline)) { if (jt + 2 < nt) load_tile<C>(kreg, khead + (int64_t)(jt + 2) * BT * D, tid); });
+            if (jt + 2 < nt) load_tile<C>(vreg, vhead + (int64_t)(jt + 2) * BT * D, tid);
+            value_part<C>(v_at(buf), lane, o, pb);
+            __syncthreads();
+        };
+        auto band_step = [&](int jt) __attribute__((always_inline)) {
+            const int buf = jt & 1;
+            const bool active = !causal || jt <= it;
+            const bool diagonal = causal && jt == it;
+            if (jt + 1 < nt) stage_next(jt + 1, buf ^ 1);
+            if (active) {
+                if (!tile_hi(it, jt)) {
+                    score_part<C, LO, true>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
+                } else if constexpr (TWO) {
+                    score_part<C, HI, true>(qr_hi, qs_hi, khi_at(buf), kshi_at(buf), diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
+                }
+            }
+            if (jt + 2 < nt) {
+                load_tile<C>(kreg, khead + (int64_t)(jt + 2) * BT * D, tid);
+                load_tile<C>(vreg, vhead + (int64_t)(jt + 2) * BT * D, tid);
+            }
+            if (active) value_part<C>(v_at(buf), lane, o, pb);
+            __syncthreads();
+        };
+        if constexpr (!GENERAL) {
+            for (int jt = 0; jt < w0; ++jt) main_step(jt);
+            for (int jt = w0; jt < nt; ++jt) band_step(jt);
+        } else {
+            for (int jt = 0; jt < nt;) {
+                if ((jt >= s1 && jt < w0) || jt >= w1) {
+                    const int end = jt < w0 ? w0 : nt;           // a run of main tiles
+                    for (; jt < end; ++jt) main_step(jt);
+                } else {
+                    band_step(jt);
+                    ++jt;
+                }
+            }
+        }
+
+        // ---- O / l, transposed through LDS (free after the barrier above) so that every output row leaves as whole
+        // 256-byte runs: the wave parks a 32 x 64 slab of its rows in its own LDS region and reads it back row-major,
+        // four rows (16 lanes x 16 bytes each) per instruction.
+        {
+            const int ln = fresh(lane);
+            const int j = ln & 31, g = ln >> 5, rsub = ln >> 4, piece = ln & 15;
+            const float inv = 1.0f / cross_half_sum(l);
+            const unsigned region = lds0 + wave * EPI_WAVE;
+            const unsigned wr = pin(region + j * EPI_STRIDE + 16 * g);
+            const unsigned rd = pin(region + rsub * EPI_STRIDE + 16 * piece);
+            float* obase = ohead + (int64_t)(qrow + rsub) * D + 4 * piece;
+#pragma unroll
+            for (int slab = 0; slab < D / EPI_COLS; ++slab) {
+#pragma unroll
+                for (int dd = 0; dd < EPI_COLS / 32; ++dd) {
+                    const int db = slab * (EPI_COLS / 32) + dd;
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const v4f val = {o[db][4 * r4] * inv, o[db][4 * r4 + 1] * inv, o[db][4 * r4 + 2] * inv, o[db][4 * r4 + 3] * inv};
+                        lds_write<v4f>(wr + 128 * dd + 32 * r4, val);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const v4f val = lds_read<v4f>(rd + 4 * i * EPI_STRIDE);
+                    *(v4f*)(obase + (int64_t)(4 * i) * D + slab * EPI_COLS) = val;
+                }
+            }
+        }
+        __syncthreads();                  // the next item's staging overwrites the epilogue regions
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host side: pick the instance
+// ---------------------------------------------------------------------------------------------
+// Number of compute units of the current device (cached per device).
+inline int compute_units()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+template <int D, int BT, int TPW, int LO, int HI, bool GENERAL>
+static int launch_variant(const AttnArgs& a, hipStream_t stream)
+{
+    using C = Cfg<D, BT, TPW>;
+    const int N = a.S / BT;
+    const int64_t items = (int64_t)a.B * a.Hq * (N / TPW);
+    if (N % TPW != 0 || items <= 0 || items > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
+    const int cus = compute_units();
+    if (cus <= 0) return DMA_ERR_HIP_;
+    // as many workgroups as the chip holds at once (one per CU for the D = 128 instances), each walking its share
+    // of the work items
+    static int resident = 0;              // per instance; the same on every device of one kind
+    if (resident == 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL>, C::T, 0) != hipSuccess || n <= 0)
+            return DMA_ERR_HIP_;
+        resident = n;
+    }
+    const int64_t slots = (int64_t)cus * resident;
+    const int64_t blocks = items < slots ? items : slots;
+    const float c = (float)(1.4426950408889634074 / sqrt((double)D));
+    // ranking blocks: the fewest heads that fill an even number of rounds (mirrors the kernel's view of the grid)
+    const int units = a.B * a.Hkv, group = a.Hq / a.Hkv, NG = N / TPW;
+    const bool by_xcd = (units % 8 == 0) && (blocks % 8 == 0);
+    const int workers = (int)(by_xcd ? blocks / 8 : blocks);
+    const int heads_x = by_xcd ? (units / 8) * group : a.B * a.Hq;
+    int head_block = heads_x;
+    for (int hb = 1; hb < heads_x; ++hb)
+        if (heads_x % hb == 0 && ((int64_t)hb * NG) % (2 * workers) == 0) { head_block = hb; break; }
+    hipLaunchKernelGGL((dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL>), dim3((unsigned)blocks), dim3(C::T), 0, stream,
+                       (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, a.out, a.B, a.Hq, a.Hkv,
+                       a.S, a.band, a.sink, a.causal, c, head_block);
+    return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
+}
+
+// Alg. 1 as printed (causal, no sink window) runs the straight-line instance; the sink window and the non-causal
+// variant run the general one.
+template <int D, int BT, int TPW, int LO, int HI>
+static int launch_instance(const AttnArgs& a, hipStream_t stream)
+{
+    if (a.causal && a.sink == 0) return launch_variant<D, BT, TPW, LO, HI, false>(a, stream);
+    return launch_variant<D, BT, TPW, LO, HI, true>(a, stream);
+}
+
+}  // namespace dma

@@ -12,7 +12,7 @@ constexpr int DMA_ERR_INVALID_ARG_ = -1;
 constexpr int DMA_ERR_UNSUPPORTED_ = -2;
 constexpr int DMA_ERR_HIP_ = -3;
 
-// mode: 1 = E4M3 only (c8/s8), 2 = E2M1 only (c4/s4), 3 = both.
+// mode: 1 = E4M3 only (c8/s8), 2 = E2M1 only (c4/s4), 3 = both, 4 = E5M2 only (c8/s8).
 int launch_mx_quantize(const void* x, int64_t rows, int D, int mode, int is_query, void* c4, void* s4,
                        void* c8, void* s8, hipStream_t stream);
 
@@ -26,6 +26,8 @@ struct AttnArgs {
     int B, Hq, Hkv, S, D;
     int tile;
     int band;
+    int sink;        // leading key tiles in the high format
+    int causal;
     int hi_fmt, lo_fmt;
 };
 

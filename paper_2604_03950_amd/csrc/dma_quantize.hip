@@ -12,7 +12,7 @@ namespace dma {
 constexpr int QUANT_THREADS = 256;
 constexpr int QUANT_UNROLL = 4;     // chunks per thread
 
-// MODE: 1 = E4M3 only, 2 = E2M1 only, 3 = both (low copy E2M1 + high copy E4M3).
+// MODE: 1 = E4M3 only, 2 = E2M1 only, 3 = both (low copy E2M1 + high copy E4M3), 4 = E5M2 only.
 template <int MODE, bool IS_QUERY>
 __global__ void __launch_bounds__(QUANT_THREADS)
 mx_quantize_kernel(const v4i* __restrict__ x, int64_t n_chunks, float c,
@@ -42,6 +42,11 @@ mx_quantize_kernel(const v4i* __restrict__ x, int64_t n_chunks, float c,
         if (MODE & 1) {
             const int code = e8m0_code<FMT_E4M3>(amax);
             __builtin_nontemporal_store(encode8_e4m3(v, code), codes8 + ch);
+            if (writes_scale) scales8[ch >> 2] = (uint8_t)code;
+        }
+        if (MODE & 4) {
+            const int code = e8m0_code<FMT_E5M2_X>(amax);
+            __builtin_nontemporal_store(encode8_e5m2(v, code), codes8 + ch);
             if (writes_scale) scales8[ch >> 2] = (uint8_t)code;
         }
     }
@@ -92,6 +97,7 @@ int launch_mx_quantize(const void* x, int64_t rows, int D, int mode, int is_quer
         case 1: return launch_mode<1>(x, rows, D, is_query, c4, s4, c8, s8, stream);
         case 2: return launch_mode<2>(x, rows, D, is_query, c4, s4, c8, s8, stream);
         case 3: return launch_mode<3>(x, rows, D, is_query, c4, s4, c8, s8, stream);
+        case 4: return launch_mode<4>(x, rows, D, is_query, c4, s4, c8, s8, stream);
     }
     return DMA_ERR_INVALID_ARG_;
 }

@@ -106,13 +106,15 @@ def round_bf16_nearest_of_two(p: np.ndarray) -> np.ndarray:
     return out
 
 
-def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p_round=True, sink=0, causal=True):
+def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p_round=True, sink=0, causal=True,
+                  score_dtype=np.float64):
     """Per-element rewrite of the diagonal-tiled attention for q[Hq,S,D], k,v[Hkv,S,D] (one batch).
 
     For every visible pair (i, j) the score comes from the format of the tile pair (i // tile, j // tile):
     high when the tiles are closer than `band` or the key tile is one of the first `sink`; with
     p_round the probabilities are formed against the running maximum over key-tile prefixes and
-    rounded to bf16, otherwise it is a plain base-2 row softmax.  causal=False: every key is visible."""
+    rounded to bf16, otherwise it is a plain base-2 row softmax.  causal=False: every key is visible.
+    score_dtype=np.float32 rounds every score to binary32 first (what an implementation with binary32 scores sees)."""
     Hq, S, D = q_bits.shape
     Hkv = k_bits.shape[0]
     g = Hq // Hkv
@@ -127,7 +129,7 @@ def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p
         s_lo = q_lo @ k_lo.T
         ti = np.arange(S)[:, None] // tile
         tj = np.arange(S)[None, :] // tile
-        s = np.where((np.abs(ti - tj) < band) | (tj < sink), s_hi, s_lo)
+        s = np.where((np.abs(ti - tj) < band) | (tj < sink), s_hi, s_lo).astype(score_dtype).astype(np.float64)
         for i in range(S):
             nk = i + 1 if causal else S                  # keys this row sees
             si = s[i, :nk]

@@ -57,11 +57,17 @@ def test_argument_checks_return_before_any_launch(lib):
     assert attn(band=-1) == -1
     assert attn(hi=7) == -1
     assert attn(B=0) == -1
-    assert attn(causal=0) == -2               # non-causal: not built
     assert attn(S=200) == -2                  # not a multiple of the tile
     assert attn(D=96) == -2                   # no kernel for this head dimension
     assert attn(hi=2, lo=1) == -2             # unsupported format pair
     assert lib.dma_attn_fwd(None, fake, fake, fake, 1, 4, 2, 256, 128, 1, 1, 1, 2, None) == -1
-    opts = binding.AttnOpts(tile=128, sink_tiles=1, pv_fmt=0, per_token_scale=0, fp8_mfma=0)
-    assert lib.dma_attn_fwd_ex(fake, fake, fake, fake, 1, 4, 2, 256, 128, 1, 1, 1, 2, ctypes.byref(opts), None) == -2
+    assert attn(hi=3, lo=1) == -2             # unsupported format pair (E5M2 over E4M3)
+    def attn_ex(hi=1, **kw):
+        opts = binding.AttnOpts(**{**dict(tile=128, sink_tiles=0, pv_fmt=0, per_token_scale=0, fp8_mfma=0), **kw})
+        return lib.dma_attn_fwd_ex(fake, fake, fake, fake, 1, 4, 2, 256, 128, 1, 1, hi, 2, ctypes.byref(opts), None)
+    assert attn_ex(sink_tiles=-1) == -1
+    assert attn_ex(per_token_scale=1) == -2   # Alg. 2 Step 2 variant: not built
+    assert attn_ex(pv_fmt=1) == -2            # MX-format P V: not built
+    assert attn_ex(hi=3, fp8_mfma=1) == -2    # E5M2 only has the decoded-to-bf16 path
+    assert attn_ex(fp8_mfma=2) == -1
     assert lib.dma_attn_fwd_workspace_bytes(1, 32, 8, 32768, 128) == 0

@@ -1,6 +1,10 @@
 """Parity of the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
 
 Bars: MX codes and E8M0 scales bit-exact; attention output max-abs <= 2e-3 and relative L2 <= 1e-3.
+Rounding a probability to bf16 is a decision on a floating-point value: where the oracle's double-precision p lies
+within binary32 score noise of the midpoint of two bf16 numbers, the kernel (binary32 scores) may round the other
+way, and both results are valid.  The oracle reports how far each output element can move through such flips
+(its "slack", zero for almost every element); the max-abs bar is 2e-3 + slack, element by element.
 """
 import numpy as np
 import pytest
@@ -26,14 +30,17 @@ def to_gpu(dma, *bits):
     return [dma.bits_to_bf16_tensor(b) for b in bits]
 
 
-def check_out(got, want, what):
+def check_out(got, want, what, slack=None):
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert np.all(np.isfinite(got)), what
-    max_abs = float(np.max(np.abs(got - want)))
+    err = np.abs(got - want)
+    max_abs = float(np.max(err))
     rel = float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
-    print(f"{what}: max-abs {max_abs:.3e} rel-L2 {rel:.3e}", flush=True)
-    assert max_abs <= MAX_ABS, (what, max_abs)
+    excess = err - (0.0 if slack is None else np.asarray(slack, dtype=np.float64))
+    flips = int(np.count_nonzero(err > MAX_ABS))
+    print(f"{what}: max-abs {max_abs:.3e} rel-L2 {rel:.3e}" + (f" ({flips} elements above {MAX_ABS:g}, all within rounding slack)" if flips else ""), flush=True)
+    assert float(np.max(excess)) <= MAX_ABS, (what, max_abs, float(np.max(excess)))
     assert rel <= REL_L2, (what, rel)
 
 
@@ -132,24 +139,21 @@ FMT_PAIRS = [("e2m1", "e4m3"), ("e2m1", "e2m1"), ("e4m3", "e4m3"), ("bf16", "bf1
 
 def fmt_ids(dma, oracle, name):
     return {"e2m1": (dma.FMT_MXFP4_E2M1, oracle.FMT_E2M1), "e4m3": (dma.FMT_MXFP8_E4M3, oracle.FMT_E4M3),
-            "bf16": (dma.FMT_BF16, oracle.FMT_BF16)}[name]
+            "e5m2": (dma.FMT_MXFP8_E5M2, oracle.FMT_E5M2), "bf16": (dma.FMT_BF16, oracle.FMT_BF16)}[name]
 
 
-def run_case(dma, oracle, w, q, k, v, band, lo, hi, rows=None, explicit_tile=True):
+def run_case(dma, oracle, w, q, k, v, band, lo, hi, rows=None, explicit_tile=True, sink=0, causal=True):
     qd, kd, vd = to_gpu(dma, q, k, v)
     (lo_g, lo_o), (hi_g, hi_o) = fmt_ids(dma, oracle, lo), fmt_ids(dma, oracle, hi)
-    out = dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, hi_fmt=hi_g, lo_fmt=lo_g,
+    out = dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, hi_fmt=hi_g, lo_fmt=lo_g, causal=causal, sink_tiles=sink,
                            tile=w.tile if explicit_tile else None)
     torch.cuda.synchronize()
     out = out.cpu().numpy()
-    if rows is None:
-        want = oracle.dma_attn(q, k, v, tile=w.tile, band=band, hi_fmt=hi_o, lo_fmt=lo_o, p_round=True)
-        got = out
-    else:
-        rows = oracle.sort_rows(rows)
-        want = oracle.dma_attn_rows(q, k, v, rows, tile=w.tile, band=band, hi_fmt=hi_o, lo_fmt=lo_o, p_round=True)
-        got = out[rows[:, 0], rows[:, 1], rows[:, 2]]
-    check_out(got, want, f"{w.name} band={band} lo={lo} hi={hi}")
+    kw = dict(tile=w.tile, band=band, hi_fmt=hi_o, lo_fmt=lo_o, p_round=True, sink=sink, causal=causal)
+    rows = oracle.all_rows(w.B, w.Hq, w.S) if rows is None else oracle.sort_rows(rows)
+    want, slack = oracle.dma_attn_rows(q, k, v, rows, with_slack=True, **kw)
+    got = out[rows[:, 0], rows[:, 1], rows[:, 2]]
+    check_out(got, want, f"{w.name} band={band} sink={sink} causal={causal} lo={lo} hi={hi}", slack)
     return out
 
 
@@ -282,3 +286,79 @@ def test_attn_odd_tile_count(dma, oracle):
     q, k, v = wl.generate(w)
     for band, lo, hi in ((2, "e2m1", "e4m3"), (0, "e2m1", "e2m1")):
         run_case(dma, oracle, w, q, k, v, band, lo, hi)
+
+
+# ------------------------------------------------------------------ E5M2, sink window, non-causal attention
+
+@pytest.mark.parametrize("is_query", [False, True])
+def test_quantize_e5m2_bit_exact(dma, oracle, is_query):
+    """MXFP8 with E5M2 elements (e_max = 15): random rows over many binades, the hand-built edge rows, values around
+    the largest finite magnitude, and every finite bf16 pattern alone in its block and next to a larger element."""
+    rng = np.random.Generator(np.random.Philox(991))
+    x = rng.standard_normal((777, 64)).astype(np.float32) * np.exp2(rng.integers(-20, 20, size=(777, 1))).astype(np.float32)
+    top = np.zeros((4, 64), dtype=np.float32)
+    top[0, :4] = [57344.0, 61440.0, 65536.0, -60000.0]
+    top[1, :4] = [32768.0, 2.0 ** -16, 3 * 2.0 ** -17, -(2.0 ** -17)]
+    top[2, :4] = [1.125, 1.375, 1.9, -1.0]
+    top[3, :2] = [3.0e38, 1.0]
+    pats = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    pats = pats[(pats & 0x7F80) != 0x7F80]
+    pat_rows = np.zeros((len(pats), 64), dtype=np.uint16)
+    pat_rows[:, 0] = pats                 # alone in block 0
+    pat_rows[:, 32] = pats                # next to 10.0 in block 1
+    pat_rows[:, 33] = 0x4120
+    bits = np.concatenate([edge_rows(64), wl.f32_to_bf16_bits(top), wl.f32_to_bf16_bits(x), pat_rows], axis=0)
+    (xd,) = to_gpu(dma, bits)
+    codes, scales = dma.dma_mx_quantize(xd, dma.FMT_MXFP8_E5M2, is_query)
+    torch.cuda.synchronize()
+    wc, ws = oracle.mx_quantize(bits, oracle.FMT_E5M2, is_query)
+    assert np.array_equal(scales.cpu().numpy(), ws)
+    assert np.array_equal(codes.cpu().numpy(), wc)
+
+
+def test_attn_e5m2_high_format(dma, oracle):
+    w = wl.CONFIGS["tiny"]
+    q, k, v = wl.generate(w)
+    for band, lo, hi in ((1, "e2m1", "e5m2"), (2, "e2m1", "e5m2"), (0, "e5m2", "e5m2")):
+        run_case(dma, oracle, w, q, k, v, band, lo, hi)
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=640, Hq=2, Hkv=2)
+    q, k, v = wl.generate(w)
+    run_case(dma, oracle, w, q, k, v, 2, "e2m1", "e5m2")
+    run_case(dma, oracle, w, q, k, v, 1, "e5m2", "e5m2")
+
+
+@pytest.mark.parametrize("band,sink", [(0, 1), (1, 1), (2, 1), (1, 3), (2, 5), (0, 100)])
+def test_attn_sink_window(dma, oracle, band, sink):
+    """First `sink` key tiles in the high format for every query tile: tiny config (4 tiles of 64) and the prefill
+    recipe at S=768 (6 tiles of 128), all rows; also the sink-like keys of the long-context recipe."""
+    w = wl.CONFIGS["tiny"]
+    q, k, v = wl.generate(w)
+    run_case(dma, oracle, w, q, k, v, band, "e2m1", "e4m3", sink=sink)
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=768, Hq=2, Hkv=2)
+    q, k, v = wl.generate(w)
+    run_case(dma, oracle, w, q, k, v, band, "e2m1", "e4m3", sink=sink)
+    w = wl.small_variant(wl.CONFIGS["gqa_32k"], S=640, Hq=8, Hkv=2)        # odd tile count: one tile per workgroup
+    q, k, v = wl.generate(w)
+    run_case(dma, oracle, w, q, k, v, band, "e2m1", "e4m3", sink=sink)
+    run_case(dma, oracle, w, q, k, v, band, "e2m1", "e2m1", sink=sink)      # one format: the sink changes nothing
+
+
+@pytest.mark.parametrize("lo,hi", FMT_PAIRS)
+@pytest.mark.parametrize("band,sink", [(0, 0), (1, 0), (2, 0), (3, 1), (100, 0)])
+def test_attn_noncausal(dma, oracle, band, sink, lo, hi):
+    """No causal mask: every key tile visited, window |jt - it| < band."""
+    w = wl.CONFIGS["tiny"]
+    q, k, v = wl.generate(w)
+    run_case(dma, oracle, w, q, k, v, band, lo, hi, sink=sink, causal=False)
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=1024, Hq=2, Hkv=1)
+    q, k, v = wl.generate(w)
+    rows = wl.sample_rows(w, [0, 1, 3, 4, 7], [(0, 0), (0, 1)], 64, 17)
+    run_case(dma, oracle, w, q, k, v, band, lo, hi, rows=rows, sink=sink, causal=False)
+
+
+def test_attn_noncausal_odd_tiles_and_batch(dma, oracle):
+    w = wl.small_variant(wl.CONFIGS["gqa_32k"], S=640, Hq=8, Hkv=2, B=2)
+    q, k, v = wl.generate(w)
+    rows = wl.sample_rows(w, [0, 2, 4], [(0, 0), (1, 5), (1, 7)], 64, 18)
+    run_case(dma, oracle, w, q, k, v, 2, "e2m1", "e4m3", rows=rows, causal=False)
+    run_case(dma, oracle, w, q, k, v, 1, "e2m1", "e4m3", rows=rows, sink=2, causal=False)

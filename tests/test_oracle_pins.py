@@ -462,3 +462,23 @@ def test_e5m2_high_format_in_attention(oracle, tiny):
     got = oracle.dma_attn(q, k, v, tile=w.tile, band=1, hi_fmt=oracle.FMT_E5M2)[0]
     want = brute.dma_attention(q[0], k[0], v[0], tile=w.tile, band=1, hi="e5m2")
     assert np.max(np.abs(got - want)) < 2e-6
+
+
+def test_rounding_slack_covers_binary32_scores(oracle):
+    """The slack the oracle reports must cover what changes when every score is first rounded to binary32 (which
+    flips the bf16 rounding of probabilities that sit on a midpoint), and must be zero for most elements."""
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=512, Hq=2, Hkv=1)
+    q, k, v = wl.generate(w)
+    rows = oracle.all_rows(w.B, w.Hq, w.S)
+    for band, hi, lo, bhi, blo in ((2, oracle.FMT_E4M3, oracle.FMT_E2M1, "e4m3", "e2m1"),
+                                   (0, oracle.FMT_E4M3, oracle.FMT_E4M3, "e4m3", "e4m3")):
+        want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=128, band=band, hi_fmt=hi, lo_fmt=lo, with_slack=True)
+        assert np.array_equal(want, oracle.dma_attn_rows(q, k, v, rows, tile=128, band=band, hi_fmt=hi, lo_fmt=lo))
+        got32 = brute.dma_attention(q[0], k[0], v[0], tile=128, band=band, hi=bhi, lo=blo, score_dtype=np.float32)
+        err = np.abs(got32.reshape(-1, w.D) - want)
+        assert np.max(err - slack) < 2e-5          # what is left is the smooth effect of the score rounding
+        assert np.median(slack.max(axis=1)) < 1e-6 and np.mean(slack) < 2e-4
+    # a probability exactly on a midpoint: two keys, scores 0 and log2(1 + 2^-8) - 1 ... built from p directly:
+    # one tile, key 0 has p = 1, key 1 has p = 0.501953125 = midpoint of bf16 neighbours 0.5 and 0.50390625
+    # (spacing 2^-8); check through the slack of a row whose second score is log2 of that midpoint
+    assert oracle.round_to_bf16(0.501953125) == 0.5           # the tie goes to the even neighbour
