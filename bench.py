@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch from the rocprofv3 --pmc runs summarised in profiles/ (FETCH_SIZE + WRITE_SIZE,
 # scaled by the same counters on a copy kernel of known size); None where not measured.
-MEASURED_TRAFFIC_BYTES = {"prefill_8k": 935.6e6}       # profiles/dma_attn_fwd_prefill_8k.md, section 2
+MEASURED_TRAFFIC_BYTES = {"prefill_8k": 436.8e6}       # profiles/dma_attn_fwd_prefill_8k.md, section 2
 COPY_CALIBRATION_BYTES = 1 << 29      # dma_diag_copy reads and writes this many bytes once per run
 
 
@@ -142,6 +142,22 @@ def main():
     quant_s = ev0.elapsed_time(ev1) * 1e-3 / 10
     quant_bytes = qd.numel() * (2 + 0.5 + 1 + 2 / 32)
 
+    # the same kernel on 2^24 rows x 128 (4 GiB of bf16 in, 3.1 GiB out): far beyond the 256 MB last-level cache,
+    # so this one is a pure HBM streaming figure
+    big_rows = 1 << 24
+    xb = torch.empty((big_rows, 128), dtype=torch.bfloat16, device="cuda")
+    xb.view(torch.int16).random_(0, 0x7F00)                # finite bf16 bit patterns over every binade
+    qb = binding.dma_mx_quantize_dual(xb, False)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(3):
+        binding.dma_mx_quantize_dual(xb, False, out=qb)
+    ev1.record()
+    torch.cuda.synchronize()
+    quant_big_s = ev0.elapsed_time(ev1) * 1e-3 / 3
+    quant_big_bytes = xb.numel() * (2 + 0.5 + 1 + 2 / 32)
+    del xb, qb
+
     # one plain copy of known size, untimed: the reference dispatch for scaling FETCH_SIZE / WRITE_SIZE under rocprofv3
     csrc = torch.empty(COPY_CALIBRATION_BYTES, dtype=torch.uint8, device="cuda")
     cdst = torch.empty_like(csrc)
@@ -164,7 +180,10 @@ def main():
         "roofline": roofline(w, band, kernel_s),
         "quantizer": {"kernel": "mx_quantize_kernel (dual)", "elements": qd.numel(), "us": round(quant_s * 1e6, 2),
                       "achieved_GBps": round(quant_bytes / quant_s / 1e9, 1), "peak_GBps": HBM_PEAK_GBS,
-                      "frac": round(quant_bytes / quant_s / 1e9 / HBM_PEAK_GBS, 4)},
+                      "frac": round(quant_bytes / quant_s / 1e9 / HBM_PEAK_GBS, 4),
+                      "streaming": {"elements": big_rows * 128, "us": round(quant_big_s * 1e6, 1),
+                                    "achieved_GBps": round(quant_big_bytes / quant_big_s / 1e9, 1),
+                                    "frac": round(quant_big_bytes / quant_big_s / 1e9 / HBM_PEAK_GBS, 4)}},
         "kernel_ms": round(kernel_s * 1e3, 4),
     }
     if not args.no_cpu_baseline:
