@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_query_prescale.argtypes = [ctypes.c_int]
         L.oracle_mx_quantize.restype = ctypes.c_int
         L.oracle_mx_quantize.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, u8p, u8p]
+        L.oracle_mx_quantize_ex.restype = ctypes.c_int
+        L.oracle_mx_quantize_ex.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, u8p, u8p, f32p]
         L.oracle_mx_dequantize.restype = ctypes.c_int
         L.oracle_mx_dequantize.argtypes = [u8p, u8p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, f64p]
         L.oracle_dma_attn_rows.restype = ctypes.c_int
@@ -74,7 +76,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_dma_attn_rows_ex.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                              i64p, ctypes.c_int64, f32p, f32p]
+                                              ctypes.c_int, i64p, ctypes.c_int64, f32p, f32p]
         L.oracle_ref_attn_rows.restype = ctypes.c_int
         L.oracle_ref_attn_rows.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_int64, ctypes.c_int, i64p, ctypes.c_int64, f64p]
@@ -154,14 +156,21 @@ def num_threads() -> int:
 
 # ---- tensor functions --------------------------------------------------------------------------
 
-def mx_quantize(x_bits, fmt: int, is_query: bool):
-    """x_bits: [..., D] uint16 (bf16 bits).  Returns (codes uint8 [..., D or D/2], scales uint8 [..., D/32])."""
+def mx_quantize(x_bits, fmt: int, is_query: bool, per_token: bool = False):
+    """x_bits: [..., D] uint16 (bf16 bits).  Returns (codes uint8 [..., D or D/2], scales uint8 [..., D/32]) and,
+    with per_token (Alg. 2 Step 2), also the per-row scale S_q as float32 [...]."""
     x = _as_bits(x_bits)
     D = x.shape[-1]
     rows = x.size // D
     cb = D // 2 if fmt == FMT_E2M1 else D
     codes = np.zeros(x.shape[:-1] + (cb,), dtype=np.uint8)
     scales = np.zeros(x.shape[:-1] + (D // 32,), dtype=np.uint8)
+    if per_token:
+        ts = np.zeros(x.shape[:-1], dtype=np.float32)
+        _check(lib().oracle_mx_quantize_ex(_p(x, ctypes.c_uint16), rows, D, fmt, int(bool(is_query)),
+                                           _p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint8), _p(ts, ctypes.c_float)),
+               "oracle_mx_quantize_ex")
+        return codes, scales, ts
     _check(lib().oracle_mx_quantize(_p(x, ctypes.c_uint16), rows, D, fmt, int(bool(is_query)),
                                     _p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint8)), "oracle_mx_quantize")
     return codes, scales
@@ -188,10 +197,10 @@ def sort_rows(rows) -> np.ndarray:
 
 def dma_attn_rows(q_bits, k_bits, v_bits, rows, *, tile: int, band: int, hi_fmt: int = FMT_E4M3,
                   lo_fmt: int = FMT_E2M1, p_round: bool = True, sink: int = 0, causal: bool = True,
-                  with_slack: bool = False):
+                  per_token: bool = False, with_slack: bool = False):
     """Diagonal-tiled attention output for the given (b, hq, i) rows -> float32 [n_rows, D].
     sink: number of leading key tiles kept in the high format; causal=False: every key tile is visited and the
-    high-precision window is |jt - it| < band.  with_slack: also return, per output element, how far the
+    high-precision window is |jt - it| < band.  per_token: Alg. 2 Step 2 on queries and keys.  with_slack: also return, per output element, how far the
     value can move when probabilities that lie within binary32 score noise of a bf16 rounding midpoint round
     the other way (see attn_one_row in dma_oracle.c)."""
     q, k, v = _as_bits(q_bits), _as_bits(k_bits), _as_bits(v_bits)
@@ -202,7 +211,8 @@ def dma_attn_rows(q_bits, k_bits, v_bits, rows, *, tile: int, band: int, hi_fmt:
     out = np.empty((r.shape[0], D), dtype=np.float32)
     slack = np.zeros((r.shape[0], D), dtype=np.float32) if with_slack else None
     _check(lib().oracle_dma_attn_rows_ex(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
-                                         B, Hq, Hkv, S, D, tile, band, int(sink), int(bool(causal)), hi_fmt, lo_fmt,
+                                         B, Hq, Hkv, S, D, tile, band, int(sink), int(bool(causal)), int(bool(per_token)),
+                                         hi_fmt, lo_fmt,
                                          int(bool(p_round)), _p(r, ctypes.c_int64), r.shape[0],
                                          _p(out, ctypes.c_float), _p(slack, ctypes.c_float) if with_slack else None),
            "oracle_dma_attn_rows_ex")

@@ -193,20 +193,55 @@ float oracle_query_prescale(int D)
 /* MX quantization of a [rows, D] bf16 matrix (Alg. 2, Steps 1 and 3-7)                       */
 /* ------------------------------------------------------------------------------------------ */
 
-/* Quantize one row.  codes: D bytes (E4M3) or D/2 bytes (E2M1, element 2t in the low nibble and
- * 2t+1 in the high nibble: Alg. 2 Step 5 and "Packing").  scales: D/32 bytes.
- * Reading: the per-token scale S_q of Alg. 2 Step 2 is 1 on this path (it exists to fit the
- * E4M3-typed scale of NVFP4; an E8M0 scale already spans the binary32 range, Sec. 3.1). */
-static void quantize_row(const uint16_t *x, int D, int fmt, int is_query, uint8_t *codes, uint8_t *scales)
+/* The per-token scale of Alg. 2 Step 2 for a row whose absolute maximum (after Step 1) is amax:
+ * S_q = amax / (448 * 6), and the factor the row is multiplied by, 1 / S_q.
+ * Reading: both are ONE binary32 division each (amax / 2688 and 2688 / amax), and X / S_q is the
+ * binary32 product X * (2688 / amax).  Rows with amax below 2^-100 (zero rows included) are left
+ * alone (S_q = 1): their reciprocal would overflow. */
+void oracle_token_scale(float amax, float *s_q, float *inv_s_q)
+{
+    if (!(amax >= 0x1p-100f)) { *s_q = 1.0f; *inv_s_q = 1.0f; return; }
+    volatile float a = amax / 2688.0f, b = 2688.0f / amax;
+    *s_q = a;
+    *inv_s_q = b;
+}
+
+/* Quantize one row.  codes: D bytes (E4M3, E5M2) or D/2 bytes (E2M1, element 2t in the low nibble
+ * and 2t+1 in the high nibble: Alg. 2 Step 5 and "Packing").  scales: D/32 bytes.
+ * per_token == 0.  Reading: the per-token scale S_q of Alg. 2 Step 2 is 1 on the default path (it
+ * exists to fit the E4M3-typed scale of NVFP4; an E8M0 scale already spans the binary32 range,
+ * Sec. 3.1).
+ * per_token != 0: Alg. 2 Step 2 as printed: the row is divided by S_q = max_D|X| / (448 * 6) before
+ * the shared scales are formed; *token_scale receives S_q (the dequantized row is decode * S_q). */
+static void quantize_row(const uint16_t *x, int D, int fmt, int is_query, int per_token, uint8_t *codes,
+                         uint8_t *scales, float *token_scale)
 {
     const float c = oracle_query_prescale(D);
     float xs[32];
+    float s_q = 1.0f, inv_s_q = 1.0f;
+    if (per_token) {
+        float rmax = 0.0f;
+        for (int d = 0; d < D; ++d) {
+            float v = oracle_bf16_to_f32(x[d]);
+            if (is_query) {
+                volatile float prod = v * c;
+                v = prod;
+            }
+            if (fabsf(v) > rmax) rmax = fabsf(v);
+        }
+        oracle_token_scale(rmax, &s_q, &inv_s_q);
+    }
+    if (token_scale) *token_scale = s_q;
     for (int blk = 0; blk < D / 32; ++blk) {
         float amax = 0.0f;
         for (int t = 0; t < 32; ++t) {
             float v = oracle_bf16_to_f32(x[blk * 32 + t]);
             if (is_query) {
                 volatile float prod = v * c;     /* one binary32 multiply, rounded once */
+                v = prod;
+            }
+            if (per_token) {
+                volatile float prod = v * inv_s_q;   /* X / S_q, one binary32 multiply */
                 v = prod;
             }
             xs[t] = v;
@@ -235,16 +270,24 @@ static void quantize_row(const uint16_t *x, int D, int fmt, int is_query, uint8_
     }
 }
 
-int oracle_mx_quantize(const uint16_t *x, int64_t rows, int D, int fmt, int is_query,
-                       uint8_t *codes, uint8_t *scales)
+/* token_scales: NULL = Step 2 skipped (S_q = 1); else [rows] binary32, receives S_q of every row. */
+int oracle_mx_quantize_ex(const uint16_t *x, int64_t rows, int D, int fmt, int is_query,
+                          uint8_t *codes, uint8_t *scales, float *token_scales)
 {
     if (!x || !codes || !scales || rows < 0 || D <= 0 || D % 32 != 0) return ORACLE_ERR_ARG;
     if (!fmt_is_mx(fmt)) return ORACLE_ERR_ARG;
     const int64_t cb = (fmt == ORACLE_FMT_E2M1) ? D / 2 : D;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r)
-        quantize_row(x + r * D, D, fmt, is_query, codes + r * cb, scales + r * (D / 32));
+        quantize_row(x + r * D, D, fmt, is_query, token_scales != NULL, codes + r * cb, scales + r * (D / 32),
+                     token_scales ? token_scales + r : NULL);
     return ORACLE_OK;
+}
+
+int oracle_mx_quantize(const uint16_t *x, int64_t rows, int D, int fmt, int is_query,
+                       uint8_t *codes, uint8_t *scales)
+{
+    return oracle_mx_quantize_ex(x, rows, D, fmt, is_query, codes, scales, NULL);
 }
 
 /* Decode codes + scales back to real values: element * 2^(scale - 127), exact in double. */
@@ -276,7 +319,7 @@ int oracle_mx_dequantize(const uint8_t *codes, const uint8_t *scales, int64_t ro
 /* What a row looks like to the score product in format fmt, as doubles:
  * quantized formats: quantize then decode; bf16: the values themselves (the softmax factor is
  * then applied to the score, see score_scale()). */
-static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, double *out)
+static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, int per_token, double *out)
 {
     if (fmt == ORACLE_FMT_BF16) {
         for (int d = 0; d < D; ++d) out[d] = (double)oracle_bf16_to_f32(x[d]);
@@ -284,9 +327,12 @@ static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, double 
     }
     uint8_t codes[1024];
     uint8_t scales[64];
+    float s_q = 1.0f;
     memset(codes, 0, sizeof codes);
-    quantize_row(x, D, fmt, is_query, codes, scales);
+    quantize_row(x, D, fmt, is_query, per_token, codes, scales, &s_q);
     oracle_mx_dequantize(codes, scales, 1, D, fmt, out);
+    if (per_token)
+        for (int d = 0; d < D; ++d) out[d] *= (double)s_q;       /* the dequantization multiplier of Step 2 */
 }
 
 /* ------------------------------------------------------------------------------------------ */
@@ -316,6 +362,9 @@ static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, double 
  *           of diagonal and sink windows).
  *   causal == 0 : every key tile is visited, nothing is masked, and the window is the tiles with
  *           |jt - it| < band (Sec. 4.1, "Compatibility with Non-Causal Attention").
+ *   per_token : queries and keys go through Alg. 2 Step 2 (row divided by S_q = rowmax / 2688 before
+ *           quantization, the decoded row multiplied by S_q again), the "Per-Token" granularity of
+ *           Sec. 5.3; the scores are then S_q[i] * S_q[j] * (q^ . k^).
  *   Reading: the printed tile ranges of the non-causal case mix index bases and the paper gives
  *   no loop for the sink window; it argues that any order that covers every tile once is valid.
  *   Here every variant visits the key tiles in ascending order, each in the format the rule
@@ -330,12 +379,12 @@ static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, double 
  * the output can move through flips that binary32 scores can cause. */
 static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const double *kseen_hi,
                          const uint16_t *v, int64_t i, int64_t S, int D, int tile, int band, int sink,
-                         int causal, int hi_fmt, int lo_fmt, int p_round, float *out, float *slack)
+                         int causal, int per_token, int hi_fmt, int lo_fmt, int p_round, float *out, float *slack)
 {
     double q_lo[512], q_hi[512], O[512], SL[512];
     double *s = (double *)malloc(sizeof(double) * (size_t)tile);
-    row_as_seen(qrow, D, lo_fmt, 1, q_lo);
-    row_as_seen(qrow, D, hi_fmt, 1, q_hi);
+    row_as_seen(qrow, D, lo_fmt, 1, per_token, q_lo);
+    row_as_seen(qrow, D, hi_fmt, 1, per_token, q_hi);
     const double c = 1.4426950408889634074 / sqrt((double)D);
     const double sc_lo = (lo_fmt == ORACLE_FMT_BF16) ? c : 1.0;   /* bf16 rows are not pre-scaled */
     const double sc_hi = (hi_fmt == ORACLE_FMT_BF16) ? c : 1.0;
@@ -401,12 +450,12 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
 }
 
 /* Keys of one kv head as seen in a format, rows 0 .. n-1, [n, D] doubles. */
-static double *keys_as_seen(const uint16_t *k, int64_t n, int D, int fmt)
+static double *keys_as_seen(const uint16_t *k, int64_t n, int D, int fmt, int per_token)
 {
     double *out = (double *)malloc(sizeof(double) * (size_t)n * (size_t)D);
     if (!out) return NULL;
 #pragma omp parallel for schedule(static)
-    for (int64_t r = 0; r < n; ++r) row_as_seen(k + r * D, D, fmt, 0, out + r * D);
+    for (int64_t r = 0; r < n; ++r) row_as_seen(k + r * D, D, fmt, 0, per_token, out + r * D);
     return out;
 }
 
@@ -418,8 +467,8 @@ static double *keys_as_seen(const uint16_t *k, int64_t n, int D, int fmt)
  */
 int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq,
                             int Hkv, int64_t S, int D, int tile, int band, int sink, int causal,
-                            int hi_fmt, int lo_fmt, int p_round, const int64_t *rows, int64_t n_rows,
-                            float *out, float *slack)
+                            int per_token, int hi_fmt, int lo_fmt, int p_round, const int64_t *rows,
+                            int64_t n_rows, float *out, float *slack)
 {
     if (!q || !k || !v || !out || (!rows && n_rows > 0)) return ORACLE_ERR_ARG;
     if (sink < 0 || (!causal && S % tile != 0)) return ORACLE_ERR_ARG;
@@ -448,14 +497,14 @@ int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t
         if (!causal) imax = S - 1;
         const uint16_t *kh = k + ((int64_t)b * Hkv + hkv) * S * D;
         const uint16_t *vh = v + ((int64_t)b * Hkv + hkv) * S * D;
-        double *klo = keys_as_seen(kh, imax + 1, D, lo_fmt);
-        double *khi = (hi_fmt == lo_fmt) ? klo : keys_as_seen(kh, imax + 1, D, hi_fmt);
+        double *klo = keys_as_seen(kh, imax + 1, D, lo_fmt, per_token);
+        double *khi = (hi_fmt == lo_fmt) ? klo : keys_as_seen(kh, imax + 1, D, hi_fmt, per_token);
         if (!klo || !khi) { free(klo); if (khi != klo) free(khi); return ORACLE_ERR_MEM; }
 #pragma omp parallel for schedule(dynamic, 1)
         for (int64_t r = r0; r < r1; ++r) {
             const int64_t hq = rows[3 * r + 1], i = rows[3 * r + 2];
             const uint16_t *qrow = q + (((int64_t)b * Hq + hq) * S + i) * D;
-            attn_one_row(qrow, klo, khi, vh, i, S, D, tile, band, sink, causal, hi_fmt, lo_fmt, p_round, out + r * D,
+            attn_one_row(qrow, klo, khi, vh, i, S, D, tile, band, sink, causal, per_token, hi_fmt, lo_fmt, p_round, out + r * D,
                          slack ? slack + r * D : NULL);
         }
         if (khi != klo) free(khi);
@@ -470,7 +519,7 @@ int oracle_dma_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v
                          int Hkv, int64_t S, int D, int tile, int band, int hi_fmt, int lo_fmt,
                          int p_round, const int64_t *rows, int64_t n_rows, float *out)
 {
-    return oracle_dma_attn_rows_ex(q, k, v, B, Hq, Hkv, S, D, tile, band, 0, 1, hi_fmt, lo_fmt, p_round, rows,
+    return oracle_dma_attn_rows_ex(q, k, v, B, Hq, Hkv, S, D, tile, band, 0, 1, 0, hi_fmt, lo_fmt, p_round, rows,
                                    n_rows, out, NULL);
 }
 

@@ -66,13 +66,23 @@ def quantize_block(x32: np.ndarray, fmt: str):
     return sb, codes, dec
 
 
-def quantize_rows(bits: np.ndarray, fmt: str, is_query: bool):
-    """bits: [rows, D] uint16.  Returns (scales[rows, D/32], codes[rows, D] unpacked, decoded[rows, D])."""
+def quantize_rows(bits: np.ndarray, fmt: str, is_query: bool, per_token: bool = False, return_token_scale=False):
+    """bits: [rows, D] uint16.  Returns (scales[rows, D/32], codes[rows, D] unpacked, decoded[rows, D]).
+    per_token: Alg. 2 Step 2: every row is first multiplied by 2688 / rowmax (float32), and the decoded row by
+    rowmax / 2688 (float32); rows whose maximum is below 2^-100 are left alone."""
     rows, D = bits.shape
     x = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
     if is_query:
         c = np.float32(np.log2(np.e) / np.sqrt(np.float64(D)))
         x = (x * c).astype(np.float32)            # one float32 multiply per element
+    s_q = np.ones(rows, dtype=np.float32)
+    if per_token:
+        rmax = np.max(np.abs(x), axis=1).astype(np.float32)
+        ok = rmax >= np.float32(2.0 ** -100)
+        inv = np.ones(rows, dtype=np.float32)
+        inv[ok] = np.float32(2688.0) / rmax[ok]
+        s_q[ok] = rmax[ok] / np.float32(2688.0)
+        x = (x * inv[:, None]).astype(np.float32)
     scales = np.zeros((rows, D // 32), dtype=np.uint8)
     codes = np.zeros((rows, D), dtype=np.uint8)
     dec = np.zeros((rows, D))
@@ -82,6 +92,9 @@ def quantize_rows(bits: np.ndarray, fmt: str, is_query: bool):
             scales[r, b] = sb
             codes[r, 32 * b:32 * b + 32] = cd
             dec[r, 32 * b:32 * b + 32] = de
+    dec = dec * s_q.astype(np.float64)[:, None]
+    if return_token_scale:
+        return scales, codes, dec, s_q
     return scales, codes, dec
 
 
@@ -107,7 +120,7 @@ def round_bf16_nearest_of_two(p: np.ndarray) -> np.ndarray:
 
 
 def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p_round=True, sink=0, causal=True,
-                  score_dtype=np.float64):
+                  score_dtype=np.float64, per_token=False):
     """Per-element rewrite of the diagonal-tiled attention for q[Hq,S,D], k,v[Hkv,S,D] (one batch).
 
     For every visible pair (i, j) the score comes from the format of the tile pair (i // tile, j // tile):
@@ -121,10 +134,10 @@ def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p
     out = np.zeros((Hq, S, D))
     v = bf16_bits_to_f64(v_bits)
     for h in range(Hq):
-        _, _, q_hi = quantize_rows(q_bits[h], hi, True)
-        _, _, q_lo = quantize_rows(q_bits[h], lo, True)
-        _, _, k_hi = quantize_rows(k_bits[h // g], hi, False)
-        _, _, k_lo = quantize_rows(k_bits[h // g], lo, False)
+        _, _, q_hi = quantize_rows(q_bits[h], hi, True, per_token)
+        _, _, q_lo = quantize_rows(q_bits[h], lo, True, per_token)
+        _, _, k_hi = quantize_rows(k_bits[h // g], hi, False, per_token)
+        _, _, k_lo = quantize_rows(k_bits[h // g], lo, False, per_token)
         s_hi = q_hi @ k_hi.T
         s_lo = q_lo @ k_lo.T
         ti = np.arange(S)[:, None] // tile

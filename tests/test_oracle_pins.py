@@ -482,3 +482,58 @@ def test_rounding_slack_covers_binary32_scores(oracle):
     # one tile, key 0 has p = 1, key 1 has p = 0.501953125 = midpoint of bf16 neighbours 0.5 and 0.50390625
     # (spacing 2^-8); check through the slack of a row whose second score is log2 of that midpoint
     assert oracle.round_to_bf16(0.501953125) == 0.5           # the tie goes to the even neighbour
+
+
+# ------------------------------------------------------------------ per-token scale (Alg. 2 Step 2)
+
+def test_token_scale_fixed_points(oracle):
+    x = np.zeros((6, 64), dtype=np.float32)
+    x[0, 7] = 2688.0                       # S_q = 1: Step 2 changes nothing
+    x[0, 40] = -3.0
+    x[1, 3] = -2688.0 * 2.0 ** -9          # S_q = 2^-9 exactly
+    x[1, 35] = 1.5 * 2.0 ** -9
+    x[2, :] = 0.0                          # zero row: left alone
+    x[3, 0] = 2.0 ** -110                  # below 2^-100: left alone
+    x[4, 5] = 1.0                          # S_q = 1/2688
+    x[5, :] = np.linspace(-5, 7, 64)
+    bits = wl.f32_to_bf16_bits(x)
+    for fmt in (oracle.FMT_E2M1, oracle.FMT_E4M3):
+        c0, s0 = oracle.mx_quantize(bits, fmt, False)
+        c1, s1, ts = oracle.mx_quantize(bits, fmt, False, per_token=True)
+        assert ts[0] == 1.0 and np.array_equal(c0[0], c1[0]) and np.array_equal(s0[0], s1[0])
+        assert ts[1] == np.float32(2.0 ** -9) and ts[2] == 1.0 and ts[3] == 1.0
+        assert np.array_equal(c0[2:4], c1[2:4]) and np.array_equal(s0[2:4], s1[2:4])
+        assert ts[4] == np.float32(1.0) / np.float32(2688.0)
+        dec = oracle.mx_dequantize(c1, s1, fmt) * ts.astype(np.float64)[:, None]
+        # the row maximum lands on 2688 = 5.25 * 2^9 = 336 * 2^3: E2M1 rounds 5.25 up to 6, E4M3 has 336 on the
+        # midpoint of 320 and 352 and takes the even mantissa (320)
+        want_max = (6.0 * 512.0) if fmt == oracle.FMT_E2M1 else (320.0 * 8.0)
+        assert dec[1, 3] == -want_max * 2.0 ** -9
+        assert abs(dec[4, 5] - want_max / 2688.0) < 1e-6
+        assert s1[1, 0] == (127 + 9 if fmt == oracle.FMT_E2M1 else 127 + 3)
+        assert s1[1, 1] == s0[1, 1] + 9    # the other block of row 1 is just shifted by the power of two
+
+
+def test_token_scale_matches_bruteforce(oracle, tiny):
+    w, q, k, v = tiny
+    for x, is_q in ((q[0, 0, :40], True), (k[0, 1, 60:100], False)):
+        for fmt, name in ((oracle.FMT_E2M1, "e2m1"), (oracle.FMT_E4M3, "e4m3"), (oracle.FMT_E5M2, "e5m2")):
+            codes, scales, ts = oracle.mx_quantize(x, fmt, is_q, per_token=True)
+            bs, bc, bd, bts = brute.quantize_rows(x, name, is_q, per_token=True, return_token_scale=True)
+            assert np.array_equal(ts, bts) and np.array_equal(scales, bs)
+            assert np.array_equal(codes, brute.pack_fp4(bc) if fmt == oracle.FMT_E2M1 else bc)
+            assert np.array_equal(oracle.mx_dequantize(codes, scales, fmt) * ts.astype(np.float64)[:, None], bd)
+
+
+@pytest.mark.parametrize("band,causal", [(0, True), (1, True), (2, False)])
+@pytest.mark.parametrize("p_round", [False, True])
+def test_token_scale_attention_matches_per_element_rewrite(oracle, tiny, band, causal, p_round):
+    w, q, k, v = tiny
+    got = oracle.dma_attn(q, k, v, tile=w.tile, band=band, p_round=p_round, causal=causal, per_token=True)[0]
+    want = brute.dma_attention(q[0], k[0], v[0], tile=w.tile, band=band, p_round=p_round, causal=causal, per_token=True)
+    assert np.max(np.abs(got - want)) < 2e-6
+    # unquantized operands ignore the option
+    a = oracle.dma_attn(q, k, v, tile=w.tile, band=band, hi_fmt=oracle.FMT_BF16, lo_fmt=oracle.FMT_BF16, causal=causal)
+    b = oracle.dma_attn(q, k, v, tile=w.tile, band=band, hi_fmt=oracle.FMT_BF16, lo_fmt=oracle.FMT_BF16, causal=causal,
+                        per_token=True)
+    assert np.array_equal(a, b)
