@@ -59,6 +59,14 @@ enum {
 int dma_mx_quantize(const void* x_bf16, int64_t rows, int D, int fmt, int is_query,
                     void* codes_u8, void* scales_u8, void* stream);
 
+/* dma_mx_quantize with Step 2 of Alg. 2 applied (the "Per-Token" granularity of Sec. 5.3): every row is first divided
+ * by S_q = max_D|x| / (448 * 6) (as one binary32 multiplication by 2688 / max), then quantized as above;
+ * token_scales_f32 [rows] float32, device, out, receives S_q (the dequantized row is decode * 2^(scale-127) * S_q).
+ * Rows whose maximum is below 2^-100 keep S_q = 1.  D / 8 must be a power of two <= 64 (D in 32, 64, 128, 256, 512),
+ * else DMA_ERR_UNSUPPORTED. */
+int dma_mx_quantize_token(const void* x_bf16, int64_t rows, int D, int fmt, int is_query,
+                          void* codes_u8, void* scales_u8, void* token_scales_f32, void* stream);
+
 /* The same with both formats produced from ONE read of x (the "MP" fusion of Alg. 2: low copy =
  * MXFP4 E2M1, high copy = MXFP8 E4M3).  Buffers as above. */
 int dma_mx_quantize_dual(const void* x_bf16, int64_t rows, int D, int is_query,
@@ -99,7 +107,9 @@ typedef struct dma_attn_opts {
     int sink_tiles;       /* >= 0: the first sink_tiles key tiles are computed in hi_fmt for every query tile (Sec. 5.3,
                              the sink window of the diagonal/sink table); 0 = Alg. 1 as printed */
     int pv_fmt;           /* must be DMA_FMT_BF16 (V and P stay 16-bit, as in Alg. 1) */
-    int per_token_scale;  /* must be 0 (Alg. 2 Step 2 is the identity on this path) */
+    int per_token_scale;  /* 0: Alg. 2 Step 2 is the identity (default).  1: queries and keys go through Step 2 (row divided by
+                             S_q = rowmax / 2688 before quantization) and the score product is multiplied by S_q of its
+                             query and of its key; ignored for DMA_FMT_BF16 operands; not with fp8_mfma = 1 */
     int fp8_mfma;         /* how MXFP8 tiles form Q K^T.
                              0 (default): the E4M3 codes and E8M0 scales are decoded exactly to bf16 and
                                multiplied on the bf16 MFMA: the product of the quantized operands is exact up to

@@ -17,7 +17,7 @@ FMT_MXFP8_E4M3 = 1
 FMT_MXFP4_E2M1 = 2
 FMT_MXFP8_E5M2 = 3
 
-EXPORTS = ("dma_mx_quantize", "dma_mx_quantize_dual", "dma_attn_fwd", "dma_attn_fwd_ex",
+EXPORTS = ("dma_mx_quantize", "dma_mx_quantize_token", "dma_mx_quantize_dual", "dma_attn_fwd", "dma_attn_fwd_ex",
            "dma_attn_fwd_workspace_bytes", "dma_diag_copy", "dma_error_string", "dma_version")
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdma_mi355x.so")
@@ -49,6 +49,8 @@ def load() -> ctypes.CDLL:
         vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         L.dma_mx_quantize.restype = ci
         L.dma_mx_quantize.argtypes = [vp, i64, ci, ci, ci, vp, vp, vp]
+        L.dma_mx_quantize_token.restype = ci
+        L.dma_mx_quantize_token.argtypes = [vp, i64, ci, ci, ci, vp, vp, vp, vp]
         L.dma_mx_quantize_dual.restype = ci
         L.dma_mx_quantize_dual.argtypes = [vp, i64, ci, ci, vp, vp, vp, vp, vp]
         L.dma_attn_fwd.restype = ci
@@ -102,6 +104,22 @@ def dma_mx_quantize(x: torch.Tensor, fmt: int, is_query: bool, codes: torch.Tens
     return codes, scales
 
 
+def dma_mx_quantize_token(x: torch.Tensor, fmt: int, is_query: bool):
+    """dma_mx_quantize with the per-token scale of Alg. 2 Step 2: returns (codes, scales, token_scales float32 [...])."""
+    D = x.shape[-1]
+    rows = x.numel() // D
+    cb = D // 2 if fmt == FMT_MXFP4_E2M1 else D
+    codes = torch.empty(x.shape[:-1] + (cb,), dtype=torch.uint8, device=x.device)
+    scales = torch.empty(x.shape[:-1] + (D // 32,), dtype=torch.uint8, device=x.device)
+    ts = torch.empty(x.shape[:-1], dtype=torch.float32, device=x.device)
+    rc = load().dma_mx_quantize_token(_dev(x, torch.bfloat16, "x"), rows, D, fmt, int(bool(is_query)),
+                                      _dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"),
+                                      _dev(ts, torch.float32, "token_scales"), _stream())
+    if rc:
+        raise DmaError(rc, "dma_mx_quantize_token")
+    return codes, scales, ts
+
+
 def dma_mx_quantize_dual(x: torch.Tensor, is_query: bool, out=None):
     """One read of x -> (codes_lo, scales_lo, codes_hi, scales_hi): MXFP4 E2M1 and MXFP8 E4M3 copies."""
     D = x.shape[-1]
@@ -120,7 +138,7 @@ def dma_mx_quantize_dual(x: torch.Tensor, is_query: bool, out=None):
 
 def dma_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, diag_band_tiles: int,
                  hi_fmt: int = FMT_MXFP8_E4M3, lo_fmt: int = FMT_MXFP4_E2M1, causal: bool = True,
-                 tile: int | None = None, fp8_mfma: bool = False, sink_tiles: int = 0,
+                 tile: int | None = None, fp8_mfma: bool = False, sink_tiles: int = 0, per_token_scale: bool = False,
                  out: torch.Tensor | None = None) -> torch.Tensor:
     """q [B,Hq,S,D], k/v [B,Hkv,S,D] bf16 -> out [B,Hq,S,D] float32.  With tile=None, fp8_mfma=False and
     sink_tiles=0 this is dma_attn_fwd (logical tile 128); otherwise dma_attn_fwd_ex with those options."""
@@ -133,10 +151,10 @@ def dma_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, diag_band
     args = [_dev(q, torch.bfloat16, "q"), _dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v"),
             _dev(out, torch.float32, "out"), B, Hq, Hkv, S, D, int(bool(causal)), int(diag_band_tiles),
             int(hi_fmt), int(lo_fmt)]
-    if tile is None and not fp8_mfma and not sink_tiles:
+    if tile is None and not fp8_mfma and not sink_tiles and not per_token_scale:
         rc = load().dma_attn_fwd(*args, _stream())
     else:
-        opts = AttnOpts(tile=int(tile or 0), sink_tiles=int(sink_tiles), pv_fmt=FMT_BF16, per_token_scale=0,
+        opts = AttnOpts(tile=int(tile or 0), sink_tiles=int(sink_tiles), pv_fmt=FMT_BF16, per_token_scale=int(bool(per_token_scale)),
                         fp8_mfma=int(bool(fp8_mfma)))
         rc = load().dma_attn_fwd_ex(*args, ctypes.byref(opts), _stream())
     if rc:

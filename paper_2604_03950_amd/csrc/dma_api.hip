@@ -22,22 +22,35 @@ int check_quant_common(const void* x, int64_t rows, int D)
 
 }  // namespace
 
-extern "C" {
-
-int dma_mx_quantize(const void* x_bf16, int64_t rows, int D, int fmt, int is_query, void* codes_u8,
-                    void* scales_u8, void* stream)
+static int quantize_one(const void* x_bf16, int64_t rows, int D, int fmt, int is_query, void* codes_u8,
+                        void* scales_u8, float* token_scales, bool per_token, void* stream)
 {
     int rc = check_quant_common(x_bf16, rows, D);
     if (rc != DMA_OK) return rc;
     if (fmt != DMA_FMT_MXFP8_E4M3 && fmt != DMA_FMT_MXFP4_E2M1 && fmt != DMA_FMT_MXFP8_E5M2) return DMA_ERR_INVALID_ARG;
     if (rows == 0) return DMA_OK;
-    if (!codes_u8 || !scales_u8) return DMA_ERR_INVALID_ARG;
+    if (!codes_u8 || !scales_u8 || (per_token && !token_scales)) return DMA_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(codes_u8) & 7u) != 0) return DMA_ERR_INVALID_ARG;
+    if (per_token && (reinterpret_cast<uintptr_t>(token_scales) & 3u) != 0) return DMA_ERR_INVALID_ARG;
     if (fmt == DMA_FMT_MXFP4_E2M1)
         return dma::launch_mx_quantize(x_bf16, rows, D, 2, is_query != 0, codes_u8, scales_u8, nullptr, nullptr,
-                                       (hipStream_t)stream);
+                                       token_scales, (hipStream_t)stream);
     return dma::launch_mx_quantize(x_bf16, rows, D, fmt == DMA_FMT_MXFP8_E5M2 ? 4 : 1, is_query != 0, nullptr, nullptr,
-                                   codes_u8, scales_u8, (hipStream_t)stream);
+                                   codes_u8, scales_u8, token_scales, (hipStream_t)stream);
+}
+
+extern "C" {
+
+int dma_mx_quantize(const void* x_bf16, int64_t rows, int D, int fmt, int is_query, void* codes_u8,
+                    void* scales_u8, void* stream)
+{
+    return quantize_one(x_bf16, rows, D, fmt, is_query, codes_u8, scales_u8, nullptr, false, stream);
+}
+
+int dma_mx_quantize_token(const void* x_bf16, int64_t rows, int D, int fmt, int is_query, void* codes_u8,
+                          void* scales_u8, void* token_scales_f32, void* stream)
+{
+    return quantize_one(x_bf16, rows, D, fmt, is_query, codes_u8, scales_u8, (float*)token_scales_f32, true, stream);
 }
 
 int dma_mx_quantize_dual(const void* x_bf16, int64_t rows, int D, int is_query, void* codes_lo_u8,
@@ -50,7 +63,7 @@ int dma_mx_quantize_dual(const void* x_bf16, int64_t rows, int D, int is_query, 
     if ((reinterpret_cast<uintptr_t>(codes_lo_u8) & 3u) != 0 || (reinterpret_cast<uintptr_t>(codes_hi_u8) & 7u) != 0)
         return DMA_ERR_INVALID_ARG;
     return dma::launch_mx_quantize(x_bf16, rows, D, 3, is_query != 0, codes_lo_u8, scales_lo_u8, codes_hi_u8,
-                                   scales_hi_u8, (hipStream_t)stream);
+                                   scales_hi_u8, nullptr, (hipStream_t)stream);
 }
 
 int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int B, int Hq, int Hkv, int S,
@@ -66,6 +79,7 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
     int tile = 128;
     int fp8_mfma = 0;
     int sink = 0;
+    int per_token = 0;
     if (opts) {
         if (opts->fp8_mfma != 0 && opts->fp8_mfma != 1) return DMA_ERR_INVALID_ARG;
         fp8_mfma = opts->fp8_mfma;
@@ -73,7 +87,8 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
         if (opts->tile < 0) return DMA_ERR_INVALID_ARG;
         if (opts->sink_tiles < 0) return DMA_ERR_INVALID_ARG;
         sink = opts->sink_tiles;
-        if (opts->per_token_scale != 0) return DMA_ERR_UNSUPPORTED;
+        if (opts->per_token_scale != 0 && opts->per_token_scale != 1) return DMA_ERR_INVALID_ARG;
+        per_token = opts->per_token_scale;
         if (opts->pv_fmt != DMA_FMT_BF16) return DMA_ERR_UNSUPPORTED;
     }
     if (S % tile != 0) return DMA_ERR_UNSUPPORTED;
@@ -85,9 +100,11 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
     a.band = diag_band_tiles > S / tile ? S / tile : diag_band_tiles;
     a.sink = sink > S / tile ? S / tile : sink;
     a.causal = causal != 0;
+    a.per_token = per_token;
     // public element format -> product path of the kernels: 3 / 4 = MXFP8 (E4M3 / E5M2) decoded exactly to bf16 and
     // multiplied on the bf16 MFMA; E5M2 has no other path
     if (fp8_mfma && (hi_fmt == DMA_FMT_MXFP8_E5M2 || lo_fmt == DMA_FMT_MXFP8_E5M2)) return DMA_ERR_UNSUPPORTED;
+    if (fp8_mfma && per_token) return DMA_ERR_UNSUPPORTED;
     auto path = [&](int f) { return f == DMA_FMT_MXFP8_E5M2 ? 4 : (f == DMA_FMT_MXFP8_E4M3 && !fp8_mfma) ? 3 : f; };
     a.hi_fmt = path(hi_fmt);
     a.lo_fmt = path(lo_fmt);

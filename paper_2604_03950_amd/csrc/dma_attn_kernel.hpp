@@ -87,9 +87,25 @@ DMA_DEV void load_q_raw(v4i (&raw)[C::NKK], const uint16_t* __restrict__ qhead, 
         for (int t = 0; t < 4; ++t) raw[4 * h + t] = *(const v4i*)(rowp + 64 * h + 8 * t);
 }
 
+// Absolute maximum of the lane's query row after the softmax pre-scale (both half-waves hold half of the row).
+template <typename C>
+DMA_DEV float q_row_amax(const v4i (&raw)[C::NKK], float c)
+{
+    float amax = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < C::NKK; ++kk) {
+        float x[8];
+        unpack8<true>(raw[kk], c, x);
+        amax = fmaxf(amax, amax8(x));
+    }
+    return cross_half_max(amax);
+}
+
 // qr / qscale from raw (scaled MFMA formats fill `qscale`: byte h = E8M0 of block 2h + g of the lane's row).
-template <typename C, int FMT, int QR>
-DMA_DEV void make_q(v4i (&qr)[QR], int& qscale, const v4i (&raw)[C::NKK], float c)
+// inv_sq: the factor 1 / S_q of Alg. 2 Step 2 for the lane's row (1 when the per-token scale is off): one more
+// binary32 multiply per element before the shared scales are formed.
+template <typename C, int FMT, bool PT, int QR>
+DMA_DEV void make_q(v4i (&qr)[QR], int& qscale, const v4i (&raw)[C::NKK], float c, float inv_sq)
 {
     qscale = 0;
     if constexpr (FMT == FMT_BF16) {
@@ -103,6 +119,10 @@ DMA_DEV void make_q(v4i (&qr)[QR], int& qscale, const v4i (&raw)[C::NKK], float 
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 unpack8<true>(raw[4 * h + t], c, x[t]);
+                if constexpr (PT) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) x[t][e] = __fmul_rn(x[t][e], inv_sq);
+                }
                 amax = fmaxf(amax, amax8(x[t]));
             }
             const int code = e8m0_code<FMT>(amax);
@@ -166,8 +186,10 @@ DMA_DEV void load_tile(v4i (&reg)[C::CPT], const uint16_t* __restrict__ tile, in
 }
 
 // K tile from registers into LDS in format FMT.  kdst / ksdst: LDS addresses of the codes and of the scale bytes.
-template <typename C, int FMT>
-DMA_DEV void stage_k(const v4i (&reg)[C::CPT], unsigned kdst, unsigned ksdst, int tid)
+// PT: Alg. 2 Step 2: every key row is first multiplied by 2688 / rowmax; inv_sk[r] is that factor for chunk round r
+// (the caller computes it once per tile for both formats, see key_token_scales).
+template <typename C, int FMT, bool PT>
+DMA_DEV void stage_k(const v4i (&reg)[C::CPT], unsigned kdst, unsigned ksdst, int tid, const float (&inv_sk)[C::CPT])
 {
     constexpr int KPR = C::T / C::CPR;                       // keys per chunk round
     constexpr int STRIDE = C::template kstride<FMT>();
@@ -180,14 +202,26 @@ DMA_DEV void stage_k(const v4i (&reg)[C::CPT], unsigned kdst, unsigned ksdst, in
     for (int r = 0; r < C::CPT; ++r) {
         if constexpr (FMT == FMT_BF16) {
             lds_write<v4i>(ka + r * KPR * STRIDE, reg[r]);
-        } else if constexpr (FMT == FMT_E2M1) {
+        } else if constexpr (FMT == FMT_E2M1 && !PT) {
             // keys are not pre-scaled: block maximum and converts work on the packed bf16 directly
             const int code = max((int)(quad_max_u32(amax8_bf16_bits(reg[r])) >> 7) - 2, 0);
             lds_write<int>(ka + r * KPR * STRIDE, encode8_e2m1_bf16(reg[r], code));
             lds_write<uint8_t>(sa + r * KPR * C::CPR, (uint8_t)code);
+        } else if constexpr (FMT == FMT_E2M1) {
+            float x[8];
+            unpack8<false>(reg[r], 1.f, x);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = __fmul_rn(x[e], inv_sk[r]);
+            const int code = e8m0_code<FMT_E2M1>(quad_max(amax8(x)));
+            lds_write<int>(ka + r * KPR * STRIDE, encode8_e2m1(x, code));
+            lds_write<uint8_t>(sa + r * KPR * C::CPR, (uint8_t)code);
         } else {
             float x[8];
             unpack8<false>(reg[r], 1.f, x);
+            if constexpr (PT) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = __fmul_rn(x[e], inv_sk[r]);
+            }
             const float amax = quad_max(amax8(x));
             const int code = e8m0_code<FMT>(amax);
             if constexpr (FMT == FMT_E4M3_X || FMT == FMT_E5M2_X) {
@@ -233,8 +267,10 @@ DMA_DEV v8i widen(const v4i& lo, const v4i& hi) { return v8i{lo[0], lo[1], lo[2]
 // ksrc / kssrc: LDS addresses of the tile's K codes / scale bytes.
 // MAYBE_DIAG = false compiles the mask away (tiles strictly below the diagonal).
 // after_mfma() runs between the matrix part and the softmax part (the caller's global loads go there).
-template <typename C, int FMT, bool MAYBE_DIAG, int QR, typename F>
-DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned kssrc,
+// PT (per-token scale, Alg. 2 Step 2): the product of the codes is multiplied by S_q of the query row (q_sq) and S_q of
+// the key (one float per key at ktssrc) before the maximum is taken.
+template <typename C, int FMT, bool MAYBE_DIAG, bool PT, int QR, typename F>
+DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned kssrc, unsigned ktssrc, float q_sq,
                         bool diagonal, int qrow_in_tile, int lane, float c,
                         float& m, float& mfloor, float& l, v16f (&o)[C::NDB], v8bf (&pb)[2 * C::NKB], F&& after_mfma)
 {
@@ -247,7 +283,8 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
     // The accumulators start at -m (the running maximum so far), so the products arrive as S - m and the
     // subtraction of the maximum costs nothing in the common case of a maximum that does not move.
     // (One register tuple holds the start value; the first MFMA of every 32-key block reads it as its C operand.)
-    const float acc0 = (FMT == FMT_BF16) ? 0.f : -m;
+    constexpr bool SCALE_AFTER = PT && FMT != FMT_BF16;       // the score is rescaled after the product
+    const float acc0 = (FMT == FMT_BF16 || SCALE_AFTER) ? 0.f : -m;
     const v16f sinit = {acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0, acc0};
 
     // ---- S^T = K . Q^T.  Operands are fetched from LDS ahead of the MFMAs that use them.
@@ -327,6 +364,18 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
         }
     }
 
+    if constexpr (SCALE_AFTER) {
+        // register r of 32-key block kb is key 32 kb + 8 (r / 4) + 4 g + r % 4: four consecutive scales per read
+        const unsigned ta = pin(ktssrc + 16 * g);
+#pragma unroll
+        for (int kb = 0; kb < C::NKB; ++kb)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const v4f sk = lds_read<v4f>(ta + 4 * (32 * kb + 8 * r4));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s[kb][4 * r4 + e] = __builtin_fmaf(s[kb][4 * r4 + e], q_sq * sk[e], -m);
+            }
+    }
     after_mfma();
 
     // ---- causal mask on the tile that straddles the diagonal: key > query -> -inf
@@ -422,22 +471,46 @@ DMA_DEV void value_part(unsigned vsrc, int lane, v16f (&o)[C::NDB], const v8bf (
 // ---------------------------------------------------------------------------------------------
 // The kernel
 // ---------------------------------------------------------------------------------------------
+// Alg. 2 Step 2 for the keys of a tile: per chunk round the row maximum over the CPR lanes of the row, S_q into LDS
+// (one float per key at ktsdst), 1 / S_q returned for the quantization.
+template <typename C>
+DMA_DEV void key_token_scales(const v4i (&reg)[C::CPT], float (&inv_sk)[C::CPT], unsigned ktsdst, int tid)
+{
+    constexpr int KPR = C::T / C::CPR;
+    tid = fresh(tid);
+    const int key0 = tid / C::CPR, dc = tid % C::CPR;
+    const unsigned ta = pin(ktsdst + 4 * key0);
+#pragma unroll
+    for (int r = 0; r < C::CPT; ++r) {
+        float x[8];
+        unpack8<false>(reg[r], 1.f, x);
+        float sk;
+        token_scale(group_max<C::CPR>(amax8(x)), sk, inv_sk[r]);
+        if (dc == 0) lds_write<float>(ta + 4 * r * KPR, sk);
+    }
+}
+
 // K and V of one key tile from registers into LDS: K in the low format if some wave computes the tile in Phase 1,
 // in the high format if some wave computes it in Phase 2.
-template <typename C, int LO, int HI>
+template <typename C, int LO, int HI, bool PT>
 DMA_DEV void stage_tile(const v4i (&kreg)[C::CPT], const v4i (&vreg)[C::CPT], bool any_lo, bool any_hi,
-                        unsigned klo, unsigned kslo, unsigned khi, unsigned kshi, unsigned vdst, int tid)
+                        unsigned klo, unsigned kslo, unsigned khi, unsigned kshi, unsigned kts, unsigned vdst, int tid)
 {
-    if (any_lo) stage_k<C, LO>(kreg, klo, kslo, tid);
+    float inv_sk[C::CPT];
+#pragma unroll
+    for (int r = 0; r < C::CPT; ++r) inv_sk[r] = 1.f;
+    if constexpr (PT) key_token_scales<C>(kreg, inv_sk, kts, tid);
+    if (any_lo) stage_k<C, LO, PT>(kreg, klo, kslo, tid, inv_sk);
     if constexpr (LO != HI) {
-        if (any_hi) stage_k<C, HI>(kreg, khi, kshi, tid);
+        if (any_hi) stage_k<C, HI, PT>(kreg, khi, kshi, tid, inv_sk);
     }
     stage_v<C>(vreg, vdst, tid);
 }
 
 // GENERAL = false: Alg. 1 as printed (causal, no sink window; sink_arg / causal_arg are ignored): main tiles then band
 // tiles, two loops in a row.  GENERAL = true: sink window and / or no causal mask: runs of main and band tiles alternate.
-template <int D, int BT, int TPW, int LO, int HI, bool GENERAL>
+// PT: per-token scale of Alg. 2 Step 2 on queries and keys (built with GENERAL only).
+template <int D, int BT, int TPW, int LO, int HI, bool GENERAL, bool PT>
 __global__ void __launch_bounds__((BT / 32) * TPW * 64, 2)
 dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     const uint16_t* __restrict__ v, float* __restrict__ out,
@@ -462,7 +535,8 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     constexpr int EPI_COLS = 64;                         // output columns per epilogue pass
     constexpr int EPI_STRIDE = EPI_COLS * 4 + 16;        // bytes per staged output row (padded against bank conflicts)
     constexpr int EPI_WAVE = 32 * EPI_STRIDE;
-    constexpr int LDS_TOTAL = cmax<OFF_KSHI + (HI_SCALES ? 2 * C::KSC : 0), C::NW * EPI_WAVE>();
+    constexpr int OFF_KTS = OFF_KSHI + (HI_SCALES ? 2 * C::KSC : 0);      // per-token key scales: one float per key
+    constexpr int LDS_TOTAL = cmax<OFF_KTS + (PT ? 2 * BT * 4 : 0), C::NW * EPI_WAVE>();
     static_assert(LDS_TOTAL <= 160 * 1024, "LDS budget of one CU");
     static_assert(D % EPI_COLS == 0, "epilogue works on 64-column slabs");
     __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_TOTAL];
@@ -472,6 +546,7 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     auto kslo_at = [&](int buf) { return lds0 + OFF_KSLO + buf * C::KSC; };
     auto khi_at = [&](int buf) { return lds0 + OFF_KHI + buf * KHI; };
     auto kshi_at = [&](int buf) { return lds0 + OFF_KSHI + (HI_SCALES ? buf * C::KSC : 0); };
+    auto kts_at = [&](int buf) { return lds0 + OFF_KTS + (PT ? buf * BT * 4 : 0); };
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -568,21 +643,25 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         v8bf pb[2 * C::NKB];
         v4i qr_lo[QRLO], qr_hi[QRHI];
         int qs_lo = 0, qs_hi = 0;
+        float q_sq = 1.f;                                // S_q of the lane's query row (per-token scale)
         {
             v4i qraw[C::NKK];
             load_q_raw<C>(qraw, qhead, qrow, fresh(lane) & 31, fresh(lane) >> 5);
             load_tile<C>(kreg, khead, tid);
             load_tile<C>(vreg, vhead, tid);
             __builtin_amdgcn_sched_barrier(0);           // every request is out before the first result is needed
-            make_q<C, LO>(qr_lo, qs_lo, qraw, c);
+            float inv_sq = 1.f;
+            if constexpr (PT) token_scale(q_row_amax<C>(qraw, c), q_sq, inv_sq);
+            make_q<C, LO, PT>(qr_lo, qs_lo, qraw, c, inv_sq);
             if constexpr (TWO) {
-                if (band > 0 || sink > 0) make_q<C, HI>(qr_hi, qs_hi, qraw, c);
+                if (band > 0 || sink > 0) make_q<C, HI, PT>(qr_hi, qs_hi, qraw, c, inv_sq);
             }
         }
         auto stage_next = [&](int jt, int buf) __attribute__((always_inline)) {         // tile jt from the K/V registers into LDS buffer buf
             bool any_lo, any_hi;
             needs(jt, any_lo, any_hi);
-            stage_tile<C, LO, HI>(kreg, vreg, any_lo, any_hi, klo_at(buf), kslo_at(buf), khi_at(buf), kshi_at(buf), v_at(buf), tid);
+            stage_tile<C, LO, HI, PT>(kreg, vreg, any_lo, any_hi, klo_at(buf), kslo_at(buf), khi_at(buf), kshi_at(buf), kts_at(buf),
+                                      v_at(buf), tid);
         };
         stage_next(0, 0);
         if (1 < nt) {
@@ -604,7 +683,7 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         auto main_step = [&](int jt) __attribute__((always_inline)) {
             const int buf = jt & 1;
             if (jt + 1 < nt) stage_next(jt + 1, buf ^ 1);
-            score_part<C, LO, false>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), false, qrow_in_tile, lane, c, m, mfloor, l, o, pb,
+            score_part<C, LO, false, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), kts_at(buf), q_sq, false, qrow_in_tile, lane, c, m, mfloor, l, o, pb,
                                      [&]() __attribute__((always_inline)) { if (jt + 2 < nt) load_tile<C>(kreg, khead + (int64_t)(jt + 2) * BT * D, tid); });
             if (jt + 2 < nt) load_tile<C>(vreg, vhead + (int64_t)(jt + 2) * BT * D, tid);
             value_part<C>(v_at(buf), lane, o, pb);
@@ -617,9 +696,9 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             if (jt + 1 < nt) stage_next(jt + 1, buf ^ 1);
             if (active) {
                 if (!tile_hi(it, jt)) {
-                    score_part<C, LO, true>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
+                    score_part<C, LO, true, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), kts_at(buf), q_sq, diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
                 } else if constexpr (TWO) {
-                    score_part<C, HI, true>(qr_hi, qs_hi, khi_at(buf), kshi_at(buf), diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
+                    score_part<C, HI, true, PT>(qr_hi, qs_hi, khi_at(buf), kshi_at(buf), kts_at(buf), q_sq, diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
                 }
             }
             if (jt + 2 < nt) {
@@ -694,7 +773,7 @@ inline int compute_units()
     return cached[dev];
 }
 
-template <int D, int BT, int TPW, int LO, int HI, bool GENERAL>
+template <int D, int BT, int TPW, int LO, int HI, bool GENERAL, bool PT>
 static int launch_variant(const AttnArgs& a, hipStream_t stream)
 {
     using C = Cfg<D, BT, TPW>;
@@ -708,7 +787,7 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
     static int resident = 0;              // per instance; the same on every device of one kind
     if (resident == 0) {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL>, C::T, 0) != hipSuccess || n <= 0)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT>, C::T, 0) != hipSuccess || n <= 0)
             return DMA_ERR_HIP_;
         resident = n;
     }
@@ -723,19 +802,22 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
     int head_block = heads_x;
     for (int hb = 1; hb < heads_x; ++hb)
         if (heads_x % hb == 0 && ((int64_t)hb * NG) % (2 * workers) == 0) { head_block = hb; break; }
-    hipLaunchKernelGGL((dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL>), dim3((unsigned)blocks), dim3(C::T), 0, stream,
+    hipLaunchKernelGGL((dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT>), dim3((unsigned)blocks), dim3(C::T), 0, stream,
                        (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, a.out, a.B, a.Hq, a.Hkv,
                        a.S, a.band, a.sink, a.causal, c, head_block);
     return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
 }
 
-// Alg. 1 as printed (causal, no sink window) runs the straight-line instance; the sink window and the non-causal
-// variant run the general one.
+// Alg. 1 as printed (causal, no sink window) runs the straight-line instance; the sink window, the non-causal variant
+// and the per-token scale run the general one (unquantized operands have no per-token scale).
 template <int D, int BT, int TPW, int LO, int HI>
 static int launch_instance(const AttnArgs& a, hipStream_t stream)
 {
-    if (a.causal && a.sink == 0) return launch_variant<D, BT, TPW, LO, HI, false>(a, stream);
-    return launch_variant<D, BT, TPW, LO, HI, true>(a, stream);
+    if constexpr (LO != FMT_BF16) {
+        if (a.per_token) return launch_variant<D, BT, TPW, LO, HI, true, true>(a, stream);
+    }
+    if (a.causal && a.sink == 0) return launch_variant<D, BT, TPW, LO, HI, false, false>(a, stream);
+    return launch_variant<D, BT, TPW, LO, HI, true, false>(a, stream);
 }
 
 }  // namespace dma

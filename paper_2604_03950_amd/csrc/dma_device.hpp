@@ -75,6 +75,29 @@ DMA_DEV float quad_max(float a)
     return fmaxf(a, b);
 }
 
+// max over a group of LANES consecutive lanes (LANES = 4, 8 or 16, group aligned to LANES): quad permutes, then the
+// DPP mirrors of half a row (8 lanes) and of a row (16 lanes).
+template <int LANES>
+DMA_DEV float group_max(float a)
+{
+    static_assert(LANES == 4 || LANES == 8 || LANES == 16, "group of 4, 8 or 16 lanes");
+    a = quad_max(a);
+    if constexpr (LANES >= 8)
+        a = fmaxf(a, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(a), 0x141, 0xF, 0xF, true)));   // row_half_mirror
+    if constexpr (LANES >= 16)
+        a = fmaxf(a, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(a), 0x140, 0xF, 0xF, true)));   // row_mirror
+    return a;
+}
+
+// Per-token scale of Alg. 2 Step 2 for a row with absolute maximum amax: s_q = amax / (448 * 6) and its reciprocal
+// 2688 / amax, one correctly rounded division each; rows with amax < 2^-100 (zero rows included) keep s_q = 1.
+DMA_DEV void token_scale(float amax, float& s_q, float& inv_s_q)
+{
+    const bool ok = amax >= 0x1p-100f;
+    s_q = ok ? __fdiv_rn(amax, 2688.0f) : 1.0f;
+    inv_s_q = ok ? __fdiv_rn(2688.0f, amax) : 1.0f;
+}
+
 DMA_DEV unsigned quad_max_u32(unsigned a)
 {
     unsigned b = (unsigned)__builtin_amdgcn_mov_dpp((int)a, 0xB1, 0xF, 0xF, true);

@@ -13,8 +13,9 @@ constexpr int DMA_ERR_UNSUPPORTED_ = -2;
 constexpr int DMA_ERR_HIP_ = -3;
 
 // mode: 1 = E4M3 only (c8/s8), 2 = E2M1 only (c4/s4), 3 = both, 4 = E5M2 only (c8/s8).
+// token_scales: NULL, or [rows] floats receiving the per-token scale of Alg. 2 Step 2 (then applied; modes 1, 2, 4).
 int launch_mx_quantize(const void* x, int64_t rows, int D, int mode, int is_query, void* c4, void* s4,
-                       void* c8, void* s8, hipStream_t stream);
+                       void* c8, void* s8, float* token_scales, hipStream_t stream);
 
 int launch_diag_copy(const void* src, void* dst, int64_t bytes, hipStream_t stream);
 
@@ -28,6 +29,7 @@ struct AttnArgs {
     int band;
     int sink;        // leading key tiles in the high format
     int causal;
+    int per_token;   // Alg. 2 Step 2 on queries and keys
     int hi_fmt, lo_fmt;
 };
 

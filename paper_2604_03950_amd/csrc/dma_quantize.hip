@@ -13,11 +13,14 @@ constexpr int QUANT_THREADS = 256;
 constexpr int QUANT_UNROLL = 4;     // chunks per thread
 
 // MODE: 1 = E4M3 only, 2 = E2M1 only, 3 = both (low copy E2M1 + high copy E4M3), 4 = E5M2 only.
-template <int MODE, bool IS_QUERY>
+// PER_TOKEN: Alg. 2 Step 2: the row (lanes_per_row = D / 8 consecutive lanes, a power of two <= 64) is multiplied by
+// 2688 / rowmax before the shared scales are formed, and rowmax / 2688 goes to token_scales[row].
+template <int MODE, bool IS_QUERY, bool PER_TOKEN>
 __global__ void __launch_bounds__(QUANT_THREADS)
 mx_quantize_kernel(const v4i* __restrict__ x, int64_t n_chunks, float c,
                    int* __restrict__ codes4, uint8_t* __restrict__ scales4,
-                   v2i* __restrict__ codes8, uint8_t* __restrict__ scales8)
+                   v2i* __restrict__ codes8, uint8_t* __restrict__ scales8,
+                   float* __restrict__ token_scales, int lanes_per_row)
 {
     const int64_t base = ((int64_t)blockIdx.x * QUANT_UNROLL) * QUANT_THREADS + threadIdx.x;
     v4i w[QUANT_UNROLL];
@@ -31,6 +34,16 @@ mx_quantize_kernel(const v4i* __restrict__ x, int64_t n_chunks, float c,
         const int64_t ch = base + (int64_t)u * QUANT_THREADS;
         float v[8];
         unpack8<IS_QUERY>(w[u], c, v);
+        if constexpr (PER_TOKEN) {
+            // row maximum: quad, then butterfly over the remaining lanes of the row (rows never straddle a wave)
+            float rmax = quad_max(amax8(v));
+            for (int off = 4; off < lanes_per_row; off <<= 1) rmax = fmaxf(rmax, __shfl_xor(rmax, off, 64));
+            float s_q, inv;
+            token_scale(rmax, s_q, inv);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) v[t] = __fmul_rn(v[t], inv);
+            if (ch < n_chunks && (ch % lanes_per_row) == 0) token_scales[ch / lanes_per_row] = s_q;
+        }
         const float amax = quad_max(amax8(v));      // every lane of the wave executes the DPP
         if (ch >= n_chunks) continue;
         const bool writes_scale = (threadIdx.x & 3) == 0;
@@ -52,9 +65,9 @@ mx_quantize_kernel(const v4i* __restrict__ x, int64_t n_chunks, float c,
     }
 }
 
-template <int MODE>
+template <int MODE, bool PER_TOKEN>
 static int launch_mode(const void* x, int64_t rows, int D, int is_query, void* c4, void* s4, void* c8,
-                       void* s8, hipStream_t stream)
+                       void* s8, float* ts, hipStream_t stream)
 {
     const int64_t n_chunks = rows * (int64_t)(D / 8);
     if (n_chunks == 0) return DMA_OK_;
@@ -62,12 +75,14 @@ static int launch_mode(const void* x, int64_t rows, int D, int is_query, void* c
     const int64_t blocks = (n_chunks + per_block - 1) / per_block;
     if (blocks > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
     const float c = (float)(1.4426950408889634074 / sqrt((double)D));
+    const int lpr = D / 8;
+    if (PER_TOKEN && (lpr > 64 || (lpr & (lpr - 1)) != 0)) return DMA_ERR_UNSUPPORTED_;
     if (is_query)
-        hipLaunchKernelGGL((mx_quantize_kernel<MODE, true>), dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream,
-                           (const v4i*)x, n_chunks, c, (int*)c4, (uint8_t*)s4, (v2i*)c8, (uint8_t*)s8);
+        hipLaunchKernelGGL((mx_quantize_kernel<MODE, true, PER_TOKEN>), dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream,
+                           (const v4i*)x, n_chunks, c, (int*)c4, (uint8_t*)s4, (v2i*)c8, (uint8_t*)s8, ts, lpr);
     else
-        hipLaunchKernelGGL((mx_quantize_kernel<MODE, false>), dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream,
-                           (const v4i*)x, n_chunks, c, (int*)c4, (uint8_t*)s4, (v2i*)c8, (uint8_t*)s8);
+        hipLaunchKernelGGL((mx_quantize_kernel<MODE, false, PER_TOKEN>), dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream,
+                           (const v4i*)x, n_chunks, c, (int*)c4, (uint8_t*)s4, (v2i*)c8, (uint8_t*)s8, ts, lpr);
     return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
 }
 
@@ -91,13 +106,21 @@ int launch_diag_copy(const void* src, void* dst, int64_t bytes, hipStream_t stre
 }
 
 int launch_mx_quantize(const void* x, int64_t rows, int D, int mode, int is_query, void* c4, void* s4,
-                       void* c8, void* s8, hipStream_t stream)
+                       void* c8, void* s8, float* token_scales, hipStream_t stream)
 {
+    if (token_scales) {
+        switch (mode) {
+            case 1: return launch_mode<1, true>(x, rows, D, is_query, c4, s4, c8, s8, token_scales, stream);
+            case 2: return launch_mode<2, true>(x, rows, D, is_query, c4, s4, c8, s8, token_scales, stream);
+            case 4: return launch_mode<4, true>(x, rows, D, is_query, c4, s4, c8, s8, token_scales, stream);
+        }
+        return DMA_ERR_INVALID_ARG_;
+    }
     switch (mode) {
-        case 1: return launch_mode<1>(x, rows, D, is_query, c4, s4, c8, s8, stream);
-        case 2: return launch_mode<2>(x, rows, D, is_query, c4, s4, c8, s8, stream);
-        case 3: return launch_mode<3>(x, rows, D, is_query, c4, s4, c8, s8, stream);
-        case 4: return launch_mode<4>(x, rows, D, is_query, c4, s4, c8, s8, stream);
+        case 1: return launch_mode<1, false>(x, rows, D, is_query, c4, s4, c8, s8, nullptr, stream);
+        case 2: return launch_mode<2, false>(x, rows, D, is_query, c4, s4, c8, s8, nullptr, stream);
+        case 3: return launch_mode<3, false>(x, rows, D, is_query, c4, s4, c8, s8, nullptr, stream);
+        case 4: return launch_mode<4, false>(x, rows, D, is_query, c4, s4, c8, s8, nullptr, stream);
     }
     return DMA_ERR_INVALID_ARG_;
 }

@@ -66,7 +66,8 @@ def test_argument_checks_return_before_any_launch(lib):
         opts = binding.AttnOpts(**{**dict(tile=128, sink_tiles=0, pv_fmt=0, per_token_scale=0, fp8_mfma=0), **kw})
         return lib.dma_attn_fwd_ex(fake, fake, fake, fake, 1, 4, 2, 256, 128, 1, 1, hi, 2, ctypes.byref(opts), None)
     assert attn_ex(sink_tiles=-1) == -1
-    assert attn_ex(per_token_scale=1) == -2   # Alg. 2 Step 2 variant: not built
+    assert attn_ex(per_token_scale=2) == -1
+    assert attn_ex(per_token_scale=1, fp8_mfma=1) == -2   # per-token scale only on the exact product paths
     assert attn_ex(pv_fmt=1) == -2            # MX-format P V: not built
     assert attn_ex(hi=3, fp8_mfma=1) == -2    # E5M2 only has the decoded-to-bf16 path
     assert attn_ex(fp8_mfma=2) == -1

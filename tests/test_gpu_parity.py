@@ -142,18 +142,18 @@ def fmt_ids(dma, oracle, name):
             "e5m2": (dma.FMT_MXFP8_E5M2, oracle.FMT_E5M2), "bf16": (dma.FMT_BF16, oracle.FMT_BF16)}[name]
 
 
-def run_case(dma, oracle, w, q, k, v, band, lo, hi, rows=None, explicit_tile=True, sink=0, causal=True):
+def run_case(dma, oracle, w, q, k, v, band, lo, hi, rows=None, explicit_tile=True, sink=0, causal=True, per_token=False):
     qd, kd, vd = to_gpu(dma, q, k, v)
     (lo_g, lo_o), (hi_g, hi_o) = fmt_ids(dma, oracle, lo), fmt_ids(dma, oracle, hi)
     out = dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, hi_fmt=hi_g, lo_fmt=lo_g, causal=causal, sink_tiles=sink,
-                           tile=w.tile if explicit_tile else None)
+                           per_token_scale=per_token, tile=w.tile if explicit_tile else None)
     torch.cuda.synchronize()
     out = out.cpu().numpy()
-    kw = dict(tile=w.tile, band=band, hi_fmt=hi_o, lo_fmt=lo_o, p_round=True, sink=sink, causal=causal)
+    kw = dict(tile=w.tile, band=band, hi_fmt=hi_o, lo_fmt=lo_o, p_round=True, sink=sink, causal=causal, per_token=per_token)
     rows = oracle.all_rows(w.B, w.Hq, w.S) if rows is None else oracle.sort_rows(rows)
     want, slack = oracle.dma_attn_rows(q, k, v, rows, with_slack=True, **kw)
     got = out[rows[:, 0], rows[:, 1], rows[:, 2]]
-    check_out(got, want, f"{w.name} band={band} sink={sink} causal={causal} lo={lo} hi={hi}", slack)
+    check_out(got, want, f"{w.name} band={band} sink={sink} causal={causal} per_token={per_token} lo={lo} hi={hi}", slack)
     return out
 
 
@@ -362,3 +362,40 @@ def test_attn_noncausal_odd_tiles_and_batch(dma, oracle):
     rows = wl.sample_rows(w, [0, 2, 4], [(0, 0), (1, 5), (1, 7)], 64, 18)
     run_case(dma, oracle, w, q, k, v, 2, "e2m1", "e4m3", rows=rows, causal=False)
     run_case(dma, oracle, w, q, k, v, 1, "e2m1", "e4m3", rows=rows, sink=2, causal=False)
+
+
+# ------------------------------------------------------------------ per-token scale (Alg. 2 Step 2)
+
+@pytest.mark.parametrize("D", [32, 64, 128, 256, 512])
+@pytest.mark.parametrize("is_query", [False, True])
+def test_quantize_token_scale_bit_exact(dma, oracle, D, is_query):
+    rng = np.random.Generator(np.random.Philox(555 + D))
+    x = rng.standard_normal((1001, D)).astype(np.float32) * np.exp2(rng.integers(-30, 30, size=(1001, 1))).astype(np.float32)
+    x[7] = 0.0
+    x[8, 3] = 2.0 ** -110
+    x[9, D - 1] = 2688.0
+    bits = np.concatenate([edge_rows(D), wl.f32_to_bf16_bits(x)], axis=0)
+    (xd,) = to_gpu(dma, bits)
+    for fmt, ofmt in ((dma.FMT_MXFP4_E2M1, oracle.FMT_E2M1), (dma.FMT_MXFP8_E4M3, oracle.FMT_E4M3),
+                      (dma.FMT_MXFP8_E5M2, oracle.FMT_E5M2)):
+        codes, scales, ts = dma.dma_mx_quantize_token(xd, fmt, is_query)
+        torch.cuda.synchronize()
+        wc, ws, wt = oracle.mx_quantize(bits, ofmt, is_query, per_token=True)
+        assert np.array_equal(ts.cpu().numpy().view(np.uint32), wt.view(np.uint32)), (D, fmt, "token scales")
+        assert np.array_equal(scales.cpu().numpy(), ws), (D, fmt, "scales")
+        assert np.array_equal(codes.cpu().numpy(), wc), (D, fmt, "codes")
+
+
+@pytest.mark.parametrize("lo,hi", [("e2m1", "e4m3"), ("e2m1", "e2m1"), ("e4m3", "e4m3"), ("e2m1", "e5m2"), ("bf16", "bf16")])
+def test_attn_token_scale(dma, oracle, lo, hi):
+    w = wl.CONFIGS["tiny"]
+    q, k, v = wl.generate(w)
+    for band in (0, 1, 2):
+        run_case(dma, oracle, w, q, k, v, band, lo, hi, per_token=True)
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=640, Hq=2, Hkv=2)
+    q, k, v = wl.generate(w)
+    run_case(dma, oracle, w, q, k, v, 2, lo, hi, per_token=True)
+    w = wl.small_variant(wl.CONFIGS["gqa_32k"], S=768, Hq=4, Hkv=1)
+    q, k, v = wl.generate(w)
+    run_case(dma, oracle, w, q, k, v, 1, lo, hi, per_token=True, sink=1)
+    run_case(dma, oracle, w, q, k, v, 2, lo, hi, per_token=True, causal=False)
