@@ -32,19 +32,24 @@ MEASURED_TRAFFIC_BYTES = {"prefill_8k": 436.8e6}       # profiles/dma_attn_fwd_p
 COPY_CALIBRATION_BYTES = 1 << 29      # dma_diag_copy reads and writes this many bytes once per run
 
 
-def tile_counts(w, band):
-    """(low tiles, high tiles) per (batch, head) for a causal run with logical tile w.tile."""
+def tile_counts(w, band, sink=0, causal=True):
+    """(low tiles, high tiles) per (batch, head) with logical tile w.tile: key tile jt of query tile it is high
+    iff it lies in the window (it - jt < band, or |it - jt| < band without the causal mask) or jt < sink."""
     n = w.S // w.tile
-    total = n * (n + 1) // 2
-    b = min(band, n)
-    hi = b * n - b * (b - 1) // 2
-    return total - hi, hi
+    lo = hi = 0
+    for it in range(n):
+        for jt in range(it + 1 if causal else n):
+            if abs(it - jt) < band or jt < sink:
+                hi += 1
+            else:
+                lo += 1
+    return lo, hi
 
 
-def roofline(w, band, seconds):
+def roofline(w, band, seconds, sink=0, causal=True):
     """Format-weighted MFMA roofline of one launch: every executed tile costs 2*Bt^2*D flop for QK^T
     in its own format plus 2*Bt^2*D flop for PV in bf16."""
-    lo, hi = tile_counts(w, band)
+    lo, hi = tile_counts(w, band, sink, causal)
     heads = w.B * w.Hq
     f_tile = 2.0 * w.tile * w.tile * w.D
     flops = heads * (lo + hi) * 2.0 * f_tile
@@ -92,6 +97,9 @@ def main():
     ap.add_argument("--workload", default="prefill_8k")
     ap.add_argument("--band", type=int, default=None)
     ap.add_argument("--fp8-mfma", action="store_true", help="MXFP8 tiles on the block-scaled FP8 MFMA")
+    ap.add_argument("--sink", type=int, default=0, help="leading key tiles in the high format (variant; default 0 = Alg. 1)")
+    ap.add_argument("--non-causal", action="store_true", help="no causal mask (variant)")
+    ap.add_argument("--per-token", action="store_true", help="per-token scale of Alg. 2 Step 2 (variant)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=200000)
     args = ap.parse_args()
@@ -114,7 +122,8 @@ def main():
     tile = None if w.tile == 128 else w.tile
 
     def step():
-        binding.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, tile=tile, fp8_mfma=args.fp8_mfma, out=out)
+        binding.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, tile=tile, fp8_mfma=args.fp8_mfma, sink_tiles=args.sink,
+                             causal=not args.non_causal, per_token_scale=args.per_token, out=out)
 
     for _ in range(args.warmup):
         step()
@@ -167,7 +176,7 @@ def main():
 
     rec = {
         "metric": METRIC,
-        "value": round(w.causal_flops / (wall / args.steps) / 1e12, 2),
+        "value": round(w.causal_flops * (2 if args.non_causal else 1) / (wall / args.steps) / 1e12, 2),
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
@@ -176,8 +185,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: causal B={w.B} Hq={w.Hq} Hkv={w.Hkv} S={w.S} D={w.D} tile={w.tile} "
                                f"band={band} (hi MXFP8-E4M3, lo MXFP4-E2M1), bf16 in, f32 out, seed {w.seed}",
-                   "flops_convention": "2*B*Hq*S^2*D", "fp8_mfma": bool(args.fp8_mfma)},
-        "roofline": roofline(w, band, kernel_s),
+                   "flops_convention": "4*B*Hq*S^2*D" if args.non_causal else "2*B*Hq*S^2*D", "fp8_mfma": bool(args.fp8_mfma),
+                   "variant": {"sink_tiles": args.sink, "causal": not args.non_causal, "per_token_scale": bool(args.per_token)}},
+        "roofline": roofline(w, band, kernel_s, args.sink, not args.non_causal),
         "quantizer": {"kernel": "mx_quantize_kernel (dual)", "elements": qd.numel(), "us": round(quant_s * 1e6, 2),
                       "achieved_GBps": round(quant_bytes / quant_s / 1e9, 1), "peak_GBps": HBM_PEAK_GBS,
                       "frac": round(quant_bytes / quant_s / 1e9 / HBM_PEAK_GBS, 4),

@@ -712,15 +712,12 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             for (int jt = 0; jt < w0; ++jt) main_step(jt);
             for (int jt = w0; jt < nt; ++jt) band_step(jt);
         } else {
-            for (int jt = 0; jt < nt;) {
-                if ((jt >= s1 && jt < w0) || jt >= w1) {
-                    const int end = jt < w0 ? w0 : nt;           // a run of main tiles
-                    for (; jt < end; ++jt) main_step(jt);
-                } else {
-                    band_step(jt);
-                    ++jt;
-                }
-            }
+            // four runs in a row (each may be empty): sink band tiles, main tiles, band tiles around the diagonal, and
+            // (without the causal mask) the main tiles above the window
+            for (int jt = 0; jt < s1; ++jt) band_step(jt);
+            for (int jt = s1; jt < w0; ++jt) main_step(jt);
+            for (int jt = w0; jt < w1; ++jt) band_step(jt);
+            for (int jt = w1; jt < nt; ++jt) main_step(jt);
         }
 
         // ---- O / l, transposed through LDS (free after the barrier above) so that every output row leaves as whole
@@ -816,7 +813,9 @@ static int launch_instance(const AttnArgs& a, hipStream_t stream)
     if constexpr (LO != FMT_BF16) {
         if (a.per_token) return launch_variant<D, BT, TPW, LO, HI, true, true>(a, stream);
     }
+#ifndef DMA_FORCE_GENERAL
     if (a.causal && a.sink == 0) return launch_variant<D, BT, TPW, LO, HI, false, false>(a, stream);
+#endif
     return launch_variant<D, BT, TPW, LO, HI, true, false>(a, stream);
 }
 
