@@ -1,12 +1,14 @@
 // Fused forward of Diagonal-Tiled Mixed-Precision Attention for gfx950 (paper, Alg. 1 with the
-// online softmax of Sec. 3.2; Q/K quantization of Alg. 2 done in-kernel).
+// online softmax of Sec. 3.2; Q/K quantization of Alg. 2 done in-kernel; options: sink window and
+// per-token scale of Sec. 5.3, non-causal variant of Sec. 4.1).
 //
-// Work split.  One workgroup owns TPW consecutive logical query tiles (B_M = BT rows each) of one
-// (batch, query head) and walks the key tiles jt = 0, 1, ... in ascending order, so one K/V tile
-// fetched and quantized once serves TPW * BT query rows.  Each wave owns 32 query rows of one
-// logical tile `it` and follows Alg. 1 for that tile: key tiles before the diagonal band in the low
-// format (Phase 1), the last `band` tiles up to the diagonal one in the high format (Phase 2),
-// tiles after its diagonal are skipped.
+// Work split.  A work item is TPW consecutive logical query tiles (B_M = BT rows each) of one
+// (batch, query head); the workgroup that owns it walks the key tiles jt = 0, 1, ... in ascending
+// order, so one K/V tile fetched and quantized once serves TPW * BT query rows.  Each wave owns 32
+// query rows of one logical tile `it` and follows Alg. 1 for that tile: key tiles before the
+// diagonal band in the low format (Phase 1), the last `band` tiles up to the diagonal one in the
+// high format (Phase 2), tiles after its diagonal are skipped.  The grid is one resident workgroup
+// per CU; each walks a static, balanced list of items (see the kernel).
 //
 // Everything is computed transposed so that a query row lives in one lane column:
 //     S^T[key, query] = K . Q^T      block-scaled MFMA 32x32x64 (A = K codes from LDS, B = Q codes in VGPRs)
@@ -18,8 +20,8 @@
 // Pipeline.  K and V of tile jt+2 are in flight from global memory (16 B per lane, coalesced) while
 // tile jt is computed out of LDS buffer jt & 1 and tile jt+1 is quantized (block maximum over a lane
 // quad by DPP, E8M0 scale, hardware scaled converts) into buffer (jt+1) & 1: one barrier per tile.
-// Two waves per SIMD let the matrix pipe of one wave overlap the softmax / quantization VALU work of
-// the other.
+// The matrix pipe and the floating-point VALU of a SIMD take turns on this chip, so the two waves of
+// a SIMD hide LDS and memory latency for each other rather than overlap matrix and softmax work.
 #pragma once
 
 #include "dma_device.hpp"
@@ -29,7 +31,6 @@ namespace dma {
 
 template <int A, int B>
 constexpr int cmax() { return A > B ? A : B; }
-
 
 template <int D_, int BT_, int TPW_>
 struct Cfg {
@@ -53,11 +54,8 @@ struct Cfg {
     static constexpr int VS = 2 * D;             // bf16 values: dense rows, 16-byte chunks XOR-swizzled (see v_swizzle)
     static constexpr int KSC = BT * CPR;         // scale bytes of one tile: one per 16-byte chunk (each block's 4 chunks repeat its code)
     static constexpr int VBYTES = BT * VS;
-    static constexpr int VLOADS = VBYTES / 1024; // 1 KiB wave-wide direct-to-LDS loads per tile
-    static constexpr int VLPW = VLOADS / NW;     // ... per wave
-    static_assert(VLOADS % NW == 0, "V tile must split evenly over the waves");
-    // V rows sit densely in LDS (the direct loads write 1 KiB contiguously); so that the transpose reads of four
-    // consecutive keys do not hit the same banks, chunk c of key k is stored at chunk c ^ (4 * v_swizzle(k)).
+    // V rows sit densely in LDS; so that the transpose reads of four consecutive keys do not hit the same banks,
+    // chunk c of key k is stored at chunk c ^ (4 * v_swizzle(k)).
     static constexpr int v_swizzle(int key) { return D == 128 ? (key & 3) : ((key >> 1) & 1); }
     template <int FMT>
     static constexpr int kstride() { return FMT == FMT_E2M1 ? KS4 : FMT == FMT_E4M3 ? KS8 : KSB; }
@@ -557,8 +555,9 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     // `head_block` query heads and dealt to the workgroups in boustrophedon order (round 0: worker 0, 1, ..., W-1;
     // round 1: W-1, ..., 0; ...), which gives every worker the same load to within the lightest items, without
     // atomics and whatever order the hardware starts workgroups in; a block is an even number of rounds (or
-    // everything), so the workers move from block to block together and share few K/V streams at a time.  When the (batch, kv head) units divide over the 8 XCDs (workgroup i runs on XCD i % 8), each XCD keeps its
-    // own units, so the K/V stream of a unit stays in one L2.
+    // everything), so the workers move from block to block together and share few K/V streams at a time.  When the
+    // (batch, kv head) units divide over the 8 XCDs (workgroup i runs on XCD i % 8), each XCD keeps its own units, so
+    // the K/V stream of a unit stays in one L2.
     const int N = S / BT;                // logical tiles per sequence (host guarantees N % TPW == 0)
     const int NG = N / TPW;              // tile groups
     const int group = Hq / Hkv;
