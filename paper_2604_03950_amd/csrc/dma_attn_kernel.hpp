@@ -20,8 +20,8 @@
 // Pipeline.  K and V of tile jt+2 are in flight from global memory (16 B per lane, coalesced) while
 // tile jt is computed out of LDS buffer jt & 1 and tile jt+1 is quantized (block maximum over a lane
 // quad by DPP, E8M0 scale, hardware scaled converts) into buffer (jt+1) & 1: one barrier per tile.
-// The matrix pipe and the floating-point VALU of a SIMD take turns on this chip, so the two waves of
-// a SIMD hide LDS and memory latency for each other rather than overlap matrix and softmax work.
+// Two waves per SIMD (the register budget allows no more): the matrix work of one overlaps the vector
+// work of the other, and together they reach the full vector issue rate, which one wave alone does not.
 #pragma once
 
 #include "dma_device.hpp"
@@ -673,9 +673,7 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         // V tiles jt+1 (loaded into registers during step jt-1) go into the other buffer (K quantized on the way) and
         // the loads of tile jt+2 start; then the wave computes tile jt.
         // (Direct global-to-LDS loads are not used for V: the compiler orders every later LDS access behind them with
-        // a full vmcnt(0) wait, which exposes the memory latency.  On this GPU the MFMA pipe and the floating-point
-        // VALU of a SIMD do not run concurrently, so the two waves of a SIMD are only there to hide LDS and memory
-        // latency, not to overlap matrix and softmax work.)
+        // a full vmcnt(0) wait, which exposes the memory latency.)
         // On main tiles K of tile jt+2 is requested in the middle of the score part (after its MFMAs), V after it:
         // the two bursts of requests (every wave of the workgroup issues them at about the same point) are half as
         // long, and the matrix part of the score has 32 registers more.
