@@ -47,7 +47,7 @@ def tile_counts(w, band, sink=0, causal=True):
     return lo, hi
 
 
-def roofline(w, band, seconds, sink=0, causal=True):
+def roofline(w, band, seconds, sink=0, causal=True, measured_config=True):
     """Format-weighted MFMA roofline of one launch: every executed tile costs 2*Bt^2*D flop for QK^T
     in its own format plus 2*Bt^2*D flop for PV in bf16."""
     lo, hi = tile_counts(w, band, sink, causal)
@@ -61,7 +61,7 @@ def roofline(w, band, seconds, sink=0, causal=True):
     return {
         "bound": "mfma", "achieved": round(achieved, 2), "peak": round(peak, 2), "unit": "TFLOP/s",
         "frac": round(achieved / peak, 4),
-        "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+        "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if measured_config else None,
         "kernel": "dma_attn_fwd_kernel",
         "executed_tile_flops": flops,
         "tile_mix": {"lo_mxfp4": lo * heads, "hi_mxfp8": hi * heads},
@@ -188,7 +188,8 @@ def main():
                                f"band={band} (hi MXFP8-E4M3, lo MXFP4-E2M1), bf16 in, f32 out, seed {w.seed}",
                    "flops_convention": "4*B*Hq*S^2*D" if args.non_causal else "2*B*Hq*S^2*D", "fp8_mfma": bool(args.fp8_mfma),
                    "variant": {"sink_tiles": args.sink, "causal": not args.non_causal, "per_token_scale": bool(args.per_token)}},
-        "roofline": roofline(w, band, kernel_s, args.sink, not args.non_causal),
+        "roofline": roofline(w, band, kernel_s, args.sink, not args.non_causal,
+                             measured_config=(band == w.band and not (args.sink or args.non_causal or args.per_token or args.fp8_mfma))),
         "quantizer": {"kernel": "mx_quantize_kernel (dual)", "elements": qd.numel(), "us": round(quant_s * 1e6, 2),
                       "achieved_GBps": round(quant_bytes / quant_s / 1e9, 1), "peak_GBps": HBM_PEAK_GBS,
                       "frac": round(quant_bytes / quant_s / 1e9 / HBM_PEAK_GBS, 4),
