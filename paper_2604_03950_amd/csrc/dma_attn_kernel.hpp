@@ -177,10 +177,18 @@ DMA_DEV v4s lds_read_tr16(unsigned addr) { return __builtin_amdgcn_ds_read_tr16_
 template <typename C>
 DMA_DEV void load_tile(v4i (&reg)[C::CPT], const uint16_t* __restrict__ tile, int tid)
 {
-    const uint8_t* base = (const uint8_t*)tile;              // uniform
+    // the tile address is uniform: kept in scalar registers so that the loads take the (scalar base + 32-bit lane
+    // offset) form and need no vector address arithmetic
+    typedef const __attribute__((address_space(1))) v4i* global_v4i;
     const unsigned lane_off = (unsigned)fresh(tid) * 16u;
 #pragma unroll
-    for (int r = 0; r < C::CPT; ++r) reg[r] = *(const v4i*)(base + (size_t)r * C::T * 16 + lane_off);
+    for (int r = 0; r < C::CPT; ++r) {
+        const uint64_t t64 = (uint64_t)tile + (uint64_t)r * C::T * 16;
+        uint32_t lo = (uint32_t)t64, hi = (uint32_t)(t64 >> 32);
+        asm volatile("" : "+s"(lo), "+s"(hi));           // pinned in scalar registers, opaque to re-association
+        const uint64_t sbase = ((uint64_t)hi << 32) | (uint64_t)lo;
+        reg[r] = *(global_v4i)(sbase + (uint64_t)lane_off);
+    }
 }
 
 // K tile from registers into LDS in format FMT.  kdst / ksdst: LDS addresses of the codes and of the scale bytes.
