@@ -173,6 +173,55 @@ DMA_DEV v4s lds_read_tr16(unsigned addr) { return __builtin_amdgcn_ds_read_tr16_
 // ---------------------------------------------------------------------------------------------
 // Staging of one key/value tile
 // ---------------------------------------------------------------------------------------------
+// The lane-dependent parts of the LDS addresses of a step never change during the kernel: the low-format ones are
+// computed once (LaneOffsets) and every step only adds the uniform buffer base; the high-format ones, used on a few
+// tiles per item, are recomputed where they are needed.
+template <typename C, int FMT>
+DMA_DEV unsigned stage_k_lane(int tid)           // where the thread's first chunk of a K tile goes (codes)
+{
+    constexpr int CB = (FMT == FMT_E2M1) ? 4 : (FMT == FMT_E4M3) ? 8 : 16;     // bytes per chunk in LDS
+    return (tid / C::CPR) * C::template kstride<FMT>() + (tid % C::CPR) * CB;
+}
+template <typename C>
+DMA_DEV unsigned stage_s_lane(int tid) { return (tid / C::CPR) * C::CPR + tid % C::CPR; }   // ... its scale byte
+template <typename C>
+DMA_DEV unsigned stage_v_lane(int tid)           // ... its first chunk of a V tile (swizzled, see Cfg::v_swizzle)
+{
+    const int key0 = tid / C::CPR, dc = tid % C::CPR;
+    return key0 * C::VS + ((dc ^ (4 * C::v_swizzle(key0))) * 16);
+}
+template <typename C, int FMT>
+DMA_DEV unsigned score_k_lane(int lane)          // the lane's key row of 32-key block 0 (K operand reads)
+{
+    // the bf16 MFMA paths read the head dimension in the query operand's order
+    return (lane & 31) * C::template kstride<FMT>() + (uses_bf16_mfma(FMT) ? 64 : 16) * (lane >> 5);
+}
+template <typename C>
+DMA_DEV unsigned score_s_lane(int lane) { return (lane & 31) * C::CPR + 4 * (lane >> 5); }  // ... its scale dword
+// Transpose read of V: lane l16 of a 16-lane group points at row (l16 / 4) of a 4-key x 16-column patch; the row's
+// 16-byte chunks are swizzled by the row index (the same for every patch: patches start at multiples of 4).
+template <typename C>
+DMA_DEV unsigned value_v_lane(int lane, int db)  // the lane's address for d-block db in the tile's first patch
+{
+    const int g = lane >> 5, l16 = lane & 15, q16 = lane >> 4;
+    const unsigned row_off = (4 * g + (l16 >> 2)) * C::VS + 8 * (l16 & 1);
+    return row_off + 16 * ((4 * db + 2 * (q16 & 1) + ((l16 & 3) >> 1)) ^ (4 * C::v_swizzle(l16 >> 2)));
+}
+template <typename C, int LO>
+struct LaneOffsets {
+    unsigned stage_k, stage_s, stage_v, score_k, score_s, value_v[C::NDB];
+    DMA_DEV void init(int tid, int lane)
+    {
+        stage_k = pin(stage_k_lane<C, LO>(tid));
+        stage_s = pin(stage_s_lane<C>(tid));
+        stage_v = pin(stage_v_lane<C>(tid));
+        score_k = pin(score_k_lane<C, LO>(lane));
+        score_s = pin(score_s_lane<C>(lane));
+#pragma unroll
+        for (int db = 0; db < C::NDB; ++db) value_v[db] = pin(value_v_lane<C>(lane, db));
+    }
+};
+
 // Chunk r of thread tid is 16-byte chunk r * T + tid of the dense tile: key r * (T / CPR) + tid / CPR.
 template <typename C>
 DMA_DEV void load_tile(v4i (&reg)[C::CPT], const uint16_t* __restrict__ tile, int tid)
@@ -194,16 +243,15 @@ DMA_DEV void load_tile(v4i (&reg)[C::CPT], const uint16_t* __restrict__ tile, in
 // K tile from registers into LDS in format FMT.  kdst / ksdst: LDS addresses of the codes and of the scale bytes.
 // PT: Alg. 2 Step 2: every key row is first multiplied by 2688 / rowmax; inv_sk[r] is that factor for chunk round r
 // (the caller computes it once per tile for both formats, see key_token_scales).
+// k_lane / s_lane: stage_k_lane / stage_s_lane of the thread.
 template <typename C, int FMT, bool PT>
-DMA_DEV void stage_k(const v4i (&reg)[C::CPT], unsigned kdst, unsigned ksdst, int tid, const float (&inv_sk)[C::CPT])
+DMA_DEV void stage_k(const v4i (&reg)[C::CPT], unsigned kdst, unsigned ksdst, unsigned k_lane, unsigned s_lane,
+                     const float (&inv_sk)[C::CPT])
 {
     constexpr int KPR = C::T / C::CPR;                       // keys per chunk round
     constexpr int STRIDE = C::template kstride<FMT>();
-    constexpr int CB = (FMT == FMT_E2M1) ? 4 : (FMT == FMT_E4M3) ? 8 : 16;     // bytes per chunk in LDS
-    tid = fresh(tid);
-    const int key0 = tid / C::CPR, dc = tid % C::CPR;
-    const unsigned ka = pin(kdst + key0 * STRIDE + dc * CB);
-    const unsigned sa = pin(ksdst + key0 * C::CPR + dc);      // every lane stores its block's scale: no divergence
+    const unsigned ka = pin(kdst + k_lane);
+    const unsigned sa = pin(ksdst + s_lane);                  // every lane stores its block's scale: no divergence
 #pragma unroll
     for (int r = 0; r < C::CPT; ++r) {
         if constexpr (FMT == FMT_BF16) {
@@ -242,13 +290,11 @@ DMA_DEV void stage_k(const v4i (&reg)[C::CPT], unsigned kdst, unsigned ksdst, in
 
 // V tile from registers into LDS, 16-byte chunks swizzled (see Cfg::v_swizzle).
 template <typename C>
-DMA_DEV void stage_v(const v4i (&reg)[C::CPT], unsigned vdst, int tid)
+DMA_DEV void stage_v(const v4i (&reg)[C::CPT], unsigned vdst, unsigned v_lane)
 {
     constexpr int KPR = C::T / C::CPR;
     static_assert(KPR % 4 == 0, "swizzle of a row must not depend on the chunk round");
-    tid = fresh(tid);
-    const int key0 = tid / C::CPR, dc = tid % C::CPR;
-    const unsigned va = pin(vdst + key0 * C::VS + ((dc ^ (4 * C::v_swizzle(key0))) * 16));
+    const unsigned va = pin(vdst + v_lane);
 #pragma unroll
     for (int r = 0; r < C::CPT; ++r) lds_write<v4i>(va + r * KPR * C::VS, reg[r]);
 }
@@ -276,16 +322,15 @@ DMA_DEV v8i widen(const v4i& lo, const v4i& hi) { return v8i{lo[0], lo[1], lo[2]
 // PT (per-token scale, Alg. 2 Step 2): the product of the codes is multiplied by S_q of the query row (q_sq) and S_q of
 // the key (one float per key at ktssrc) before the maximum is taken.
 template <typename C, int FMT, bool MAYBE_DIAG, bool PT, int QR, typename F>
-DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned kssrc, unsigned ktssrc, float q_sq,
-                        bool diagonal, int qrow_in_tile, int lane, float c,
+DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned kssrc, unsigned k_lane, unsigned s_lane,
+                        unsigned ktssrc, float q_sq, bool diagonal, int qrow_in_tile, int lane, float c,
                         float& m, float& mfloor, float& l, v16f (&o)[C::NDB], v8bf (&pb)[2 * C::NKB], F&& after_mfma)
 {
     lane = fresh(lane);
     const int j = lane & 31, g = lane >> 5;
     v16f s[C::NKB];
     constexpr int STRIDE = C::template kstride<FMT>();
-    // the lane's key row of 32-key block 0; the bf16 MFMA paths read the head dimension in the query operand's order
-    const unsigned ka = pin(ksrc + j * STRIDE + (uses_bf16_mfma(FMT) ? 64 : 16) * g);
+    const unsigned ka = pin(ksrc + k_lane);                       // the lane's key row of 32-key block 0 (score_k_lane)
     // The accumulators start at -m (the running maximum so far), so the products arrive as S - m and the
     // subtraction of the maximum costs nothing in the common case of a maximum that does not move.
     // (One register tuple holds the start value; the first MFMA of every 32-key block reads it as its C operand.)
@@ -298,7 +343,7 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
         // operands of two 32-key blocks at a time (2 * NH 16-byte reads + 2 scale dwords) ahead of their MFMAs,
         // which go h-major so that the two MFMAs into one accumulator are not adjacent
         // scale of MX block 2h + g of the lane's key: byte 0 of the dword at chunk 4 (2h + g) of the key's scale row
-        const unsigned sa = pin(kssrc + j * C::CPR + 4 * g);
+        const unsigned sa = pin(kssrc + s_lane);
         static_assert(C::NKB % 2 == 0, "key tile must hold an even number of 32-key blocks");
         v4i a[2][2][C::NH];
         int ksc[2][2][C::NH];
@@ -327,7 +372,7 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
             __builtin_amdgcn_sched_barrier(0);
         }
     } else if constexpr (FMT == FMT_E4M3) {
-        const unsigned sa = pin(kssrc + j * C::CPR + 4 * g);
+        const unsigned sa = pin(kssrc + s_lane);
 #pragma unroll
         for (int kb = 0; kb < C::NKB; ++kb) {
             static_for<C::NH>([&](auto H) {
@@ -438,18 +483,12 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
 // Second half (all matrix work): O^T += V^T . P^T in groups of 16 keys; the V^T operands of the next group are in
 // flight from LDS while the MFMAs of the current group run.  vsrc: LDS address of the V tile.
 template <typename C>
-DMA_DEV void value_part(unsigned vsrc, int lane, v16f (&o)[C::NDB], const v8bf (&pb)[2 * C::NKB])
+DMA_DEV void value_part(unsigned vsrc, const unsigned (&v_lane)[C::NDB], v16f (&o)[C::NDB], const v8bf (&pb)[2 * C::NKB])
 {
-    lane = fresh(lane);
-    const int g = lane >> 5, l16 = lane & 15, q16 = lane >> 4;
-    // Transpose read: lane l16 of a 16-lane group points at row (l16 / 4) of a 4-key x 16-column patch; the row's
-    // 16-byte chunks are swizzled by the row index (the same for every patch: patches start at multiples of 4).
-    // va[db]: the lane's address for d-block db in the tile's first patch; other patches are constant offsets.
-    const unsigned row_off = (4 * g + (l16 >> 2)) * C::VS + 8 * (l16 & 1);
+    // va[db]: the lane's address for d-block db in the tile's first patch (value_v_lane); other patches are constant offsets
     unsigned va[C::NDB];
 #pragma unroll
-    for (int db = 0; db < C::NDB; ++db)
-        va[db] = pin(vsrc + row_off + 16 * ((4 * db + 2 * (q16 & 1) + ((l16 & 3) >> 1)) ^ (4 * C::v_swizzle(l16 >> 2))));
+    for (int db = 0; db < C::NDB; ++db) va[db] = pin(vsrc + v_lane[db]);
 
     auto read_vt = [&](v8s (&a)[C::NDB], int grp) {             // V^T operands of key group grp (16 keys)
 #pragma unroll
@@ -500,17 +539,18 @@ DMA_DEV void key_token_scales(const v4i (&reg)[C::CPT], float (&inv_sk)[C::CPT],
 // in the high format if some wave computes it in Phase 2.
 template <typename C, int LO, int HI, bool PT>
 DMA_DEV void stage_tile(const v4i (&kreg)[C::CPT], const v4i (&vreg)[C::CPT], bool any_lo, bool any_hi,
-                        unsigned klo, unsigned kslo, unsigned khi, unsigned kshi, unsigned kts, unsigned vdst, int tid)
+                        unsigned klo, unsigned kslo, unsigned khi, unsigned kshi, unsigned kts, unsigned vdst,
+                        const LaneOffsets<C, LO>& lo, int tid)
 {
     float inv_sk[C::CPT];
 #pragma unroll
     for (int r = 0; r < C::CPT; ++r) inv_sk[r] = 1.f;
     if constexpr (PT) key_token_scales<C>(kreg, inv_sk, kts, tid);
-    if (any_lo) stage_k<C, LO, PT>(kreg, klo, kslo, tid, inv_sk);
+    if (any_lo) stage_k<C, LO, PT>(kreg, klo, kslo, lo.stage_k, lo.stage_s, inv_sk);
     if constexpr (LO != HI) {
-        if (any_hi) stage_k<C, HI, PT>(kreg, khi, kshi, tid, inv_sk);
+        if (any_hi) stage_k<C, HI, PT>(kreg, khi, kshi, stage_k_lane<C, HI>(fresh(tid)), lo.stage_s, inv_sk);
     }
-    stage_v<C>(vreg, vdst, tid);
+    stage_v<C>(vreg, vdst, lo.stage_v);
 }
 
 // GENERAL = false: Alg. 1 as printed (causal, no sink window; sink_arg / causal_arg are ignored): main tiles then band
@@ -557,6 +597,8 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
+    LaneOffsets<C, LO> lofs;
+    lofs.init(tid, lane);
 
     // ---- static schedule.  The grid is one workgroup per CU; a work item is (batch, query head, group of TPW query
     // tiles) and costs about 2 * grp + 2 key-tile steps.  Items are ranked heaviest first within blocks of
@@ -668,7 +710,7 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             bool any_lo, any_hi;
             needs(jt, any_lo, any_hi);
             stage_tile<C, LO, HI, PT>(kreg, vreg, any_lo, any_hi, klo_at(buf), kslo_at(buf), khi_at(buf), kshi_at(buf), kts_at(buf),
-                                      v_at(buf), tid);
+                                      v_at(buf), lofs, tid);
         };
         stage_next(0, 0);
         if (1 < nt) {
@@ -688,10 +730,10 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         auto main_step = [&](int jt) __attribute__((always_inline)) {
             const int buf = jt & 1;
             if (jt + 1 < nt) stage_next(jt + 1, buf ^ 1);
-            score_part<C, LO, false, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), kts_at(buf), q_sq, false, qrow_in_tile, lane, c, m, mfloor, l, o, pb,
+            score_part<C, LO, false, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), lofs.score_k, lofs.score_s, kts_at(buf), q_sq, false, qrow_in_tile, lane, c, m, mfloor, l, o, pb,
                                      [&]() __attribute__((always_inline)) { if (jt + 2 < nt) load_tile<C>(kreg, khead + (int64_t)(jt + 2) * BT * D, tid); });
             if (jt + 2 < nt) load_tile<C>(vreg, vhead + (int64_t)(jt + 2) * BT * D, tid);
-            value_part<C>(v_at(buf), lane, o, pb);
+            value_part<C>(v_at(buf), lofs.value_v, o, pb);
             __syncthreads();
         };
         auto band_step = [&](int jt) __attribute__((always_inline)) {
@@ -701,16 +743,16 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             if (jt + 1 < nt) stage_next(jt + 1, buf ^ 1);
             if (active) {
                 if (!tile_hi(it, jt)) {
-                    score_part<C, LO, true, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), kts_at(buf), q_sq, diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
+                    score_part<C, LO, true, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), lofs.score_k, lofs.score_s, kts_at(buf), q_sq, diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
                 } else if constexpr (TWO) {
-                    score_part<C, HI, true, PT>(qr_hi, qs_hi, khi_at(buf), kshi_at(buf), kts_at(buf), q_sq, diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
+                    score_part<C, HI, true, PT>(qr_hi, qs_hi, khi_at(buf), kshi_at(buf), score_k_lane<C, HI>(fresh(lane)), lofs.score_s, kts_at(buf), q_sq, diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
                 }
             }
             if (jt + 2 < nt) {
                 load_tile<C>(kreg, khead + (int64_t)(jt + 2) * BT * D, tid);
                 load_tile<C>(vreg, vhead + (int64_t)(jt + 2) * BT * D, tid);
             }
-            if (active) value_part<C>(v_at(buf), lane, o, pb);
+            if (active) value_part<C>(v_at(buf), lofs.value_v, o, pb);
             __syncthreads();
         };
         if constexpr (!GENERAL) {
