@@ -145,8 +145,9 @@ DMA_DEV int encode8_e2m1(const float (&x)[8], int code)
 }
 
 // The same from eight packed bf16 (no pre-scale): the convert reads the bf16 pairs directly.
-// Each source dword is first pinned into a VGPR of its own: with the source taken straight out of a
-// 128-bit register tuple this compiler emitted the tuple's first register for all four converts.
+// Each source dword is first pinned into a VGPR of its own: with the elements of the 128-bit vector named directly in
+// the builtins this compiler emits the FIRST register of the source tuple for all four converts (wrong codes).
+// tests/test_isa.py checks the generated code of every instance for four distinct source registers per group.
 DMA_DEV int encode8_e2m1_bf16(const v4i& w, int code)
 {
     const float sc = cvt_scale_operand(code);

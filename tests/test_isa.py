@@ -1,0 +1,33 @@
+"""Checks on the generated gfx950 code (no GPU needed: hipcc cross-compiles).
+
+The packed-bf16 FP4 convert of the K staging takes its four source dwords out of one 128-bit load tuple.  One shape of
+that code made the compiler name the tuple's first register in all four converts (wrong codes, caught by the parity
+tests at the time); this test pins the generated code: every group of four converts into one destination reads four
+different source registers.  (The compiler is the image's; the check guards edits of the source.)
+"""
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_2604_03950_amd import build as B
+
+
+@pytest.mark.parametrize("lo,hi", [(2, 3), (2, 1), (2, 4), (2, 2)])      # every pair whose low format is MXFP4
+def test_fp4_convert_groups_read_four_registers(tmp_path, lo, hi):
+    out = tmp_path / f"inst_{lo}_{hi}.s"
+    flags = [f for f in B.HIPCC_FLAGS if f != "-fPIC"]
+    cmd = ["hipcc"] + flags + [f"-DDMA_LO={lo}", f"-DDMA_HI={hi}", "-S", "--cuda-device-only", "-o", str(out),
+                              os.path.join(B.CSRC, "dma_attn_inst.hip")]
+    subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    lines = [ln.strip() for ln in open(out) if "v_cvt_scalef32_pk_fp4_bf16" in ln]
+    assert len(lines) >= 16 and len(lines) % 4 == 0
+    want_sel = ["", "[0,0,1,0]", "[0,0,0,1]", "[0,0,1,1]"]
+    for i in range(0, len(lines), 4):
+        grp = lines[i:i + 4]
+        sels = [(re.search(r"op_sel:(\[[0-9,]+\])", ln).group(1) if "op_sel" in ln else "") for ln in grp]
+        assert sels == want_sel, grp
+        ops = [ln.split() for ln in grp]
+        assert len({o[1] for o in ops}) == 1, grp             # one destination dword
+        assert len({o[2] for o in ops}) == 4, grp             # four different source registers
