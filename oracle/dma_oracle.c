@@ -393,7 +393,7 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
     for (int d = 0; d < D; ++d) { O[d] = 0.0; SL[d] = 0.0; }
 
     const int64_t it = i / tile;
-    const int64_t n_tiles = causal ? it + 1 : S / tile;
+    const int64_t n_tiles = causal ? it + 1 : (S + tile - 1) / tile;   /* the last tile may be partial: keys >= S do not exist */
     for (int64_t jt = 0; jt < n_tiles; ++jt) {
         const int64_t dist = (it >= jt) ? it - jt : jt - it;
         const int use_hi = dist < (int64_t)band || jt < (int64_t)sink;
@@ -404,7 +404,7 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
         for (int t = 0; t < tile; ++t) {
             int64_t j = jt * tile + t;
             double acc;
-            if (causal && j > i) {
+            if ((causal && j > i) || j >= S) {
                 acc = -INFINITY;
             } else {
                 acc = 0.0;
@@ -421,7 +421,7 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
         for (int d = 0; d < D; ++d) { O[d] *= alpha; SL[d] *= alpha; }
         for (int t = 0; t < tile; ++t) {
             int64_t j = jt * tile + t;
-            if (causal && j > i) continue;             /* p = 2^(-inf) = 0 */
+            if ((causal && j > i) || j >= S) continue; /* p = 2^(-inf) = 0 */
             double p = exp2(s[t] - mnew);
             psum += p;
             double ph = p_round ? oracle_round_to_bf16(p) : p;
@@ -471,7 +471,7 @@ int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t
                             int64_t n_rows, float *out, float *slack)
 {
     if (!q || !k || !v || !out || (!rows && n_rows > 0)) return ORACLE_ERR_ARG;
-    if (sink < 0 || (!causal && S % tile != 0)) return ORACLE_ERR_ARG;
+    if (sink < 0) return ORACLE_ERR_ARG;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || S <= 0 || D <= 0 || D % 32 != 0 || D > 512)
         return ORACLE_ERR_ARG;
     if (tile <= 0 || band < 0) return ORACLE_ERR_ARG;

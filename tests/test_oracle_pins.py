@@ -537,3 +537,20 @@ def test_token_scale_attention_matches_per_element_rewrite(oracle, tiny, band, c
     b = oracle.dma_attn(q, k, v, tile=w.tile, band=band, hi_fmt=oracle.FMT_BF16, lo_fmt=oracle.FMT_BF16, causal=causal,
                         per_token=True)
     assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------ sequence lengths that are not a multiple of the tile
+
+@pytest.mark.parametrize("S,causal", [(200, True), (200, False), (65, True), (65, False), (1, True), (130, False)])
+def test_ragged_sequence_matches_per_element_rewrite(oracle, tiny, S, causal):
+    """The last key tile may be partial (Sec. 3.2 tiles the sequence with a ceiling): keys past the end do not exist."""
+    w, q, k, v = tiny
+    q, k, v = (np.ascontiguousarray(a[:, :, :S]) for a in (q, k, v))
+    for band, sink in ((1, 0), (2, 1)):
+        got = oracle.dma_attn(q, k, v, tile=64, band=band, sink=sink, causal=causal)[0]
+        want = brute.dma_attention(q[0], k[0], v[0], tile=64, band=band, sink=sink, causal=causal)
+        assert np.max(np.abs(got - want)) < 2e-6
+    tq, tk, tv = (torch.from_numpy(wl.bf16_bits_to_f32(a)).double() for a in (q, k, v))
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=causal).numpy()
+    got = oracle.dma_attn(q, k, v, tile=64, band=1, hi_fmt=oracle.FMT_BF16, lo_fmt=oracle.FMT_BF16, p_round=False, causal=causal)
+    assert np.max(np.abs(got - want)) < 2e-6
