@@ -89,7 +89,9 @@ int dma_mx_quantize_dual(const void* x_bf16, int64_t rows, int D, int is_query,
  *                     Supported pairs (lo, hi): (E2M1, E4M3), (E2M1, E5M2), (E2M1, E2M1), (E4M3, E4M3),
  *                     (E5M2, E5M2), (BF16, BF16); any other pair returns DMA_ERR_UNSUPPORTED.
  *   Key tiles are visited in ascending order in every variant.
- *   The logical tile is B_M = B_N = 128 for dma_attn_fwd; D must be 128 and S a multiple of 128.
+ *   The logical tile is B_M = B_N = 128 for dma_attn_fwd and D must be 128.  S >= 1 is arbitrary: the last tile may be
+ *   partial (Sec. 3.2 tiles the sequence with a ceiling); keys past the end do not exist and rows past the end are
+ *   not written.  S * D * 4 must stay below 4 GiB.
  *
  *   Per key tile: scores in base 2 (the factor log2(e)/sqrt(D) is folded into Q before quantization;
  *   for BF16 it multiplies the binary32 score), keys after the query masked to -inf on the diagonal

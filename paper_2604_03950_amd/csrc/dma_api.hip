@@ -91,14 +91,16 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
         per_token = opts->per_token_scale;
         if (opts->pv_fmt != DMA_FMT_BF16) return DMA_ERR_UNSUPPORTED;
     }
-    if (S % tile != 0) return DMA_ERR_UNSUPPORTED;
+    if (tile != 64 && tile != 128) return DMA_ERR_UNSUPPORTED;
+    if ((int64_t)S * D * 4 >= ((int64_t)1 << 32)) return DMA_ERR_UNSUPPORTED;      // one head of the output must fit a 4 GiB buffer resource
     if ((int64_t)B * Hq * S * D > (int64_t)1 << 40) return DMA_ERR_UNSUPPORTED;
     dma::AttnArgs a;
     a.q = q; a.k = k; a.v = v; a.out = (float*)out;
     a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.S = S; a.D = D;
     a.tile = tile;
-    a.band = diag_band_tiles > S / tile ? S / tile : diag_band_tiles;
-    a.sink = sink > S / tile ? S / tile : sink;
+    const int n_tiles = (S + tile - 1) / tile;          // the last tile may be partial
+    a.band = diag_band_tiles > n_tiles ? n_tiles : diag_band_tiles;
+    a.sink = sink > n_tiles ? n_tiles : sink;
     a.causal = causal != 0;
     a.per_token = per_token;
     // public element format -> product path of the kernels: 3 / 4 = MXFP8 (E4M3 / E5M2) decoded exactly to bf16 and

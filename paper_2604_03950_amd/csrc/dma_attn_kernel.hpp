@@ -75,14 +75,33 @@ struct Cfg {
 //   bf16 MFMA (k = 16 per step kk = 4h + t): the lane's 8 elements of step kk are chunk t of block 2h + g -- a
 //   permutation of the head dimension against the instruction's natural order, which the K side mirrors (see score_part).
 // ---------------------------------------------------------------------------------------------
-template <typename C>
-DMA_DEV void load_q_raw(v4i (&raw)[C::NKK], const uint16_t* __restrict__ qhead, int row0, int j, int g)
+// Global memory goes through buffer resources whose size is the valid part of the [S, D] matrix: a 16-byte access
+// past row S - 1 is out of range for the hardware bounds check, reads as zero and is dropped on a store, so a partial
+// last tile needs no address guards.  Only the per-lane offset operand takes part in that check (the scalar offset
+// operand does not), so everything that can run past the end is in the per-lane offset or in the resource's base.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+DMA_DEV rsrc_t make_rsrc(const void* base, uint32_t bytes)
 {
-    const uint16_t* rowp = qhead + (int64_t)(row0 + j) * C::D + 32 * g;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);   // raw dword buffer
+}
+DMA_DEV v4i buffer_load16(rsrc_t r, unsigned byte_offset)
+{
+    return __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_offset, 0, 0));
+}
+DMA_DEV void buffer_store16(rsrc_t r, unsigned byte_offset, v4f v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), r, (int)byte_offset, 0, 0);
+}
+
+// qmat: the [S, D] bf16 query matrix of the head (resource over its S rows); rows >= S read as zero.
+template <typename C>
+DMA_DEV void load_q_raw(v4i (&raw)[C::NKK], rsrc_t qmat, int row0, int j, int g)
+{
+    const unsigned off = (unsigned)(row0 + j) * (C::D * 2) + 64 * g;
 #pragma unroll
     for (int h = 0; h < C::NH; ++h)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) raw[4 * h + t] = *(const v4i*)(rowp + 64 * h + 8 * t);
+        for (int t = 0; t < 4; ++t) raw[4 * h + t] = buffer_load16(qmat, off + 128 * h + 16 * t);
 }
 
 // Absolute maximum of the lane's query row after the softmax pre-scale (both half-waves hold half of the row).
@@ -223,20 +242,34 @@ struct LaneOffsets {
 };
 
 // Chunk r of thread tid is 16-byte chunk r * T + tid of the dense tile: key r * (T / CPR) + tid / CPR.
-template <typename C>
-DMA_DEV void load_tile(v4i (&reg)[C::CPT], const uint16_t* __restrict__ tile, int tid)
+template <typename C, bool BOUNDED>
+DMA_DEV void load_tile(v4i (&reg)[C::CPT], const uint16_t* __restrict__ mat, int row0, int S, int tid)
 {
-    // the tile address is uniform: kept in scalar registers so that the loads take the (scalar base + 32-bit lane
-    // offset) form and need no vector address arithmetic
-    typedef const __attribute__((address_space(1))) v4i* global_v4i;
+    // rows [row0, row0 + BT) of the [S, D] bf16 matrix `mat` (uniform).  BOUNDED: rows >= S read as zero; otherwise
+    // the caller guarantees row0 + BT <= S.
+    constexpr int KPR = C::T / C::CPR;                       // rows per chunk round
     const unsigned lane_off = (unsigned)fresh(tid) * 16u;
+    if constexpr (!BOUNDED) {
+        // whole tile: plain loads in the (scalar base + 32-bit lane offset) form; the bases are pinned in scalar
+        // registers so that no vector address arithmetic is generated
+        typedef const __attribute__((address_space(1))) v4i* global_v4i;
 #pragma unroll
-    for (int r = 0; r < C::CPT; ++r) {
-        const uint64_t t64 = (uint64_t)tile + (uint64_t)r * C::T * 16;
-        uint32_t lo = (uint32_t)t64, hi = (uint32_t)(t64 >> 32);
-        asm volatile("" : "+s"(lo), "+s"(hi));           // pinned in scalar registers, opaque to re-association
-        const uint64_t sbase = ((uint64_t)hi << 32) | (uint64_t)lo;
-        reg[r] = *(global_v4i)(sbase + (uint64_t)lane_off);
+        for (int r = 0; r < C::CPT; ++r) {
+            const uint64_t t64 = (uint64_t)(mat + (int64_t)row0 * C::D) + (uint64_t)r * C::T * 16;
+            uint32_t lo = (uint32_t)t64, hi = (uint32_t)(t64 >> 32);
+            asm volatile("" : "+s"(lo), "+s"(hi));
+            reg[r] = *(global_v4i)((((uint64_t)hi << 32) | (uint64_t)lo) + (uint64_t)lane_off);
+        }
+    } else {
+        // one buffer resource per chunk round, based at the round's first row and as long as what is left of the
+        // matrix from there
+#pragma unroll
+        for (int r = 0; r < C::CPT; ++r) {
+            const int row = row0 + r * KPR;
+            const int64_t left = (int64_t)(S - row) * (C::D * 2);
+            const rsrc_t rs = make_rsrc(mat + (int64_t)row * C::D, left > 0 ? (uint32_t)left : 0u);
+            reg[r] = buffer_load16(rs, lane_off);
+        }
     }
 }
 
@@ -323,7 +356,7 @@ DMA_DEV v8i widen(const v4i& lo, const v4i& hi) { return v8i{lo[0], lo[1], lo[2]
 // the key (one float per key at ktssrc) before the maximum is taken.
 template <typename C, int FMT, bool MAYBE_DIAG, bool PT, int QR, typename F>
 DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned kssrc, unsigned k_lane, unsigned s_lane,
-                        unsigned ktssrc, float q_sq, bool diagonal, int qrow_in_tile, int lane, float c,
+                        unsigned ktssrc, float q_sq, bool diagonal, int key_limit, int qrow_in_tile, int lane, float c,
                         float& m, float& mfloor, float& l, v16f (&o)[C::NDB], v8bf (&pb)[2 * C::NKB], F&& after_mfma)
 {
     lane = fresh(lane);
@@ -429,16 +462,17 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
     }
     after_mfma();
 
-    // ---- causal mask on the tile that straddles the diagonal: key > query -> -inf
+    // ---- causal mask on the tile that straddles the diagonal (key > query -> -inf) and / or the keys of a partial
+    // last tile that lie past the end of the sequence (key >= key_limit -> -inf)
     if constexpr (MAYBE_DIAG) {
-        if (diagonal) {
-            const int qi = qrow_in_tile + j;
+        if (diagonal || key_limit < C::BT) {
+            const int last_key = min(diagonal ? qrow_in_tile + j : C::BT - 1, key_limit - 1);
 #pragma unroll
             for (int kb = 0; kb < C::NKB; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int kj = kb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (kj > qi) s[kb][r] = -INFINITY;
+                    if (kj > last_key) s[kb][r] = -INFINITY;
                 }
         }
     }
@@ -608,7 +642,7 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     // everything), so the workers move from block to block together and share few K/V streams at a time.  When the
     // (batch, kv head) units divide over the 8 XCDs (workgroup i runs on XCD i % 8), each XCD keeps its own units, so
     // the K/V stream of a unit stays in one L2.
-    const int N = S / BT;                // logical tiles per sequence (host guarantees N % TPW == 0)
+    const int N = (S + BT - 1) / BT;     // logical tiles per sequence, the last one may be partial (host guarantees N % TPW == 0)
     const int NG = N / TPW;              // tile groups
     const int group = Hq / Hkv;
     const int units = B * Hkv;
@@ -662,6 +696,9 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         } else {
             w0 = w1 = nt;
         }
+        // without the causal mask a partial last tile must be a band tile (its missing keys are masked there)
+        const bool ragged_tail = !causal && S % BT != 0;
+        if (ragged_tail) w0 = min(w0, nt - 1);
         if (s1 > w0) { w1 = max(w1, s1); w0 = 0; s1 = 0; }
         // what the workgroup needs of key tile jt in LDS
         auto needs = [&](int jt, bool& any_lo, bool& any_hi) __attribute__((always_inline)) {
@@ -695,9 +732,9 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         float q_sq = 1.f;                                // S_q of the lane's query row (per-token scale)
         {
             v4i qraw[C::NKK];
-            load_q_raw<C>(qraw, qhead, qrow, fresh(lane) & 31, fresh(lane) >> 5);
-            load_tile<C>(kreg, khead, tid);
-            load_tile<C>(vreg, vhead, tid);
+            load_q_raw<C>(qraw, make_rsrc(qhead, (uint32_t)S * (D * 2)), qrow, fresh(lane) & 31, fresh(lane) >> 5);
+            load_tile<C, GENERAL>(kreg, khead, 0, S, tid);
+            load_tile<C, GENERAL>(vreg, vhead, 0, S, tid);
             __builtin_amdgcn_sched_barrier(0);           // every request is out before the first result is needed
             float inv_sq = 1.f;
             if constexpr (PT) token_scale(q_row_amax<C>(qraw, c), q_sq, inv_sq);
@@ -714,8 +751,8 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         };
         stage_next(0, 0);
         if (1 < nt) {
-            load_tile<C>(kreg, khead + (int64_t)BT * D, tid);
-            load_tile<C>(vreg, vhead + (int64_t)BT * D, tid);
+            load_tile<C, GENERAL>(kreg, khead, BT, S, tid);
+            load_tile<C, GENERAL>(vreg, vhead, BT, S, tid);
         }
         __syncthreads();
 
@@ -730,9 +767,9 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         auto main_step = [&](int jt) __attribute__((always_inline)) {
             const int buf = jt & 1;
             if (jt + 1 < nt) stage_next(jt + 1, buf ^ 1);
-            score_part<C, LO, false, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), lofs.score_k, lofs.score_s, kts_at(buf), q_sq, false, qrow_in_tile, lane, c, m, mfloor, l, o, pb,
-                                     [&]() __attribute__((always_inline)) { if (jt + 2 < nt) load_tile<C>(kreg, khead + (int64_t)(jt + 2) * BT * D, tid); });
-            if (jt + 2 < nt) load_tile<C>(vreg, vhead + (int64_t)(jt + 2) * BT * D, tid);
+            score_part<C, LO, false, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), lofs.score_k, lofs.score_s, kts_at(buf), q_sq, false, BT, qrow_in_tile, lane, c, m, mfloor, l, o, pb,
+                                     [&]() __attribute__((always_inline)) { if (jt + 2 < nt) load_tile<C, GENERAL>(kreg, khead, (jt + 2) * BT, S, tid); });
+            if (jt + 2 < nt) load_tile<C, GENERAL>(vreg, vhead, (jt + 2) * BT, S, tid);
             value_part<C>(v_at(buf), lofs.value_v, o, pb);
             __syncthreads();
         };
@@ -740,17 +777,19 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             const int buf = jt & 1;
             const bool active = !causal || jt <= it;
             const bool diagonal = causal && jt == it;
+            // keys of this tile that exist (a partial last tile; under the causal mask the diagonal rule covers it)
+            const int key_limit = causal ? BT : min(BT, S - jt * BT);
             if (jt + 1 < nt) stage_next(jt + 1, buf ^ 1);
             if (active) {
                 if (!tile_hi(it, jt)) {
-                    score_part<C, LO, true, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), lofs.score_k, lofs.score_s, kts_at(buf), q_sq, diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
+                    score_part<C, LO, true, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), lofs.score_k, lofs.score_s, kts_at(buf), q_sq, diagonal, key_limit, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
                 } else if constexpr (TWO) {
-                    score_part<C, HI, true, PT>(qr_hi, qs_hi, khi_at(buf), kshi_at(buf), score_k_lane<C, HI>(fresh(lane)), lofs.score_s, kts_at(buf), q_sq, diagonal, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
+                    score_part<C, HI, true, PT>(qr_hi, qs_hi, khi_at(buf), kshi_at(buf), score_k_lane<C, HI>(fresh(lane)), lofs.score_s, kts_at(buf), q_sq, diagonal, key_limit, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
                 }
             }
             if (jt + 2 < nt) {
-                load_tile<C>(kreg, khead + (int64_t)(jt + 2) * BT * D, tid);
-                load_tile<C>(vreg, vhead + (int64_t)(jt + 2) * BT * D, tid);
+                load_tile<C, GENERAL>(kreg, khead, (jt + 2) * BT, S, tid);
+                load_tile<C, GENERAL>(vreg, vhead, (jt + 2) * BT, S, tid);
             }
             if (active) value_part<C>(v_at(buf), lofs.value_v, o, pb);
             __syncthreads();
@@ -761,10 +800,13 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         } else {
             // four runs in a row (each may be empty): sink band tiles, main tiles, band tiles around the diagonal, and
             // (without the causal mask) the main tiles above the window
+            // ... and a partial last tile, whose missing keys a band step masks
+            const int mend = ragged_tail ? max(w1, nt - 1) : nt;
             for (int jt = 0; jt < s1; ++jt) band_step(jt);
             for (int jt = s1; jt < w0; ++jt) main_step(jt);
             for (int jt = w0; jt < w1; ++jt) band_step(jt);
-            for (int jt = w1; jt < nt; ++jt) main_step(jt);
+            for (int jt = w1; jt < mend; ++jt) main_step(jt);
+            for (int jt = mend; jt < nt; ++jt) band_step(jt);
         }
 
         // ---- O / l, transposed through LDS (free after the barrier above) so that every output row leaves as whole
@@ -777,7 +819,8 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             const unsigned region = lds0 + wave * EPI_WAVE;
             const unsigned wr = pin(region + j * EPI_STRIDE + 16 * g);
             const unsigned rd = pin(region + rsub * EPI_STRIDE + 16 * piece);
-            float* obase = ohead + (int64_t)(qrow + rsub) * D + 4 * piece;
+            const rsrc_t omat = make_rsrc(ohead, (uint32_t)S * (D * 4));      // rows >= S (partial last tile) are dropped
+            const unsigned obase = (unsigned)(qrow + rsub) * (D * 4) + 16 * piece;
 #pragma unroll
             for (int slab = 0; slab < D / EPI_COLS; ++slab) {
 #pragma unroll
@@ -792,7 +835,7 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const v4f val = lds_read<v4f>(rd + 4 * i * EPI_STRIDE);
-                    *(v4f*)(obase + (int64_t)(4 * i) * D + slab * EPI_COLS) = val;
+                    buffer_store16(omat, obase + 4 * i * (D * 4) + slab * (EPI_COLS * 4), val);
                 }
             }
         }
@@ -821,7 +864,7 @@ template <int D, int BT, int TPW, int LO, int HI, bool GENERAL, bool PT>
 static int launch_variant(const AttnArgs& a, hipStream_t stream)
 {
     using C = Cfg<D, BT, TPW>;
-    const int N = a.S / BT;
+    const int N = (a.S + BT - 1) / BT;
     const int64_t items = (int64_t)a.B * a.Hq * (N / TPW);
     if (N % TPW != 0 || items <= 0 || items > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
     const int cus = compute_units();
@@ -852,8 +895,9 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
     return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
 }
 
-// Alg. 1 as printed (causal, no sink window) runs the straight-line instance; the sink window, the non-causal variant
-// and the per-token scale run the general one (unquantized operands have no per-token scale).
+// Alg. 1 as printed (causal, no sink window, sequence a whole number of tiles) runs the straight-line instance, whose
+// tile loads are unbounded; the sink window, the non-causal variant, the per-token scale and a partial last tile run
+// the general one, whose loads are bounded by buffer resources (unquantized operands have no per-token scale).
 template <int D, int BT, int TPW, int LO, int HI>
 static int launch_instance(const AttnArgs& a, hipStream_t stream)
 {
@@ -861,7 +905,7 @@ static int launch_instance(const AttnArgs& a, hipStream_t stream)
         if (a.per_token) return launch_variant<D, BT, TPW, LO, HI, true, true>(a, stream);
     }
 #ifndef DMA_FORCE_GENERAL
-    if (a.causal && a.sink == 0) return launch_variant<D, BT, TPW, LO, HI, false, false>(a, stream);
+    if (a.causal && a.sink == 0 && a.S % BT == 0) return launch_variant<D, BT, TPW, LO, HI, false, false>(a, stream);
 #endif
     return launch_variant<D, BT, TPW, LO, HI, true, false>(a, stream);
 }

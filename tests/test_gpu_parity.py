@@ -416,3 +416,35 @@ def test_attn_variants_full_size_sampled(dma, oracle):
     rows = wl.sample_rows(w, [1, 63], [(0, 0), (0, 31)], 64, seed=w.seed + 2)
     run_case(dma, oracle, w, q, k, v, 1, "e2m1", "e4m3", rows=rows, sink=1, explicit_tile=False)
     run_case(dma, oracle, w, q, k, v, 1, "e2m1", "e5m2", rows=rows, sink=2, explicit_tile=False)
+
+
+# ------------------------------------------------------------------ sequence lengths that are not a multiple of the tile
+
+@pytest.mark.parametrize("S", [1, 63, 65, 200, 257])
+@pytest.mark.parametrize("causal", [True, False])
+def test_attn_ragged_sequence_d64(dma, oracle, S, causal):
+    """Partial last tile (tile 64): keys past the end do not exist, rows past the end are not written."""
+    w = wl.small_variant(wl.CONFIGS["tiny"], S=S)
+    q, k, v = wl.generate(w)
+    guard = np.float32(-12345.0)
+    for band, lo, hi, sink in ((1, "e2m1", "e4m3", 0), (2, "e2m1", "e4m3", 1), (0, "e2m1", "e2m1", 0), (0, "bf16", "bf16", 0)):
+        run_case(dma, oracle, w, q, k, v, band, lo, hi, sink=sink, causal=causal)
+    # nothing is written outside the output: a guard band after the tensor stays untouched
+    qd, kd, vd = to_gpu(dma, q, k, v)
+    buf = torch.full((w.B * w.Hq * S * w.D + 4096,), float(guard), dtype=torch.float32, device="cuda")
+    out = buf[:w.B * w.Hq * S * w.D].view(w.B, w.Hq, S, w.D)
+    dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=1, tile=64, causal=causal, out=out)
+    torch.cuda.synchronize()
+    assert bool((buf[w.B * w.Hq * S * w.D:] == float(guard)).all())
+    assert bool(torch.isfinite(out).all())
+
+
+@pytest.mark.parametrize("S", [129, 300, 1000])
+@pytest.mark.parametrize("causal", [True, False])
+def test_attn_ragged_sequence_d128(dma, oracle, S, causal):
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=S, Hq=4, Hkv=2)
+    q, k, v = wl.generate(w)
+    run_case(dma, oracle, w, q, k, v, 2, "e2m1", "e4m3", causal=causal, explicit_tile=False)
+    run_case(dma, oracle, w, q, k, v, 1, "e2m1", "e4m3", sink=1, causal=causal)
+    run_case(dma, oracle, w, q, k, v, 2, "e2m1", "e4m3", per_token=True, causal=causal)
+    run_case(dma, oracle, w, q, k, v, 0, "e4m3", "e4m3", causal=causal)
