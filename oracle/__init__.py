@@ -83,6 +83,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_ref_attn_rows_ex.restype = ctypes.c_int
         L.oracle_ref_attn_rows_ex.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_int64, ctypes.c_int, ctypes.c_int, i64p, ctypes.c_int64, f64p]
+        L.oracle_values_as_seen_mxfp8.restype = ctypes.c_int
+        L.oracle_values_as_seen_mxfp8.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int64, f64p, u8p]
         L.oracle_num_threads.restype = ctypes.c_int
         L.oracle_num_threads.argtypes = []
         _lib = L
@@ -197,12 +199,13 @@ def sort_rows(rows) -> np.ndarray:
 
 def dma_attn_rows(q_bits, k_bits, v_bits, rows, *, tile: int, band: int, hi_fmt: int = FMT_E4M3,
                   lo_fmt: int = FMT_E2M1, p_round: bool = True, sink: int = 0, causal: bool = True,
-                  per_token: bool = False, with_slack: bool = False):
+                  per_token: bool = False, with_slack: bool = False, pv_mx: bool = False):
     """Diagonal-tiled attention output for the given (b, hq, i) rows -> float32 [n_rows, D].
     sink: number of leading key tiles kept in the high format; causal=False: every key tile is visited and the
     high-precision window is |jt - it| < band.  per_token: Alg. 2 Step 2 on queries and keys.  with_slack: also return, per output element, how far the
     value can move when probabilities that lie within binary32 score noise of a bf16 rounding midpoint round
-    the other way (see attn_one_row in dma_oracle.c)."""
+    the other way (see attn_one_row in dma_oracle.c).  pv_mx: the MX-format P V product (P and V in MXFP8-E4M3 with
+    blocks of 32 keys) instead of the 16-bit one; the slack then covers E4M3 rounding flips and block-scale flips."""
     q, k, v = _as_bits(q_bits), _as_bits(k_bits), _as_bits(v_bits)
     B, Hq, S, D = q.shape
     Hkv = k.shape[1]
@@ -213,10 +216,22 @@ def dma_attn_rows(q_bits, k_bits, v_bits, rows, *, tile: int, band: int, hi_fmt:
     _check(lib().oracle_dma_attn_rows_ex(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
                                          B, Hq, Hkv, S, D, tile, band, int(sink), int(bool(causal)), int(bool(per_token)),
                                          hi_fmt, lo_fmt,
-                                         int(bool(p_round)), _p(r, ctypes.c_int64), r.shape[0],
+                                         2 if pv_mx else int(bool(p_round)), _p(r, ctypes.c_int64), r.shape[0],
                                          _p(out, ctypes.c_float), _p(slack, ctypes.c_float) if with_slack else None),
            "oracle_dma_attn_rows_ex")
     return (out, slack) if with_slack else out
+
+
+def values_as_seen_mxfp8(v_bits):
+    """V of one kv head, [S, D] bf16 bits, as the MX-format P V product sees it: (decoded values float64 [S, D],
+    scale bytes uint8 [ceil(S/32), D]); blocks of 32 consecutive keys per column, zero-padded past S."""
+    v = _as_bits(v_bits)
+    S, D = v.shape
+    seen = np.empty((S, D), dtype=np.float64)
+    scales = np.empty(((S + 31) // 32, D), dtype=np.uint8)
+    _check(lib().oracle_values_as_seen_mxfp8(_p(v, ctypes.c_uint16), S, D, S, _p(seen, ctypes.c_double),
+                                             _p(scales, ctypes.c_uint8)), "oracle_values_as_seen_mxfp8")
+    return seen, scales
 
 
 def all_rows(B: int, Hq: int, S: int) -> np.ndarray:

@@ -336,6 +336,64 @@ static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, int per
 }
 
 /* ------------------------------------------------------------------------------------------ */
+/* MX-format P V (an extension beyond Alg. 1, which keeps V and P in 16 bit)                     */
+/* ------------------------------------------------------------------------------------------ */
+/* The second product contracts over keys, so its MX blocks run along the key axis: 32 consecutive
+ * keys (aligned to multiples of 32) of one head-dimension column of V, and 32 consecutive keys of
+ * one query row of P, each with one E8M0 scale byte and E4M3 elements, quantized by the rule of
+ * Alg. 2 Steps 6-7 (shared scale from the block maximum with e_max = 8, clamp to +-448, round to
+ * nearest even).  Keys at or beyond S count as zeros. */
+
+/* One block of n <= 32 real values: its scale byte and what the block looks like after
+ * quantize + decode.  x holds binary32-representable values or probabilities in [0, 1]. */
+static int block_e4m3_as_seen(const double *x, int n, double *seen)
+{
+    double amax = 0.0;
+    for (int t = 0; t < n; ++t)
+        if (fabs(x[t]) > amax) amax = fabs(x[t]);
+    long biased = 0;
+    if (amax > 0.0) {
+        int ex;
+        (void)frexp(amax, &ex);
+        biased = (long)(ex - 1) - 8 + 127;          /* floor(log2 amax) - e_max, biased */
+        if (biased < 0) biased = 0;
+        if (biased > 254) biased = 254;
+    }
+    for (int t = 0; t < n; ++t) {
+        double y = ldexp(x[t], 127 - (int)biased);
+        if (y > 448.0) y = 448.0;
+        if (y < -448.0) y = -448.0;
+        seen[t] = ldexp(oracle_e4m3_decode(oracle_e4m3_encode(y, signbit(x[t]) ? 1 : 0)), (int)biased - 127);
+    }
+    return (int)biased;
+}
+
+/* V of one kv head as the MX-format P V product sees it: v [S, D] bf16 -> seen [n, D] doubles for the
+ * keys 0 .. n-1 (n a multiple of 32 or n = S; blocks that reach past S are padded with zeros). */
+int oracle_values_as_seen_mxfp8(const uint16_t *v, int64_t S, int D, int64_t n, double *seen, uint8_t *scales)
+{
+    if (!v || !seen || S <= 0 || D <= 0 || n <= 0 || n > ((S + 31) / 32) * 32) return ORACLE_ERR_ARG;
+    const int64_t nblk = (n + 31) / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < nblk; ++b) {
+        double x[32], y[32];
+        for (int d = 0; d < D; ++d) {
+            for (int t = 0; t < 32; ++t) {
+                const int64_t j = b * 32 + t;
+                x[t] = (j < S) ? (double)oracle_bf16_to_f32(v[j * D + d]) : 0.0;
+            }
+            const int sc = block_e4m3_as_seen(x, 32, y);
+            if (scales) scales[b * D + d] = (uint8_t)sc;
+            for (int t = 0; t < 32; ++t) {
+                const int64_t j = b * 32 + t;
+                if (j < n && j < S) seen[j * D + d] = y[t];
+            }
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------------ */
 /* Diagonal-tiled attention for a list of query rows (Alg. 1 + Sec. 3.2)                       */
 /* ------------------------------------------------------------------------------------------ */
 
@@ -355,7 +413,11 @@ static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, int per
  *   elsewhere), and the mask applies to the diagonal tile whatever its format.
  *   OnlineSoftmax (Sec. 3.2): m' = max(m, max_j s_j); alpha = 2^(m-m'); p_j = 2^(s_j - m');
  *   l = alpha*l + sum_j p_j;  O = alpha*O + sum_j p^_j * v_j;  finally O / l (line 12).
- *   Reading: p^_j = p_j rounded to bf16 when p_round != 0 (l sums the unrounded p_j).
+ *   Reading: p^_j = p_j rounded to bf16 when p_round = 1 (l sums the unrounded p_j).
+ *   p_round = 2 (MX-format P V, beyond the paper): within the key tile, each block of 32 consecutive
+ *   keys of the row's p_j (masked keys count as 0) is quantized to MXFP8-E4M3 as described above, V is
+ *   taken as oracle_values_as_seen_mxfp8 gives it, and O accumulates the products of the two decoded
+ *   values; l still sums the unrounded p_j.
  */
 /* Extensions beyond Alg. 1 (both change only which key tiles are visited and in which format):
  *   sink  : the first `sink` key tiles are high precision for every query tile (Sec. 5.3, table
@@ -378,11 +440,12 @@ static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, int per
  * of a midpoint of (spacing_j * |v_jd|), carried through the rescaling like O, divided by l: the most
  * the output can move through flips that binary32 scores can cause. */
 static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const double *kseen_hi,
-                         const uint16_t *v, int64_t i, int64_t S, int D, int tile, int band, int sink,
+                         const uint16_t *v, const double *vseen, int64_t i, int64_t S, int D, int tile, int band, int sink,
                          int causal, int per_token, int hi_fmt, int lo_fmt, int p_round, float *out, float *slack)
 {
     double q_lo[512], q_hi[512], O[512], SL[512];
-    double *s = (double *)malloc(sizeof(double) * (size_t)tile);
+    double *s = (double *)malloc(sizeof(double) * (size_t)tile * 3);
+    double *pt = s + tile, *ph_t = s + 2 * tile;          /* p and its rounded image for the keys of a tile */
     row_as_seen(qrow, D, lo_fmt, 1, per_token, q_lo);
     row_as_seen(qrow, D, hi_fmt, 1, per_token, q_hi);
     const double c = 1.4426950408889634074 / sqrt((double)D);
@@ -421,23 +484,83 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
         for (int d = 0; d < D; ++d) { O[d] *= alpha; SL[d] *= alpha; }
         for (int t = 0; t < tile; ++t) {
             int64_t j = jt * tile + t;
-            if ((causal && j > i) || j >= S) continue; /* p = 2^(-inf) = 0 */
-            double p = exp2(s[t] - mnew);
-            psum += p;
-            double ph = p_round ? oracle_round_to_bf16(p) : p;
-            const uint16_t *vr = v + j * D;
-            for (int d = 0; d < D; ++d) O[d] += ph * (double)oracle_bf16_to_f32(vr[d]);
-            if (slack && p_round && p > 0.0) {
-                int ex;
-                (void)frexp(p, &ex);
-                int quantum = (ex - 1) - 7;
-                if (quantum < -133) quantum = -133;
-                const double sp = ldexp(1.0, quantum);                 /* spacing of bf16 numbers at p */
-                const double r = p / sp;
-                const double dist = fabs(r - floor(r) - 0.5) * sp;     /* distance of p to the nearest midpoint */
-                const double eps = ldexp(fabs(s[t]) + fabs(mnew) + 1.0, -20) * 0.6931471805599453 * p;
-                if (dist <= eps)
-                    for (int d = 0; d < D; ++d) SL[d] += sp * fabs((double)oracle_bf16_to_f32(vr[d]));
+            pt[t] = ((causal && j > i) || j >= S) ? 0.0 : exp2(s[t] - mnew);   /* 2^(-inf) = 0 */
+            psum += pt[t];
+        }
+        if (p_round == 2) {
+            /* MX-format P V: blocks of 32 keys of the tile */
+            for (int t0 = 0; t0 < tile; t0 += 32) {
+                const int n = (tile - t0 < 32) ? tile - t0 : 32;
+                const int sc = block_e4m3_as_seen(pt + t0, n, ph_t + t0);
+                if (!slack) continue;
+                /* slack: the block's scale is decided by floor(max_j (s_j - m')); an implementation with binary32
+                 * scores may see that maximum on the other side of an integer when it lies within the score noise
+                 * of one, and then the whole block is rounded one binade coarser or finer: at most 2^-3 of each
+                 * p_j, or one subnormal step.  The row maximum itself gives exactly 0 on both sides. */
+                double xmax = -INFINITY, second = m - mnew;
+                for (int t = 0; t < tile; ++t) {
+                    const int64_t j = jt * tile + t;
+                    if ((causal && j > i) || j >= S) continue;
+                    const double x = s[t] - mnew;
+                    if (t >= t0 && t < t0 + n) { if (x > xmax) xmax = x; }
+                    else if (x > second) second = x;
+                }
+                if (xmax == -INFINITY) continue;
+                const double eps_x = ldexp(fabs(xmax + mnew) + fabs(mnew) + 1.0, -20);
+                const double frac = fabs(xmax - nearbyint(xmax));
+                const int scale_unsure = (xmax == 0.0) ? (second >= -eps_x) : (frac <= eps_x);
+                for (int t = t0; t < t0 + n; ++t) {
+                    const int64_t j = jt * tile + t;
+                    const double p = pt[t];
+                    if (!(p > 0.0)) continue;
+                    const double *vr = vseen + j * D;
+                    const double unit = ldexp(1.0, sc - 127);
+                    if (scale_unsure) {
+                        const double e = ldexp(p, -3) + ldexp(unit, -8);
+                        for (int d = 0; d < D; ++d) SL[d] += e * fabs(vr[d]);
+                        continue;
+                    }
+                    /* rounding flip of one element: spacing of E4M3 numbers at y = p / 2^scale (2^-9 for subnormals) */
+                    double y = p / unit;
+                    if (y >= 448.0) continue;                         /* clamped either way */
+                    int ex;
+                    (void)frexp(y, &ex);
+                    int quantum = (ex - 1) - 3;
+                    if (quantum < -9) quantum = -9;
+                    const double sp = ldexp(1.0, quantum);
+                    const double r = y / sp;
+                    const double dist = fabs(r - floor(r) - 0.5) * sp * unit;
+                    const double eps = ldexp(fabs(s[t]) + fabs(mnew) + 1.0, -20) * 0.6931471805599453 * p;
+                    if (dist <= eps)
+                        for (int d = 0; d < D; ++d) SL[d] += sp * unit * fabs(vr[d]);
+                }
+            }
+            for (int t = 0; t < tile; ++t) {
+                const int64_t j = jt * tile + t;
+                if (!(pt[t] > 0.0)) continue;
+                const double *vr = vseen + j * D;
+                for (int d = 0; d < D; ++d) O[d] += ph_t[t] * vr[d];
+            }
+        } else {
+            for (int t = 0; t < tile; ++t) {
+                int64_t j = jt * tile + t;
+                if ((causal && j > i) || j >= S) continue; /* p = 2^(-inf) = 0 */
+                double p = pt[t];
+                double ph = p_round ? oracle_round_to_bf16(p) : p;
+                const uint16_t *vr = v + j * D;
+                for (int d = 0; d < D; ++d) O[d] += ph * (double)oracle_bf16_to_f32(vr[d]);
+                if (slack && p_round && p > 0.0) {
+                    int ex;
+                    (void)frexp(p, &ex);
+                    int quantum = (ex - 1) - 7;
+                    if (quantum < -133) quantum = -133;
+                    const double sp = ldexp(1.0, quantum);                 /* spacing of bf16 numbers at p */
+                    const double r = p / sp;
+                    const double dist = fabs(r - floor(r) - 0.5) * sp;     /* distance of p to the nearest midpoint */
+                    const double eps = ldexp(fabs(s[t]) + fabs(mnew) + 1.0, -20) * 0.6931471805599453 * p;
+                    if (dist <= eps)
+                        for (int d = 0; d < D; ++d) SL[d] += sp * fabs((double)oracle_bf16_to_f32(vr[d]));
+                }
             }
         }
         l = alpha * l + psum;
@@ -475,6 +598,7 @@ int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || S <= 0 || D <= 0 || D % 32 != 0 || D > 512)
         return ORACLE_ERR_ARG;
     if (tile <= 0 || band < 0) return ORACLE_ERR_ARG;
+    if (p_round < 0 || p_round > 2 || (p_round == 2 && tile % 32 != 0)) return ORACLE_ERR_ARG;
     for (int f = 0; f < 2; ++f) {
         int fm = f ? hi_fmt : lo_fmt;
         if (fm != ORACLE_FMT_BF16 && !fmt_is_mx(fm)) return ORACLE_ERR_ARG;
@@ -500,15 +624,26 @@ int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t
         double *klo = keys_as_seen(kh, imax + 1, D, lo_fmt, per_token);
         double *khi = (hi_fmt == lo_fmt) ? klo : keys_as_seen(kh, imax + 1, D, hi_fmt, per_token);
         if (!klo || !khi) { free(klo); if (khi != klo) free(khi); return ORACLE_ERR_MEM; }
+        double *vseen = NULL;
+        if (p_round == 2) {
+            /* every key of the tiles visited (whole 32-key blocks), but none past the end of the sequence */
+            int64_t nv = ((imax + tile) / tile) * tile;
+            if (nv > S) nv = S;
+            vseen = (double *)malloc(sizeof(double) * (size_t)nv * (size_t)D);
+            if (!vseen || oracle_values_as_seen_mxfp8(vh, S, D, nv, vseen, NULL) != ORACLE_OK) {
+                free(vseen); free(klo); if (khi != klo) free(khi); return ORACLE_ERR_MEM;
+            }
+        }
 #pragma omp parallel for schedule(dynamic, 1)
         for (int64_t r = r0; r < r1; ++r) {
             const int64_t hq = rows[3 * r + 1], i = rows[3 * r + 2];
             const uint16_t *qrow = q + (((int64_t)b * Hq + hq) * S + i) * D;
-            attn_one_row(qrow, klo, khi, vh, i, S, D, tile, band, sink, causal, per_token, hi_fmt, lo_fmt, p_round, out + r * D,
+            attn_one_row(qrow, klo, khi, vh, vseen, i, S, D, tile, band, sink, causal, per_token, hi_fmt, lo_fmt, p_round, out + r * D,
                          slack ? slack + r * D : NULL);
         }
         if (khi != klo) free(khi);
         free(klo);
+        free(vseen);
         r0 = r1;
     }
     return ORACLE_OK;

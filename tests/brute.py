@@ -120,19 +120,23 @@ def round_bf16_nearest_of_two(p: np.ndarray) -> np.ndarray:
 
 
 def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p_round=True, sink=0, causal=True,
-                  score_dtype=np.float64, per_token=False):
+                  score_dtype=np.float64, per_token=False, pv_mx=False):
     """Per-element rewrite of the diagonal-tiled attention for q[Hq,S,D], k,v[Hkv,S,D] (one batch).
 
     For every visible pair (i, j) the score comes from the format of the tile pair (i // tile, j // tile):
     high when the tiles are closer than `band` or the key tile is one of the first `sink`; with
     p_round the probabilities are formed against the running maximum over key-tile prefixes and
     rounded to bf16, otherwise it is a plain base-2 row softmax.  causal=False: every key is visible.
-    score_dtype=np.float32 rounds every score to binary32 first (what an implementation with binary32 scores sees)."""
+    score_dtype=np.float32 rounds every score to binary32 first (what an implementation with binary32 scores sees).
+    pv_mx: instead of the bf16 rounding, every block of 32 consecutive keys (aligned to multiples of 32, masked keys
+    and keys past the end counting as zeros) of a row's probabilities, and of every column of V, is an MXFP8-E4M3 block."""
     Hq, S, D = q_bits.shape
     Hkv = k_bits.shape[0]
     g = Hq // Hkv
     out = np.zeros((Hq, S, D))
     v = bf16_bits_to_f64(v_bits)
+    if pv_mx:
+        v = np.stack([values_in_key_blocks(v[hk]) for hk in range(Hkv)])
     for h in range(Hq):
         _, _, q_hi = quantize_rows(q_bits[h], hi, True, per_token)
         _, _, q_lo = quantize_rows(q_bits[h], lo, True, per_token)
@@ -156,10 +160,32 @@ def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p
             mj = run[np.arange(nk) // tile]              # maximum in force when key j was processed
             mfin = run[-1]
             p_at = np.exp2(si - mj)
-            p_hat = round_bf16_nearest_of_two(p_at)
+            if pv_mx:
+                p_hat = np.zeros(nk)
+                for b0 in range(0, nk, 32):
+                    blk = np.zeros(32)
+                    n = min(32, nk - b0)
+                    blk[:n] = p_at[b0:b0 + n]
+                    p_hat[b0:b0 + n] = quantize_block(blk, "e4m3")[2][:n]
+            else:
+                p_hat = round_bf16_nearest_of_two(p_at)
             w_num = p_hat * np.exp2(mj - mfin)
             w_den = (p_at * np.exp2(mj - mfin)).sum()
             out[h, i] = (w_num @ v[h // g, :nk]) / w_den
+    return out
+
+
+def values_in_key_blocks(v: np.ndarray) -> np.ndarray:
+    """v [S, D] real values -> every column cut into blocks of 32 consecutive keys (zero-padded at the end), each an
+    MXFP8-E4M3 block; the decoded values, [S, D]."""
+    S, D = v.shape
+    out = np.zeros((S, D))
+    for b0 in range(0, S, 32):
+        n = min(32, S - b0)
+        for d in range(D):
+            blk = np.zeros(32)
+            blk[:n] = v[b0:b0 + n, d]
+            out[b0:b0 + n, d] = quantize_block(blk, "e4m3")[2][:n]
     return out
 
 

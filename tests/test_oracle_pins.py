@@ -554,3 +554,68 @@ def test_ragged_sequence_matches_per_element_rewrite(oracle, tiny, S, causal):
     want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=causal).numpy()
     got = oracle.dma_attn(q, k, v, tile=64, band=1, hi_fmt=oracle.FMT_BF16, lo_fmt=oracle.FMT_BF16, p_round=False, causal=causal)
     assert np.max(np.abs(got - want)) < 2e-6
+
+
+# ------------------------------------------------------------------ MX-format P V (blocks of 32 keys; beyond Alg. 1)
+
+def test_values_in_key_blocks(oracle, tiny):
+    """V as the MX-format P V product sees it: the pinned row quantizer applied to the transposed matrix (blocks then
+    run along keys), and the per-block brute force for a length that is not a multiple of 32 (zero-padded block)."""
+    w, q, k, v = tiny
+    vh = np.ascontiguousarray(v[0, 1])                         # [S, D], S = 256
+    seen, scales = oracle.values_as_seen_mxfp8(vh)
+    vt = np.ascontiguousarray(vh.T)                             # [D, S]: rows are columns of V
+    codes_t, scales_t = oracle.mx_quantize(vt, oracle.FMT_E4M3, False)
+    assert np.array_equal(scales, scales_t.T)
+    assert np.array_equal(seen, oracle.mx_dequantize(codes_t, scales_t, oracle.FMT_E4M3).T)
+    # columns with very different magnitudes: blocks along the head dimension would share one scale and lose them
+    big = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(vh[:70]) * (2.0 ** (3 * (np.arange(w.D) % 20)))[None, :].astype(np.float32))
+    seen, scales = oracle.values_as_seen_mxfp8(big)
+    want = brute.values_in_key_blocks(brute.bf16_bits_to_f64(big))
+    assert np.array_equal(seen, want)
+    assert scales.shape == (3, w.D) and len(np.unique(scales[0])) >= 20
+    rel = np.abs(seen - brute.bf16_bits_to_f64(big)) / np.maximum(np.abs(brute.bf16_bits_to_f64(big)), 1e-30)
+    assert np.max(rel[np.abs(brute.bf16_bits_to_f64(big)) > 0]) <= 1.0          # nothing lost to a foreign scale ...
+    assert np.median(rel) < 2.0 ** -4                                            # ... and typical elements keep 3-4 bits
+
+
+@pytest.mark.parametrize("band,causal,S", [(0, True, 256), (1, True, 256), (1, False, 128), (2, True, 200), (1, False, 100)])
+def test_mx_pv_matches_per_element_rewrite(oracle, tiny, band, causal, S):
+    w, q, k, v = tiny
+    q, k, v = (np.ascontiguousarray(a[:, :, :S]) for a in (q, k, v))
+    got = oracle.dma_attn(q, k, v, tile=w.tile, band=band, causal=causal, pv_mx=True)[0]
+    want = brute.dma_attention(q[0], k[0], v[0], tile=w.tile, band=band, causal=causal, pv_mx=True)
+    assert np.max(np.abs(got - want)) < 2e-6
+    # and it is a different computation from the 16-bit product, by about the E4M3 step
+    other = oracle.dma_attn(q, k, v, tile=w.tile, band=band, causal=causal)[0]
+    assert 1e-4 < np.max(np.abs(got - other)) < 0.5
+
+
+def test_mx_pv_closed_form_with_exact_blocks(oracle):
+    """Zero queries make every probability 1 (exact in E4M3 with any scale); values on the E4M3 grid times one power
+    of two per (32-key block, column) survive quantization exactly, so the output is the running mean of V."""
+    S, D = 128, 64
+    rng = np.random.Generator(np.random.Philox(77))
+    grid = np.array([1.0, 1.125, 1.25, 1.5, 1.75, 2.0, 3.0, 3.5, 0.5, 0.875, -1.0, -1.375, -2.5, 0.0])
+    v = rng.choice(grid, size=(S, D)) * np.exp2(rng.integers(-20, 20, size=(S // 32, 1, D)).repeat(32, axis=1).reshape(S, D))
+    vb = wl.f32_to_bf16_bits(v.astype(np.float32))[None, None]
+    assert np.array_equal(brute.bf16_bits_to_f64(vb[0, 0]), v)
+    qb = np.zeros((1, 1, S, D), dtype=np.uint16)
+    kb = wl.f32_to_bf16_bits(rng.standard_normal((1, 1, S, D)).astype(np.float32))
+    got = oracle.dma_attn(qb, kb, vb, tile=64, band=1, pv_mx=True)[0, 0]
+    want = np.cumsum(v, axis=0) / np.arange(1, S + 1)[:, None]
+    assert np.max(np.abs(got - want) / (np.abs(want) + 1e-30)) < 1e-6
+
+
+def test_mx_pv_slack_covers_binary32_scores(oracle):
+    """As for the bf16 rounding: what changes when the scores are first rounded to binary32 (E4M3 rounding flips of
+    single probabilities, and the scale byte of a block whose maximum sits on a power of two) stays within the slack."""
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=256, Hq=2, Hkv=1)
+    q, k, v = wl.generate(w)
+    rows = oracle.all_rows(w.B, w.Hq, w.S)
+    want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=128, band=1, with_slack=True, pv_mx=True)
+    assert np.array_equal(want, oracle.dma_attn_rows(q, k, v, rows, tile=128, band=1, pv_mx=True))
+    got32 = brute.dma_attention(q[0], k[0], v[0], tile=128, band=1, score_dtype=np.float32, pv_mx=True)
+    err = np.abs(got32.reshape(-1, w.D) - want)
+    assert np.max(err - slack) < 2e-5
+    assert np.median(slack.max(axis=1)) < 1e-5
