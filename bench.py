@@ -30,6 +30,7 @@ HBM_PEAK_GBS = 8000.0
 # scaled by the same counters on a copy kernel of known size); None where not measured.
 MEASURED_TRAFFIC_BYTES = {"prefill_8k": 436.8e6,      # profiles/dma_attn_fwd_prefill_8k.md, section 2
                           "gqa_32k": 2.781e9}         # profiles/dma_attn_fwd_gqa_32k.md, section 2
+RAMP_MS = 60.0                        # untimed work before the timed region (clock ramp-up), see main()
 COPY_CALIBRATION_BYTES = 1 << 29      # dma_diag_copy reads and writes this many bytes once per run
 
 
@@ -47,14 +48,15 @@ def tile_counts(w, band, sink=0, causal=True):
     return lo, hi
 
 
-def roofline(w, band, seconds, sink=0, causal=True, measured_config=True):
+def roofline(w, band, seconds, sink=0, causal=True, measured_config=True, pv_mx=False):
     """Format-weighted MFMA roofline of one launch: every executed tile costs 2*Bt^2*D flop for QK^T
     in its own format plus 2*Bt^2*D flop for PV in bf16."""
     lo, hi = tile_counts(w, band, sink, causal)
     heads = w.B * w.Hq
     f_tile = 2.0 * w.tile * w.tile * w.D
     flops = heads * (lo + hi) * 2.0 * f_tile
-    t_min = heads * (lo * f_tile / PEAK["fp4"] + hi * f_tile / PEAK["fp8"] + (lo + hi) * f_tile / PEAK["bf16"]) / 1e12
+    pv_peak = PEAK["fp8"] if pv_mx else PEAK["bf16"]
+    t_min = heads * (lo * f_tile / PEAK["fp4"] + hi * f_tile / PEAK["fp8"] + (lo + hi) * f_tile / pv_peak) / 1e12
     t_min_mx_only = heads * (lo * 2 * f_tile / PEAK["fp4"] + hi * 2 * f_tile / PEAK["fp8"]) / 1e12
     achieved = flops / seconds / 1e12
     peak = flops / t_min / 1e12
@@ -68,7 +70,7 @@ def roofline(w, band, seconds, sink=0, causal=True, measured_config=True):
         "t_min_us": round(t_min * 1e6, 2),
         "frac_mx_only_weighting": round(t_min_mx_only / seconds, 4),
         "note": "peak = executed flops / sum over tiles of flops/peak(format): QK^T at the MXFP4 or MXFP8 "
-                "peak of its tile, PV at the bf16 peak (V stays 16-bit); frac_mx_only_weighting prices PV at "
+                "peak of its tile, PV at the bf16 peak (V stays 16-bit; with --pv-mx at the MXFP8 peak); frac_mx_only_weighting prices PV at "
                 "the tile's MX peak (ceiling about 0.4 with a bf16 PV)",
     }
 
@@ -93,14 +95,15 @@ def cpu_baseline(w, q, k, v, band, budget_rows):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="prefill_8k")
     ap.add_argument("--band", type=int, default=None)
     ap.add_argument("--fp8-mfma", action="store_true", help="MXFP8 tiles on the block-scaled FP8 MFMA")
     ap.add_argument("--sink", type=int, default=0, help="leading key tiles in the high format (variant; default 0 = Alg. 1)")
     ap.add_argument("--non-causal", action="store_true", help="no causal mask (variant)")
     ap.add_argument("--per-token", action="store_true", help="per-token scale of Alg. 2 Step 2 (variant)")
+    ap.add_argument("--pv-mx", action="store_true", help="P V in MXFP8-E4M3 with blocks of 32 keys (variant beyond Alg. 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=200000)
     args = ap.parse_args()
@@ -124,9 +127,19 @@ def main():
 
     def step():
         binding.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, tile=tile, fp8_mfma=args.fp8_mfma, sink_tiles=args.sink,
-                             causal=not args.non_causal, per_token_scale=args.per_token, out=out)
+                             causal=not args.non_causal, per_token_scale=args.per_token, pv_mx=args.pv_mx, out=out)
 
-    for _ in range(args.warmup):
+    # The GPU reaches its sustained clocks only after some tens of milliseconds of work (measured here: the first ~40
+    # launches of the 8k workload run up to 45 % slower than the later ones, and 2 s of idling bring the slow start
+    # back), so at least RAMP_MS of untimed steps precede the timed region whatever --warmup says.
+    step()
+    torch.cuda.synchronize()
+    t_one = time.perf_counter()
+    step()
+    torch.cuda.synchronize()
+    t_one = time.perf_counter() - t_one
+    ramp_steps = max(0, int(RAMP_MS * 1e-3 / max(t_one, 1e-6)) - args.warmup)
+    for _ in range(ramp_steps + args.warmup):
         step()
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -179,17 +192,19 @@ def main():
         "metric": METRIC,
         "value": round(w.causal_flops * (2 if args.non_causal else 1) / (wall / args.steps) / 1e12, 2),
         "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_ramp_steps": ramp_steps + 2,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "mxfp4+mxfp8 QK^T / bf16 PV / f32 softmax+accumulate",
+        "dtype": "mxfp4+mxfp8 QK^T / " + ("mxfp8 PV" if args.pv_mx else "bf16 PV") + " / f32 softmax+accumulate",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: causal B={w.B} Hq={w.Hq} Hkv={w.Hkv} S={w.S} D={w.D} tile={w.tile} "
                                f"band={band} (hi MXFP8-E4M3, lo MXFP4-E2M1), bf16 in, f32 out, seed {w.seed}",
                    "flops_convention": "4*B*Hq*S^2*D" if args.non_causal else "2*B*Hq*S^2*D", "fp8_mfma": bool(args.fp8_mfma),
-                   "variant": {"sink_tiles": args.sink, "causal": not args.non_causal, "per_token_scale": bool(args.per_token)}},
+                   "variant": {"sink_tiles": args.sink, "causal": not args.non_causal, "per_token_scale": bool(args.per_token),
+                               "pv_mx": bool(args.pv_mx)}},
         "roofline": roofline(w, band, kernel_s, args.sink, not args.non_causal,
-                             measured_config=(band == w.band and not (args.sink or args.non_causal or args.per_token or args.fp8_mfma))),
+                             measured_config=(band == w.band and not (args.sink or args.non_causal or args.per_token or args.fp8_mfma or args.pv_mx)),
+                             pv_mx=args.pv_mx),
         "quantizer": {"kernel": "mx_quantize_kernel (dual)", "elements": qd.numel(), "us": round(quant_s * 1e6, 2),
                       "achieved_GBps": round(quant_bytes / quant_s / 1e9, 1), "peak_GBps": HBM_PEAK_GBS,
                       "frac": round(quant_bytes / quant_s / 1e9 / HBM_PEAK_GBS, 4),

@@ -108,7 +108,12 @@ typedef struct dma_attn_opts {
     int tile;             /* logical tile B_M = B_N: 128 (with D = 128) or 64 (with D = 64); 0 = 128 */
     int sink_tiles;       /* >= 0: the first sink_tiles key tiles are computed in hi_fmt for every query tile (Sec. 5.3,
                              the sink window of the diagonal/sink table); 0 = Alg. 1 as printed */
-    int pv_fmt;           /* must be DMA_FMT_BF16 (V and P stay 16-bit, as in Alg. 1) */
+    int pv_fmt;           /* DMA_FMT_BF16 (default): V and P stay 16-bit, as in Alg. 1.
+                             DMA_FMT_MXFP8_E4M3: an extension beyond the paper: P (per key tile, masked keys as 0) and V are
+                             quantized to MXFP8-E4M3 with one E8M0 scale per 32 consecutive keys (rule of Alg. 2 Steps 6-7) and
+                             multiplied on the block-scaled FP8 MFMA; the row sum still adds the unrounded probabilities.
+                             Only with lo_fmt = MXFP4_E2M1, hi_fmt = MXFP8_E4M3, fp8_mfma = 0, per_token_scale = 0; slower
+                             than the default on gfx950.  Any other value: DMA_ERR_UNSUPPORTED */
     int per_token_scale;  /* 0: Alg. 2 Step 2 is the identity (default).  1: queries and keys go through Step 2 (row divided by
                              S_q = rowmax / 2688 before quantization) and the score product is multiplied by S_q of its
                              query and of its key; ignored for DMA_FMT_BF16 operands; not with fp8_mfma = 1 */

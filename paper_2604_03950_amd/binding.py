@@ -139,9 +139,10 @@ def dma_mx_quantize_dual(x: torch.Tensor, is_query: bool, out=None):
 def dma_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, diag_band_tiles: int,
                  hi_fmt: int = FMT_MXFP8_E4M3, lo_fmt: int = FMT_MXFP4_E2M1, causal: bool = True,
                  tile: int | None = None, fp8_mfma: bool = False, sink_tiles: int = 0, per_token_scale: bool = False,
-                 out: torch.Tensor | None = None) -> torch.Tensor:
+                 pv_mx: bool = False, out: torch.Tensor | None = None) -> torch.Tensor:
     """q [B,Hq,S,D], k/v [B,Hkv,S,D] bf16 -> out [B,Hq,S,D] float32.  With tile=None, fp8_mfma=False and
-    sink_tiles=0 this is dma_attn_fwd (logical tile 128); otherwise dma_attn_fwd_ex with those options."""
+    sink_tiles=0 this is dma_attn_fwd (logical tile 128); otherwise dma_attn_fwd_ex with those options.
+    pv_mx: the P V product in MXFP8-E4M3 with blocks of 32 keys (opts.pv_fmt) instead of 16-bit."""
     B, Hq, S, D = q.shape
     Hkv = k.shape[1]
     if k.shape != (B, Hkv, S, D) or v.shape != k.shape:
@@ -151,10 +152,10 @@ def dma_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, diag_band
     args = [_dev(q, torch.bfloat16, "q"), _dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v"),
             _dev(out, torch.float32, "out"), B, Hq, Hkv, S, D, int(bool(causal)), int(diag_band_tiles),
             int(hi_fmt), int(lo_fmt)]
-    if tile is None and not fp8_mfma and not sink_tiles and not per_token_scale:
+    if tile is None and not fp8_mfma and not sink_tiles and not per_token_scale and not pv_mx:
         rc = load().dma_attn_fwd(*args, _stream())
     else:
-        opts = AttnOpts(tile=int(tile or 0), sink_tiles=int(sink_tiles), pv_fmt=FMT_BF16, per_token_scale=int(bool(per_token_scale)),
+        opts = AttnOpts(tile=int(tile or 0), sink_tiles=int(sink_tiles), pv_fmt=FMT_MXFP8_E4M3 if pv_mx else FMT_BF16, per_token_scale=int(bool(per_token_scale)),
                         fp8_mfma=int(bool(fp8_mfma)))
         rc = load().dma_attn_fwd_ex(*args, ctypes.byref(opts), _stream())
     if rc:

@@ -80,6 +80,7 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
     int fp8_mfma = 0;
     int sink = 0;
     int per_token = 0;
+    int pv_mx = 0;
     if (opts) {
         if (opts->fp8_mfma != 0 && opts->fp8_mfma != 1) return DMA_ERR_INVALID_ARG;
         fp8_mfma = opts->fp8_mfma;
@@ -89,7 +90,8 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
         sink = opts->sink_tiles;
         if (opts->per_token_scale != 0 && opts->per_token_scale != 1) return DMA_ERR_INVALID_ARG;
         per_token = opts->per_token_scale;
-        if (opts->pv_fmt != DMA_FMT_BF16) return DMA_ERR_UNSUPPORTED;
+        if (opts->pv_fmt != DMA_FMT_BF16 && opts->pv_fmt != DMA_FMT_MXFP8_E4M3) return DMA_ERR_UNSUPPORTED;
+        pv_mx = opts->pv_fmt == DMA_FMT_MXFP8_E4M3;
     }
     if (tile != 64 && tile != 128) return DMA_ERR_UNSUPPORTED;
     if ((int64_t)S * D * 4 >= ((int64_t)1 << 32)) return DMA_ERR_UNSUPPORTED;      // one head of the output must fit a 4 GiB buffer resource
@@ -103,6 +105,9 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
     a.sink = sink > n_tiles ? n_tiles : sink;
     a.causal = causal != 0;
     a.per_token = per_token;
+    a.pv_mx = pv_mx;
+    // the MX-format P V exists for the default pair (MXFP4 / MXFP8-E4M3 decoded exactly), without the per-token scale
+    if (pv_mx && (per_token || fp8_mfma || lo_fmt != DMA_FMT_MXFP4_E2M1 || hi_fmt != DMA_FMT_MXFP8_E4M3)) return DMA_ERR_UNSUPPORTED;
     // public element format -> product path of the kernels: 3 / 4 = MXFP8 (E4M3 / E5M2) decoded exactly to bf16 and
     // multiplied on the bf16 MFMA; E5M2 has no other path
     if (fp8_mfma && (hi_fmt == DMA_FMT_MXFP8_E5M2 || lo_fmt == DMA_FMT_MXFP8_E5M2)) return DMA_ERR_UNSUPPORTED;

@@ -54,6 +54,15 @@ struct Cfg {
     static constexpr int VS = 2 * D;             // bf16 values: dense rows, 16-byte chunks XOR-swizzled (see v_swizzle)
     static constexpr int KSC = BT * CPR;         // scale bytes of one tile: one per 16-byte chunk (each block's 4 chunks repeat its code)
     static constexpr int VBYTES = BT * VS;
+    // MX-format P V: V as E4M3 codes, one byte per element in padded rows, then one scale byte per (32-key block,
+    // column).  In its staging each wave owns the keys of one 32-key block (and, with two logical tiles per workgroup,
+    // half of the columns), so that the block maxima along the key axis never leave the wave.
+    static constexpr int VS8 = D + 16;
+    static constexpr int V8CODES = BT * VS8;
+    static constexpr int V8BYTES = V8CODES + NKB * D;
+    static constexpr int VCW = CPR / TPW;        // 16-byte chunks (of 8 columns) per row of lanes
+    static constexpr int VRG = 64 / VCW;         // keys per chunk round of a wave
+    static_assert(NW == NKB * TPW && VRG * CPT == 32, "one 32-key block per wave (and column half)");
     // V rows sit densely in LDS; so that the transpose reads of four consecutive keys do not hit the same banks,
     // chunk c of key k is stored at chunk c ^ (4 * v_swizzle(k)).
     static constexpr int v_swizzle(int key) { return D == 128 ? (key & 3) : ((key >> 1) & 1); }
@@ -188,6 +197,7 @@ DMA_DEV T lds_read(unsigned addr) { return *(const DMA_LDS T*)(uintptr_t)addr; }
 template <typename T>
 DMA_DEV void lds_write(unsigned addr, T v) { *(DMA_LDS T*)(uintptr_t)addr = v; }
 DMA_DEV v4s lds_read_tr16(unsigned addr) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16((DMA_LDS v4s*)(uintptr_t)addr); }
+DMA_DEV v2i lds_read_tr8(unsigned addr) { return __builtin_amdgcn_ds_read_tr8_b64_v2i32((DMA_LDS v2i*)(uintptr_t)addr); }
 
 // ---------------------------------------------------------------------------------------------
 // Staging of one key/value tile
@@ -225,6 +235,25 @@ DMA_DEV unsigned value_v_lane(int lane, int db)  // the lane's address for d-blo
     const int g = lane >> 5, l16 = lane & 15, q16 = lane >> 4;
     const unsigned row_off = (4 * g + (l16 >> 2)) * C::VS + 8 * (l16 & 1);
     return row_off + 16 * ((4 * db + 2 * (q16 & 1) + ((l16 & 3) >> 1)) ^ (4 * C::v_swizzle(l16 >> 2)));
+}
+// MX-format P V.  Thread -> (32-key block kb, key in the block, 16-byte chunk of the row) of its round-0 chunk; round r
+// is VRG keys further on.
+template <typename C>
+DMA_DEV void vmx_thread(int tid, int& kb, int& key, int& chunk)
+{
+    const int w = tid >> 6, ln = tid & 63;
+    kb = w % C::NKB;
+    key = ln / C::VCW;
+    chunk = C::VCW * (w / C::NKB) + ln % C::VCW;
+}
+// Transpose read of the E4M3 V tile: lanes 2 r and 2 r + 1 of a 16-lane group point at the halves of 16 columns of key
+// row f(r) = r (r < 4) or r + 4 (r >= 4), plus 4 for the upper half-wave: read 0 then delivers, byte by byte, the keys
+// 8 v + 4 g + b of VGPRs v = 0, 1 of the operand; the other reads are 16, 32 and 48 keys further on.
+template <typename C>
+DMA_DEV unsigned value_vmx_lane(int lane)
+{
+    const int g = lane >> 5, l16 = lane & 15, q16 = (lane >> 4) & 1, r = l16 >> 1;
+    return (4 * g + (r < 4 ? r : r + 4)) * C::VS8 + 16 * q16 + 8 * (l16 & 1);
 }
 template <typename C, int LO>
 struct LaneOffsets {
@@ -266,6 +295,33 @@ DMA_DEV void load_tile(v4i (&reg)[C::CPT], const uint16_t* __restrict__ mat, int
 #pragma unroll
         for (int r = 0; r < C::CPT; ++r) {
             const int row = row0 + r * KPR;
+            const int64_t left = (int64_t)(S - row) * (C::D * 2);
+            const rsrc_t rs = make_rsrc(mat + (int64_t)row * C::D, left > 0 ? (uint32_t)left : 0u);
+            reg[r] = buffer_load16(rs, lane_off);
+        }
+    }
+}
+
+// V tile in the thread mapping of the MX-format P V (vmx_thread).
+template <typename C, bool BOUNDED>
+DMA_DEV void load_tile_vmx(v4i (&reg)[C::CPT], const uint16_t* __restrict__ mat, int row0, int S, int tid)
+{
+    int kb, key, chunk;
+    vmx_thread<C>(fresh(tid), kb, key, chunk);
+    const unsigned lane_off = (unsigned)((32 * kb + key) * C::CPR + chunk) * 16u;     // < BT * D * 2: inside the tile
+    if constexpr (!BOUNDED) {
+        typedef const __attribute__((address_space(1))) v4i* global_v4i;
+#pragma unroll
+        for (int r = 0; r < C::CPT; ++r) {
+            const uint64_t t64 = (uint64_t)(mat + (int64_t)(row0 + r * C::VRG) * C::D);
+            uint32_t lo = (uint32_t)t64, hi = (uint32_t)(t64 >> 32);
+            asm volatile("" : "+s"(lo), "+s"(hi));
+            reg[r] = *(global_v4i)((((uint64_t)hi << 32) | (uint64_t)lo) + (uint64_t)lane_off);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < C::CPT; ++r) {
+            const int row = row0 + r * C::VRG;
             const int64_t left = (int64_t)(S - row) * (C::D * 2);
             const rsrc_t rs = make_rsrc(mat + (int64_t)row * C::D, left > 0 ? (uint32_t)left : 0u);
             reg[r] = buffer_load16(rs, lane_off);
@@ -332,6 +388,57 @@ DMA_DEV void stage_v(const v4i (&reg)[C::CPT], unsigned vdst, unsigned v_lane)
     for (int r = 0; r < C::CPT; ++r) lds_write<v4i>(va + r * KPR * C::VS, reg[r]);
 }
 
+// V tile (thread mapping of vmx_thread) from registers into LDS as MXFP8-E4M3 with blocks of 32 keys per column: the
+// wave's 32 keys of a column are spread over its chunk rounds and over the lanes that share lane % VCW.
+template <typename C>
+DMA_DEV void stage_v_mx(const v4i (&reg)[C::CPT], unsigned vdst, int tid)
+{
+    int kb, key, chunk;
+    vmx_thread<C>(fresh(tid), kb, key, chunk);
+    unsigned am[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        unsigned a = 0u;
+#pragma unroll
+        for (int r = 0; r < C::CPT; ++r) a = pk_max_u16(a, (unsigned)reg[r][t] & 0x7fff7fffu);
+        am[t] = strided_lane_max_u16<C::VCW>(a);
+    }
+    // column t of the chunk: scale byte max(biased exponent - 8, 0) (Alg. 2 Steps 6-7 with e_max = 8) and 2^(127 - byte)
+    int code[8];
+    float inv[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const int bits = (t & 1) ? (int)(am[t >> 1] >> 16) : (int)(am[t >> 1] & 0xffffu);
+        code[t] = max((bits >> 7) - 8, 0);
+        inv[t] = __int_as_float((254 - code[t]) << 23);
+    }
+    const unsigned va = pin(vdst + (32 * kb + key) * C::VS8 + chunk * 8);
+#pragma unroll
+    for (int r = 0; r < C::CPT; ++r) {
+        float x[8];
+        unpack8<false>(reg[r], 1.f, x);
+        lds_write<v2i>(va + r * C::VRG * C::VS8, encode8_e4m3_each(x, inv));
+    }
+    if (key == 0) {
+        v2i sc;
+        sc[0] = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+        sc[1] = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
+        lds_write<v2i>(vdst + C::V8CODES + kb * C::D + chunk * 8, sc);
+    }
+}
+
+// The P^T operand of the value part for one wave and one key tile: bf16 pairs (16 keys per group), or, for the
+// MX-format P V, E4M3 codes of 64 keys per group with the lane's scale byte.
+template <typename C, bool PVMX>
+struct PTile {
+    v8bf b[2 * C::NKB];
+};
+template <typename C>
+struct PTile<C, true> {
+    v8i q[C::NKB / 2];
+    int sc[C::NKB / 2];
+};
+
 // ---------------------------------------------------------------------------------------------
 // One key tile for one wave: scores, mask, online softmax, P V
 // ---------------------------------------------------------------------------------------------
@@ -354,10 +461,14 @@ DMA_DEV v8i widen(const v4i& lo, const v4i& hi) { return v8i{lo[0], lo[1], lo[2]
 // after_mfma() runs between the matrix part and the softmax part (the caller's global loads go there).
 // PT (per-token scale, Alg. 2 Step 2): the product of the codes is multiplied by S_q of the query row (q_sq) and S_q of
 // the key (one float per key at ktssrc) before the maximum is taken.
-template <typename C, int FMT, bool MAYBE_DIAG, bool PT, int QR, typename F>
+// PVMX (MX-format P V): the probabilities leave as MXFP8-E4M3 blocks of 32 keys.  The lane holds 16 keys of every
+// 32-key block of its query (the other half-wave holds the other 16): keys 8 v + 4 g + b of block kb are byte b of
+// VGPR v (block 2c) or 4 + v (block 2c + 1) of the operand of key group c, which is the order the V^T operand is read
+// in (value_vmx_lane).  The block's scale comes from its largest probability 2^max(S - m): floor of that exponent.
+template <typename C, int FMT, bool MAYBE_DIAG, bool PT, bool PVMX, int QR, typename F>
 DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned kssrc, unsigned k_lane, unsigned s_lane,
                         unsigned ktssrc, float q_sq, bool diagonal, int key_limit, int qrow_in_tile, int lane, float c,
-                        float& m, float& mfloor, float& l, v16f (&o)[C::NDB], v8bf (&pb)[2 * C::NKB], F&& after_mfma)
+                        float& m, float& mfloor, float& l, v16f (&o)[C::NDB], PTile<C, PVMX>& pt, F&& after_mfma)
 {
     lane = fresh(lane);
     const int j = lane & 31, g = lane >> 5;
@@ -480,11 +591,24 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
     // ---- online softmax in base 2.  s holds S - m.  delta = how far the row maximum moves (>= 0; on the first tile
     // of a row, where m is only the arbitrary start value 0, any sign: mfloor is -inf there and 0 afterwards).
     float mx = -INFINITY;
+    float bmax[C::NKB];                                   // MX-format P V: maxima per 32-key block
+    if constexpr (PVMX) {
 #pragma unroll
-    for (int kb = 0; kb < C::NKB; ++kb)
+        for (int kb = 0; kb < C::NKB; ++kb) {
+            bmax[kb] = -INFINITY;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-    const float delta = fmaxf(cross_half_max(mx), mfloor);
+            for (int r = 0; r < 16; ++r) bmax[kb] = fmaxf(bmax[kb], s[kb][r]);
+            bmax[kb] = cross_half_max(bmax[kb]);
+            mx = fmaxf(mx, bmax[kb]);
+        }
+    } else {
+#pragma unroll
+        for (int kb = 0; kb < C::NKB; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
+        mx = cross_half_max(mx);
+    }
+    const float delta = fmaxf(mx, mfloor);
     const float mnew = m + delta;
     const float alpha = __builtin_amdgcn_exp2f(fminf(m - mnew, 0.f));     // first tile: l and O are 0, any finite factor does
     m = mnew;
@@ -496,19 +620,50 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
         for (int kb = 0; kb < C::NKB; ++kb) s[kb] -= delta;
     }
 
-    // ---- P = 2^(S - m): row sums from the binary32 values, bf16 (round to nearest even) for the P V product
+    // ---- P = 2^(S - m): row sums from the binary32 values; for the P V product bf16 (round to nearest even), or ...
     float psum[2] = {0.f, 0.f};
+    if constexpr (!PVMX) {
 #pragma unroll
-    for (int grp = 0; grp < 2 * C::NKB; ++grp) {
+        for (int grp = 0; grp < 2 * C::NKB; ++grp) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const float p0 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t]);
-            const float p1 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t + 1]);
-            psum[0] += p0;
-            psum[1] += p1;
-            const v2bf h2 = __builtin_convertvector(v2f{p0, p1}, v2bf);
-            pb[grp][2 * t] = h2[0];
-            pb[grp][2 * t + 1] = h2[1];
+            for (int t = 0; t < 4; ++t) {
+                const float p0 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t]);
+                const float p1 = __builtin_amdgcn_exp2f(s[grp >> 1][8 * (grp & 1) + 2 * t + 1]);
+                psum[0] += p0;
+                psum[1] += p1;
+                const v2bf h2 = __builtin_convertvector(v2f{p0, p1}, v2bf);
+                pt.b[grp][2 * t] = h2[0];
+                pt.b[grp][2 * t + 1] = h2[1];
+            }
+        }
+    } else {
+        // ... MXFP8-E4M3 blocks of 32 keys.  The block maximum of S - m after the rescale is bmax - delta (rounding is
+        // monotone); the largest probability of the block is 2^that, so its biased exponent is 127 + floor(that) and the
+        // scale byte max(127 + floor - 8, 0).  A block with every key masked has maximum -inf and scale byte 0.
+#pragma unroll
+        for (int cgrp = 0; cgrp < C::NKB / 2; ++cgrp) {
+            int code[2];
+            int packed[8];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int kb = 2 * cgrp + u;
+                const float top = fmaxf(bmax[kb] - delta, -256.f);
+                code[u] = max((int)__builtin_floorf(top) + 119, 0);
+#pragma unroll
+                for (int h8 = 0; h8 < 2; ++h8) {
+                    float p[8];
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        p[t] = __builtin_amdgcn_exp2f(s[kb][8 * h8 + t]);
+                        psum[t & 1] += p[t];
+                    }
+                    const v2i e = encode8_e4m3_prob(p, code[u]);
+                    packed[4 * u + 2 * h8] = e[0];
+                    packed[4 * u + 2 * h8 + 1] = e[1];
+                }
+            }
+            pt.q[cgrp] = v8i{packed[0], packed[1], packed[2], packed[3], packed[4], packed[5], packed[6], packed[7]};
+            pt.sc[cgrp] = g ? code[1] : code[0];
         }
     }
     l = l * alpha + (psum[0] + psum[1]);
@@ -517,8 +672,9 @@ DMA_DEV void score_part(const v4i (&qr)[QR], int qscale, unsigned ksrc, unsigned
 // Second half (all matrix work): O^T += V^T . P^T in groups of 16 keys; the V^T operands of the next group are in
 // flight from LDS while the MFMAs of the current group run.  vsrc: LDS address of the V tile.
 template <typename C>
-DMA_DEV void value_part(unsigned vsrc, const unsigned (&v_lane)[C::NDB], v16f (&o)[C::NDB], const v8bf (&pb)[2 * C::NKB])
+DMA_DEV void value_part(unsigned vsrc, const unsigned (&v_lane)[C::NDB], v16f (&o)[C::NDB], const PTile<C, false>& pt)
 {
+    const v8bf (&pb)[2 * C::NKB] = pt.b;
     // va[db]: the lane's address for d-block db in the tile's first patch (value_v_lane); other patches are constant offsets
     unsigned va[C::NDB];
 #pragma unroll
@@ -547,6 +703,36 @@ DMA_DEV void value_part(unsigned vsrc, const unsigned (&v_lane)[C::NDB], v16f (&
     }
 }
 
+// The same for the MX-format P V: O^T += V^T . P^T on the block-scaled FP8 MFMA in groups of 64 keys.  vsrc: LDS
+// address of the E4M3 V tile (codes, then the scale bytes [32-key block][column]).
+template <typename C>
+DMA_DEV void value_part(unsigned vsrc, int lane, v16f (&o)[C::NDB], const PTile<C, true>& pt)
+{
+    lane = fresh(lane);
+    const unsigned va = pin(vsrc + value_vmx_lane<C>(lane));
+    const unsigned sa = pin(vsrc + C::V8CODES + (lane >> 5) * C::D + (lane & 31));
+#pragma unroll
+    for (int cgrp = 0; cgrp < C::NKB / 2; ++cgrp) {
+        v8i a[C::NDB];
+        int vsc[C::NDB];
+#pragma unroll
+        for (int db = 0; db < C::NDB; ++db) {
+            vsc[db] = (int)lds_read<uint8_t>(sa + 2 * cgrp * C::D + 32 * db);
+            int w[8];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const v2i t = lds_read_tr8(va + (64 * cgrp + 16 * r) * C::VS8 + 32 * db);
+                w[2 * r] = t[0];
+                w[2 * r + 1] = t[1];
+            }
+            a[db] = v8i{w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]};
+        }
+#pragma unroll
+        for (int db = 0; db < C::NDB; ++db)
+            o[db] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[db], pt.q[cgrp], o[db], 0, 0, 0, vsc[db], 0, pt.sc[cgrp]);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // The kernel
 // ---------------------------------------------------------------------------------------------
@@ -571,7 +757,7 @@ DMA_DEV void key_token_scales(const v4i (&reg)[C::CPT], float (&inv_sk)[C::CPT],
 
 // K and V of one key tile from registers into LDS: K in the low format if some wave computes the tile in Phase 1,
 // in the high format if some wave computes it in Phase 2.
-template <typename C, int LO, int HI, bool PT>
+template <typename C, int LO, int HI, bool PT, bool PVMX>
 DMA_DEV void stage_tile(const v4i (&kreg)[C::CPT], const v4i (&vreg)[C::CPT], bool any_lo, bool any_hi,
                         unsigned klo, unsigned kslo, unsigned khi, unsigned kshi, unsigned kts, unsigned vdst,
                         const LaneOffsets<C, LO>& lo, int tid)
@@ -584,13 +770,15 @@ DMA_DEV void stage_tile(const v4i (&kreg)[C::CPT], const v4i (&vreg)[C::CPT], bo
     if constexpr (LO != HI) {
         if (any_hi) stage_k<C, HI, PT>(kreg, khi, kshi, stage_k_lane<C, HI>(fresh(tid)), lo.stage_s, inv_sk);
     }
-    stage_v<C>(vreg, vdst, lo.stage_v);
+    if constexpr (PVMX) stage_v_mx<C>(vreg, vdst, tid);
+    else stage_v<C>(vreg, vdst, lo.stage_v);
 }
 
 // GENERAL = false: Alg. 1 as printed (causal, no sink window; sink_arg / causal_arg are ignored): main tiles then band
 // tiles, two loops in a row.  GENERAL = true: sink window and / or no causal mask: runs of main and band tiles alternate.
 // PT: per-token scale of Alg. 2 Step 2 on queries and keys (built with GENERAL only).
-template <int D, int BT, int TPW, int LO, int HI, bool GENERAL, bool PT>
+// PVMX: the P V product in MXFP8-E4M3 with blocks of 32 keys (an extension beyond Alg. 1, which keeps P and V in 16 bit).
+template <int D, int BT, int TPW, int LO, int HI, bool GENERAL, bool PT, bool PVMX>
 __global__ void __launch_bounds__((BT / 32) * TPW * 64, 2)
 dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     const uint16_t* __restrict__ v, float* __restrict__ out,
@@ -607,7 +795,8 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     // LDS map (bytes): V, the low-format K and the high-format K (each + scale bytes) double-buffered for the pipelined
     // tile loops.  The output transpose of the epilogue reuses the same memory.
     constexpr int OFF_V = 0;
-    constexpr int OFF_KLO = OFF_V + 2 * C::VBYTES;
+    constexpr int VB = PVMX ? C::V8BYTES : C::VBYTES;
+    constexpr int OFF_KLO = OFF_V + 2 * VB;
     constexpr int OFF_KSLO = OFF_KLO + 2 * KLO;
     constexpr int OFF_KHI = OFF_KSLO + 2 * C::KSC;
     constexpr bool HI_SCALES = TWO && !uses_bf16_mfma(HI);   // the decoded-to-bf16 high format carries no scale bytes
@@ -621,12 +810,20 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     static_assert(D % EPI_COLS == 0, "epilogue works on 64-column slabs");
     __shared__ __attribute__((aligned(16))) uint8_t lds[LDS_TOTAL];
     const unsigned lds0 = (unsigned)(uintptr_t)(DMA_LDS uint8_t*)lds;
-    auto v_at = [&](int buf) { return lds0 + OFF_V + buf * C::VBYTES; };
+    auto v_at = [&](int buf) { return lds0 + OFF_V + buf * VB; };
     auto klo_at = [&](int buf) { return lds0 + OFF_KLO + buf * KLO; };
     auto kslo_at = [&](int buf) { return lds0 + OFF_KSLO + buf * C::KSC; };
     auto khi_at = [&](int buf) { return lds0 + OFF_KHI + buf * KHI; };
     auto kshi_at = [&](int buf) { return lds0 + OFF_KSHI + (HI_SCALES ? buf * C::KSC : 0); };
     auto kts_at = [&](int buf) { return lds0 + OFF_KTS + (PT ? buf * BT * 4 : 0); };
+    auto load_v = [&](v4i (&reg)[C::CPT], const uint16_t* mat, int row0, int S_, int tid_) __attribute__((always_inline)) {
+        if constexpr (PVMX) load_tile_vmx<C, GENERAL>(reg, mat, row0, S_, tid_);
+        else load_tile<C, GENERAL>(reg, mat, row0, S_, tid_);
+    };
+    auto pv = [&](unsigned vsrc, const LaneOffsets<C, LO>& lo_, int lane_, v16f (&o_)[C::NDB], const PTile<C, PVMX>& p_) __attribute__((always_inline)) {
+        if constexpr (PVMX) value_part<C>(vsrc, lane_, o_, p_);
+        else value_part<C>(vsrc, lo_.value_v, o_, p_);
+    };
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -726,7 +923,7 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         // ---- prologue: key tile 0 and the query operands (all loads in flight together), tile 0 into LDS buffer 0.
         // Invariant from here on: the K/V registers hold the tile after the one staged last, if there is one.
         v4i kreg[C::CPT], vreg[C::CPT];
-        v8bf pb[2 * C::NKB];
+        PTile<C, PVMX> pb;
         v4i qr_lo[QRLO], qr_hi[QRHI];
         int qs_lo = 0, qs_hi = 0;
         float q_sq = 1.f;                                // S_q of the lane's query row (per-token scale)
@@ -734,7 +931,7 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             v4i qraw[C::NKK];
             load_q_raw<C>(qraw, make_rsrc(qhead, (uint32_t)S * (D * 2)), qrow, fresh(lane) & 31, fresh(lane) >> 5);
             load_tile<C, GENERAL>(kreg, khead, 0, S, tid);
-            load_tile<C, GENERAL>(vreg, vhead, 0, S, tid);
+            load_v(vreg, vhead, 0, S, tid);
             __builtin_amdgcn_sched_barrier(0);           // every request is out before the first result is needed
             float inv_sq = 1.f;
             if constexpr (PT) token_scale(q_row_amax<C>(qraw, c), q_sq, inv_sq);
@@ -746,13 +943,13 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         auto stage_next = [&](int jt, int buf) __attribute__((always_inline)) {         // tile jt from the K/V registers into LDS buffer buf
             bool any_lo, any_hi;
             needs(jt, any_lo, any_hi);
-            stage_tile<C, LO, HI, PT>(kreg, vreg, any_lo, any_hi, klo_at(buf), kslo_at(buf), khi_at(buf), kshi_at(buf), kts_at(buf),
+            stage_tile<C, LO, HI, PT, PVMX>(kreg, vreg, any_lo, any_hi, klo_at(buf), kslo_at(buf), khi_at(buf), kshi_at(buf), kts_at(buf),
                                       v_at(buf), lofs, tid);
         };
         stage_next(0, 0);
         if (1 < nt) {
             load_tile<C, GENERAL>(kreg, khead, BT, S, tid);
-            load_tile<C, GENERAL>(vreg, vhead, BT, S, tid);
+            load_v(vreg, vhead, BT, S, tid);
         }
         __syncthreads();
 
@@ -767,10 +964,10 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         auto main_step = [&](int jt) __attribute__((always_inline)) {
             const int buf = jt & 1;
             if (jt + 1 < nt) stage_next(jt + 1, buf ^ 1);
-            score_part<C, LO, false, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), lofs.score_k, lofs.score_s, kts_at(buf), q_sq, false, BT, qrow_in_tile, lane, c, m, mfloor, l, o, pb,
+            score_part<C, LO, false, PT, PVMX>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), lofs.score_k, lofs.score_s, kts_at(buf), q_sq, false, BT, qrow_in_tile, lane, c, m, mfloor, l, o, pb,
                                      [&]() __attribute__((always_inline)) { if (jt + 2 < nt) load_tile<C, GENERAL>(kreg, khead, (jt + 2) * BT, S, tid); });
-            if (jt + 2 < nt) load_tile<C, GENERAL>(vreg, vhead, (jt + 2) * BT, S, tid);
-            value_part<C>(v_at(buf), lofs.value_v, o, pb);
+            if (jt + 2 < nt) load_v(vreg, vhead, (jt + 2) * BT, S, tid);
+            pv(v_at(buf), lofs, lane, o, pb);
             __syncthreads();
         };
         auto band_step = [&](int jt) __attribute__((always_inline)) {
@@ -782,16 +979,16 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             if (jt + 1 < nt) stage_next(jt + 1, buf ^ 1);
             if (active) {
                 if (!tile_hi(it, jt)) {
-                    score_part<C, LO, true, PT>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), lofs.score_k, lofs.score_s, kts_at(buf), q_sq, diagonal, key_limit, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
+                    score_part<C, LO, true, PT, PVMX>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), lofs.score_k, lofs.score_s, kts_at(buf), q_sq, diagonal, key_limit, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
                 } else if constexpr (TWO) {
-                    score_part<C, HI, true, PT>(qr_hi, qs_hi, khi_at(buf), kshi_at(buf), score_k_lane<C, HI>(fresh(lane)), lofs.score_s, kts_at(buf), q_sq, diagonal, key_limit, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
+                    score_part<C, HI, true, PT, PVMX>(qr_hi, qs_hi, khi_at(buf), kshi_at(buf), score_k_lane<C, HI>(fresh(lane)), lofs.score_s, kts_at(buf), q_sq, diagonal, key_limit, qrow_in_tile, lane, c, m, mfloor, l, o, pb, [] {});
                 }
             }
             if (jt + 2 < nt) {
                 load_tile<C, GENERAL>(kreg, khead, (jt + 2) * BT, S, tid);
-                load_tile<C, GENERAL>(vreg, vhead, (jt + 2) * BT, S, tid);
+                load_v(vreg, vhead, (jt + 2) * BT, S, tid);
             }
-            if (active) value_part<C>(v_at(buf), lofs.value_v, o, pb);
+            if (active) pv(v_at(buf), lofs, lane, o, pb);
             __syncthreads();
         };
         if constexpr (!GENERAL) {
@@ -860,7 +1057,7 @@ inline int compute_units()
     return cached[dev];
 }
 
-template <int D, int BT, int TPW, int LO, int HI, bool GENERAL, bool PT>
+template <int D, int BT, int TPW, int LO, int HI, bool GENERAL, bool PT, bool PVMX = false>
 static int launch_variant(const AttnArgs& a, hipStream_t stream)
 {
     using C = Cfg<D, BT, TPW>;
@@ -874,7 +1071,7 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
     static int resident = 0;              // per instance; the same on every device of one kind
     if (resident == 0) {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT>, C::T, 0) != hipSuccess || n <= 0)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT, PVMX>, C::T, 0) != hipSuccess || n <= 0)
             return DMA_ERR_HIP_;
         resident = n;
     }
@@ -889,7 +1086,7 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
     int head_block = heads_x;
     for (int hb = 1; hb < heads_x; ++hb)
         if (heads_x % hb == 0 && ((int64_t)hb * NG) % (2 * workers) == 0) { head_block = hb; break; }
-    hipLaunchKernelGGL((dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT>), dim3((unsigned)blocks), dim3(C::T), 0, stream,
+    hipLaunchKernelGGL((dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT, PVMX>), dim3((unsigned)blocks), dim3(C::T), 0, stream,
                        (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, a.out, a.B, a.Hq, a.Hkv,
                        a.S, a.band, a.sink, a.causal, c, head_block);
     return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
@@ -901,6 +1098,16 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
 template <int D, int BT, int TPW, int LO, int HI>
 static int launch_instance(const AttnArgs& a, hipStream_t stream)
 {
+    if (a.pv_mx) {
+        // the MX-format P V is built for the default pair only, without the per-token scale
+        if constexpr (LO == FMT_E2M1 && HI == FMT_E4M3_X) {
+            if (a.per_token) return DMA_ERR_UNSUPPORTED_;
+            if (a.causal && a.sink == 0 && a.S % BT == 0) return launch_variant<D, BT, TPW, LO, HI, false, false, true>(a, stream);
+            return launch_variant<D, BT, TPW, LO, HI, true, false, true>(a, stream);
+        } else {
+            return DMA_ERR_UNSUPPORTED_;
+        }
+    }
     if constexpr (LO != FMT_BF16) {
         if (a.per_token) return launch_variant<D, BT, TPW, LO, HI, true, true>(a, stream);
     }

@@ -11,6 +11,8 @@
 //   32 x 32 accumulator: lane l holds column l % 32; VGPR r holds row 8 * (r / 4) + 4 * (l / 32) + r % 4.
 //   ds_read_b64_tr_b16: inside each group of 16 lanes, lane i receives element i % 4 ... precisely,
 //          out[i][e] = chunk[4 * e + i / 4][i % 4], where chunk[j] is the 8-byte row lane j points to.
+//   ds_read_b64_tr_b8: inside each group of 16 lanes, lanes 2 r and 2 r + 1 point at the two 8-byte halves of a
+//          16-byte row r (r < 8); lane i receives column i of that 8 x 16 byte patch, byte r from row r.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -282,6 +284,69 @@ DMA_DEV float cross_half_sum(float x)
 {
     v2u r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// MX-format P V: helpers for blocks that run along the key axis
+// ---------------------------------------------------------------------------------------------
+typedef unsigned short v2us __attribute__((ext_vector_type(2)));
+
+// Element-wise maximum of two packed 16-bit magnitudes (two per dword).
+DMA_DEV unsigned pk_max_u16(unsigned a, unsigned b)
+{
+    return __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(v2us, a), __builtin_bit_cast(v2us, b)));
+}
+
+// Maximum over the lanes that share lane % CW (CW = 4, 8 or 16), of two packed 16-bit magnitudes: rotations inside
+// the 16-lane rows, then the rows pairwise (v_permlane16_swap), then the two half-waves (v_permlane32_swap).
+// (One dword at a time, in a scalar variable of its own: see encode8_e2m1_bf16 for why no vector element is named in
+// a builtin here.)
+template <int CW>
+DMA_DEV unsigned strided_lane_max_u16(unsigned a)
+{
+    static_assert(CW == 4 || CW == 8 || CW == 16, "4, 8 or 16 columns per row of lanes");
+    asm volatile("" : "+v"(a));
+    if constexpr (CW <= 4) a = pk_max_u16(a, (unsigned)__builtin_amdgcn_mov_dpp((int)a, 0x124, 0xF, 0xF, true));   // row_ror:4
+    if constexpr (CW <= 8) a = pk_max_u16(a, (unsigned)__builtin_amdgcn_mov_dpp((int)a, 0x128, 0xF, 0xF, true));   // row_ror:8
+    v2u r = __builtin_amdgcn_permlane16_swap(a, a, false, false);
+    a = pk_max_u16(r[0], r[1]);
+    r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+    return pk_max_u16(r[0], r[1]);
+}
+
+// Eight binary32 values, element t divided by its own power of two 2^(code[t] - 127) (exactly: a multiplication by
+// inv[t] = 2^(127 - code[t])), clamped to +-448 and rounded to E4M3 (nearest even): two dwords of codes.
+DMA_DEV v2i encode8_e4m3_each(const float (&x)[8], const float (&inv)[8])
+{
+    const float one = cvt_scale_operand(127);
+    float y[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) y[t] = __builtin_amdgcn_fmed3f(__fmul_rn(x[t], inv[t]), -448.f, 448.f);
+    v2s a = {0, 0}, b = {0, 0};
+    a = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(a, y[0], y[1], one, false);
+    a = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(a, y[2], y[3], one, true);
+    b = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(b, y[4], y[5], one, false);
+    b = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(b, y[6], y[7], one, true);
+    v2i r;
+    r[0] = __builtin_bit_cast(int, a);
+    r[1] = __builtin_bit_cast(int, b);
+    return r;
+}
+
+// Eight probabilities (0 <= p <= 1) with one shared scale byte -> E4M3 codes, clamped at 448 * 2^(code - 127).
+DMA_DEV v2i encode8_e4m3_prob(const float (&x)[8], int code)
+{
+    const float sc = cvt_scale_operand(code);
+    const float lim = __int_as_float(((code + 8) << 23) | 0x00600000);   // 1.75 * 2^(code + 8 - 127)
+    v2s a = {0, 0}, b = {0, 0};
+    a = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(a, fminf(x[0], lim), fminf(x[1], lim), sc, false);
+    a = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(a, fminf(x[2], lim), fminf(x[3], lim), sc, true);
+    b = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(b, fminf(x[4], lim), fminf(x[5], lim), sc, false);
+    b = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(b, fminf(x[6], lim), fminf(x[7], lim), sc, true);
+    v2i r;
+    r[0] = __builtin_bit_cast(int, a);
+    r[1] = __builtin_bit_cast(int, b);
+    return r;
 }
 
 }  // namespace dma

@@ -30,6 +30,7 @@ struct AttnArgs {
     int sink;        // leading key tiles in the high format
     int causal;
     int per_token;   // Alg. 2 Step 2 on queries and keys
+    int pv_mx;       // P V in MXFP8-E4M3 with blocks of 32 keys instead of 16-bit
     int hi_fmt, lo_fmt;
 };
 

@@ -68,7 +68,9 @@ def test_argument_checks_return_before_any_launch(lib):
     assert attn_ex(sink_tiles=-1) == -1
     assert attn_ex(per_token_scale=2) == -1
     assert attn_ex(per_token_scale=1, fp8_mfma=1) == -2   # per-token scale only on the exact product paths
-    assert attn_ex(pv_fmt=1) == -2            # MX-format P V: not built
+    assert attn_ex(pv_fmt=2) == -2            # P V formats: bf16 or MXFP8-E4M3 only
+    assert attn_ex(pv_fmt=1, per_token_scale=1) == -2   # MX-format P V: not with the per-token scale ...
+    assert attn_ex(pv_fmt=1, hi=2) == -2      # ... and only for the default format pair
     assert attn_ex(hi=3, fp8_mfma=1) == -2    # E5M2 only has the decoded-to-bf16 path
     assert attn_ex(fp8_mfma=2) == -1
     assert lib.dma_attn_fwd_workspace_bytes(1, 32, 8, 32768, 128) == 0

@@ -30,7 +30,9 @@ def to_gpu(dma, *bits):
     return [dma.bits_to_bf16_tensor(b) for b in bits]
 
 
-def check_out(got, want, what, slack=None):
+def check_out(got, want, what, slack=None, max_abs_bar=None, rel_bar=None):
+    max_abs_bar = MAX_ABS if max_abs_bar is None else max_abs_bar
+    rel_bar = REL_L2 if rel_bar is None else rel_bar
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert np.all(np.isfinite(got)), what
@@ -38,10 +40,10 @@ def check_out(got, want, what, slack=None):
     max_abs = float(np.max(err))
     rel = float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
     excess = err - (0.0 if slack is None else np.asarray(slack, dtype=np.float64))
-    flips = int(np.count_nonzero(err > MAX_ABS))
-    print(f"{what}: max-abs {max_abs:.3e} rel-L2 {rel:.3e}" + (f" ({flips} elements above {MAX_ABS:g}, all within rounding slack)" if flips else ""), flush=True)
-    assert float(np.max(excess)) <= MAX_ABS, (what, max_abs, float(np.max(excess)))
-    assert rel <= REL_L2, (what, rel)
+    flips = int(np.count_nonzero(err > max_abs_bar))
+    print(f"{what}: max-abs {max_abs:.3e} rel-L2 {rel:.3e}" + (f" ({flips} elements above {max_abs_bar:g}, all within rounding slack)" if flips else ""), flush=True)
+    assert float(np.max(excess)) <= max_abs_bar, (what, max_abs, float(np.max(excess)))
+    assert rel <= rel_bar, (what, rel)
 
 
 # ------------------------------------------------------------------ quantizer: bit-exact
@@ -142,18 +144,20 @@ def fmt_ids(dma, oracle, name):
             "e5m2": (dma.FMT_MXFP8_E5M2, oracle.FMT_E5M2), "bf16": (dma.FMT_BF16, oracle.FMT_BF16)}[name]
 
 
-def run_case(dma, oracle, w, q, k, v, band, lo, hi, rows=None, explicit_tile=True, sink=0, causal=True, per_token=False):
+def run_case(dma, oracle, w, q, k, v, band, lo, hi, rows=None, explicit_tile=True, sink=0, causal=True, per_token=False,
+             pv_mx=False, max_abs_bar=None, rel_bar=None):
     qd, kd, vd = to_gpu(dma, q, k, v)
     (lo_g, lo_o), (hi_g, hi_o) = fmt_ids(dma, oracle, lo), fmt_ids(dma, oracle, hi)
     out = dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, hi_fmt=hi_g, lo_fmt=lo_g, causal=causal, sink_tiles=sink,
-                           per_token_scale=per_token, tile=w.tile if explicit_tile else None)
+                           per_token_scale=per_token, pv_mx=pv_mx, tile=w.tile if explicit_tile else None)
     torch.cuda.synchronize()
     out = out.cpu().numpy()
-    kw = dict(tile=w.tile, band=band, hi_fmt=hi_o, lo_fmt=lo_o, p_round=True, sink=sink, causal=causal, per_token=per_token)
+    kw = dict(tile=w.tile, band=band, hi_fmt=hi_o, lo_fmt=lo_o, p_round=True, sink=sink, causal=causal, per_token=per_token, pv_mx=pv_mx)
     rows = oracle.all_rows(w.B, w.Hq, w.S) if rows is None else oracle.sort_rows(rows)
     want, slack = oracle.dma_attn_rows(q, k, v, rows, with_slack=True, **kw)
     got = out[rows[:, 0], rows[:, 1], rows[:, 2]]
-    check_out(got, want, f"{w.name} band={band} sink={sink} causal={causal} per_token={per_token} lo={lo} hi={hi}", slack)
+    check_out(got, want, f"{w.name} band={band} sink={sink} causal={causal} per_token={per_token} pv_mx={pv_mx} lo={lo} hi={hi}", slack,
+              max_abs_bar, rel_bar)
     return out
 
 
@@ -448,3 +452,37 @@ def test_attn_ragged_sequence_d128(dma, oracle, S, causal):
     run_case(dma, oracle, w, q, k, v, 1, "e2m1", "e4m3", sink=1, causal=causal)
     run_case(dma, oracle, w, q, k, v, 2, "e2m1", "e4m3", per_token=True, causal=causal)
     run_case(dma, oracle, w, q, k, v, 0, "e4m3", "e4m3", causal=causal)
+
+
+# ------------------------------------------------------------------ MX-format P V (blocks of 32 keys; beyond Alg. 1)
+
+# The block-scaled FP8 matrix instruction does not sum a block's products exactly (it aligns them to the largest and
+# drops what falls below a fixed window); with probabilities <= 1 and values of order 1 that stays within the bar of
+# the 16-bit product (measured: up to 6e-4 on these cases), so the same bar is kept.
+PV_MX_MAX_ABS = MAX_ABS
+PV_MX_REL_L2 = REL_L2
+
+
+@pytest.mark.parametrize("band", [0, 1, 4])
+def test_attn_pv_mx_tiny(dma, oracle, band):
+    w = wl.CONFIGS["tiny"]
+    q, k, v = wl.generate(w)
+    run_case(dma, oracle, w, q, k, v, band, "e2m1", "e4m3", pv_mx=True, max_abs_bar=PV_MX_MAX_ABS, rel_bar=PV_MX_REL_L2)
+
+
+@pytest.mark.parametrize("S,causal,sink", [(512, True, 0), (640, True, 0), (384, True, 1), (512, False, 0), (300, True, 0), (300, False, 0)])
+def test_attn_pv_mx_d128(dma, oracle, S, causal, sink):
+    """Both tile pairings (even / odd tile counts), the general instance (sink, no mask) and a partial last tile."""
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=S, Hq=2, Hkv=1)
+    q, k, v = wl.generate(w)
+    run_case(dma, oracle, w, q, k, v, 1, "e2m1", "e4m3", sink=sink, causal=causal, pv_mx=True,
+             max_abs_bar=PV_MX_MAX_ABS, rel_bar=PV_MX_REL_L2)
+
+
+def test_attn_pv_mx_full_size_sampled(dma, oracle):
+    """The benchmark configuration with the MX-format P V, on sampled rows."""
+    w = wl.CONFIGS["prefill_8k"]
+    q, k, v = wl.generate(w)
+    rows = wl.sample_rows(w, [0, 31, 63], [(0, 0), (0, 13)], 128, seed=w.seed + 5)
+    run_case(dma, oracle, w, q, k, v, w.band, "e2m1", "e4m3", rows=rows, explicit_tile=False, pv_mx=True,
+             max_abs_bar=PV_MX_MAX_ABS, rel_bar=PV_MX_REL_L2)
