@@ -486,3 +486,15 @@ def test_attn_pv_mx_full_size_sampled(dma, oracle):
     rows = wl.sample_rows(w, [0, 31, 63], [(0, 0), (0, 13)], 128, seed=w.seed + 5)
     run_case(dma, oracle, w, q, k, v, w.band, "e2m1", "e4m3", rows=rows, explicit_tile=False, pv_mx=True,
              max_abs_bar=PV_MX_MAX_ABS, rel_bar=PV_MX_REL_L2)
+
+
+# ------------------------------------------------------------------ even tile counts at D = 128 (two query tiles per workgroup)
+
+@pytest.mark.parametrize("lo,hi", FMT_PAIRS)
+@pytest.mark.parametrize("S,band", [(256, 0), (256, 1), (512, 2), (1024, 0), (1024, 1), (1024, 3), (1024, 8)])
+def test_attn_d128_even_tiles_all_rows(dma, oracle, S, band, lo, hi):
+    """The instance that pairs two query tiles per workgroup and runs its two halves half a tile out of step: the
+    smallest case (one pair), and several pairs with every window width (none, inside a pair, across pairs, all)."""
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=S, Hq=2, Hkv=1)
+    q, k, v = wl.generate(w)
+    run_case(dma, oracle, w, q, k, v, band, lo, hi, explicit_tile=False)
