@@ -83,6 +83,11 @@ def lib() -> ctypes.CDLL:
         L.oracle_ref_attn_rows_ex.restype = ctypes.c_int
         L.oracle_ref_attn_rows_ex.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_int64, ctypes.c_int, ctypes.c_int, i64p, ctypes.c_int64, f64p]
+        L.oracle_group_amax.restype = ctypes.c_int
+        L.oracle_group_amax.argtypes = [u16p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                        ctypes.c_int64, f32p]
+        L.oracle_mx_quantize_grouped.restype = ctypes.c_int
+        L.oracle_mx_quantize_grouped.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, f32p, u8p, u8p, f32p]
         L.oracle_values_as_seen_mxfp8.restype = ctypes.c_int
         L.oracle_values_as_seen_mxfp8.argtypes = [u16p, ctypes.c_int64, ctypes.c_int, ctypes.c_int64, f64p, u8p]
         L.oracle_num_threads.restype = ctypes.c_int
@@ -202,7 +207,8 @@ def dma_attn_rows(q_bits, k_bits, v_bits, rows, *, tile: int, band: int, hi_fmt:
                   per_token: bool = False, with_slack: bool = False, pv_mx: bool = False):
     """Diagonal-tiled attention output for the given (b, hq, i) rows -> float32 [n_rows, D].
     sink: number of leading key tiles kept in the high format; causal=False: every key tile is visited and the
-    high-precision window is |jt - it| < band.  per_token: Alg. 2 Step 2 on queries and keys.  with_slack: also return, per output element, how far the
+    high-precision window is |jt - it| < band.  per_token: Alg. 2 Step 2 on queries and keys (True / "token": from the
+    row's own maximum; "block": from the maximum of the row's tile of its head; "tensor": from the maximum of Q resp. K).  with_slack: also return, per output element, how far the
     value can move when probabilities that lie within binary32 score noise of a bf16 rounding midpoint round
     the other way (see attn_one_row in dma_oracle.c).  pv_mx: the MX-format P V product (P and V in MXFP8-E4M3 with
     blocks of 32 keys) instead of the 16-bit one; the slack then covers E4M3 rounding flips and block-scale flips."""
@@ -214,12 +220,49 @@ def dma_attn_rows(q_bits, k_bits, v_bits, rows, *, tile: int, band: int, hi_fmt:
     out = np.empty((r.shape[0], D), dtype=np.float32)
     slack = np.zeros((r.shape[0], D), dtype=np.float32) if with_slack else None
     _check(lib().oracle_dma_attn_rows_ex(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
-                                         B, Hq, Hkv, S, D, tile, band, int(sink), int(bool(causal)), int(bool(per_token)),
+                                         B, Hq, Hkv, S, D, tile, band, int(sink), int(bool(causal)), granularity_id(per_token),
                                          hi_fmt, lo_fmt,
                                          2 if pv_mx else int(bool(p_round)), _p(r, ctypes.c_int64), r.shape[0],
                                          _p(out, ctypes.c_float), _p(slack, ctypes.c_float) if with_slack else None),
            "oracle_dma_attn_rows_ex")
     return (out, slack) if with_slack else out
+
+
+GRANULARITY = {False: 0, None: 0, True: 1, "token": 1, "block": 2, "tensor": 3}
+
+
+def granularity_id(per_token) -> int:
+    """per_token argument -> 0 (no Step 2), 1 (per-token), 2 (per-block: the rows of one tile of one head), 3 (per-tensor)."""
+    return GRANULARITY[per_token]
+
+
+def group_amax(x_bits, is_query: bool, granularity, block_rows: int = 0) -> np.ndarray:
+    """x_bits: [..., S, D] bf16 bits.  Maximum magnitude (after the query pre-scale) of the group every row belongs to:
+    the row ("token"), block_rows consecutive rows of one [S, D] matrix ("block"), everything ("tensor"); float32 [..., S]."""
+    x = _as_bits(x_bits)
+    S, D = x.shape[-2], x.shape[-1]
+    n_mat = x.size // (S * D)
+    out = np.empty(x.shape[:-1], dtype=np.float32)
+    _check(lib().oracle_group_amax(_p(x, ctypes.c_uint16), n_mat, S, D, int(bool(is_query)), granularity_id(granularity),
+                                   int(block_rows), _p(out, ctypes.c_float)), "oracle_group_amax")
+    return out
+
+
+def mx_quantize_grouped(x_bits, fmt: int, is_query: bool, amax):
+    """Alg. 2 with Step 2 driven by the given group maxima (float32 [...], one per row): (codes, scales, S_q)."""
+    x = _as_bits(x_bits)
+    D = x.shape[-1]
+    rows = x.size // D
+    am = np.ascontiguousarray(amax, dtype=np.float32).reshape(-1)
+    assert am.size == rows
+    cb = D // 2 if fmt == FMT_E2M1 else D
+    codes = np.zeros(x.shape[:-1] + (cb,), dtype=np.uint8)
+    scales = np.zeros(x.shape[:-1] + (D // 32,), dtype=np.uint8)
+    ts = np.zeros(x.shape[:-1], dtype=np.float32)
+    _check(lib().oracle_mx_quantize_grouped(_p(x, ctypes.c_uint16), rows, D, fmt, int(bool(is_query)), _p(am, ctypes.c_float),
+                                            _p(codes, ctypes.c_uint8), _p(scales, ctypes.c_uint8), _p(ts, ctypes.c_float)),
+           "oracle_mx_quantize_grouped")
+    return codes, scales, ts
 
 
 def values_as_seen_mxfp8(v_bits):

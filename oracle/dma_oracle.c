@@ -212,9 +212,12 @@ void oracle_token_scale(float amax, float *s_q, float *inv_s_q)
  * exists to fit the E4M3-typed scale of NVFP4; an E8M0 scale already spans the binary32 range,
  * Sec. 3.1).
  * per_token != 0: Alg. 2 Step 2 as printed: the row is divided by S_q = max_D|X| / (448 * 6) before
- * the shared scales are formed; *token_scale receives S_q (the dequantized row is decode * S_q). */
-static void quantize_row(const uint16_t *x, int D, int fmt, int is_query, int per_token, uint8_t *codes,
-                         uint8_t *scales, float *token_scale)
+ * the shared scales are formed; *token_scale receives S_q (the dequantized row is decode * S_q).
+ * amax_in >= 0 (with per_token != 0): the maximum is not the row's own but that of the group of rows
+ * it belongs to (Sec. 5.3 names per-block and per-tensor granularities of this scale), given by the
+ * caller (oracle_group_amax). */
+static void quantize_row(const uint16_t *x, int D, int fmt, int is_query, int per_token, float amax_in,
+                         uint8_t *codes, uint8_t *scales, float *token_scale)
 {
     const float c = oracle_query_prescale(D);
     float xs[32];
@@ -229,6 +232,7 @@ static void quantize_row(const uint16_t *x, int D, int fmt, int is_query, int pe
             }
             if (fabsf(v) > rmax) rmax = fabsf(v);
         }
+        if (amax_in >= 0.0f) rmax = amax_in;
         oracle_token_scale(rmax, &s_q, &inv_s_q);
     }
     if (token_scale) *token_scale = s_q;
@@ -270,7 +274,64 @@ static void quantize_row(const uint16_t *x, int D, int fmt, int is_query, int pe
     }
 }
 
-/* token_scales: NULL = Step 2 skipped (S_q = 1); else [rows] binary32, receives S_q of every row. */
+/* Maximum magnitude (after the query pre-scale if is_query) of the group each row belongs to, for
+ * Alg. 2 Step 2 at the granularities Sec. 5.3 names.  x: [n_mat, S, D] bf16; out: [n_mat * S].
+ * gran 1: the row itself (per-token); 2: blocks of block_rows consecutive rows of one [S, D] matrix,
+ * starting at multiples of block_rows (per-block; the last block of a matrix may be shorter);
+ * 3: all of x (per-tensor).
+ * Reading: the paper names the granularities without defining the groups; a block is taken to be the
+ * rows of one attention tile of one head, the tensor everything passed to the call. */
+int oracle_group_amax(const uint16_t *x, int64_t n_mat, int64_t S, int D, int is_query, int gran,
+                      int64_t block_rows, float *out)
+{
+    if (!x || !out || n_mat <= 0 || S <= 0 || D <= 0 || gran < 1 || gran > 3) return ORACLE_ERR_ARG;
+    if (gran == 2 && block_rows <= 0) return ORACLE_ERR_ARG;
+    const float c = oracle_query_prescale(D);
+    const int64_t rows = n_mat * S;
+    for (int64_t r = 0; r < rows; ++r) {
+        float rmax = 0.0f;
+        for (int d = 0; d < D; ++d) {
+            float v = oracle_bf16_to_f32(x[r * D + d]);
+            if (is_query) {
+                volatile float prod = v * c;
+                v = prod;
+            }
+            if (fabsf(v) > rmax) rmax = fabsf(v);
+        }
+        out[r] = rmax;
+    }
+    if (gran == 2) {
+        for (int64_t mtx = 0; mtx < n_mat; ++mtx)
+            for (int64_t r0 = 0; r0 < S; r0 += block_rows) {
+                const int64_t r1 = (r0 + block_rows < S) ? r0 + block_rows : S;
+                float g = 0.0f;
+                for (int64_t r = r0; r < r1; ++r)
+                    if (out[mtx * S + r] > g) g = out[mtx * S + r];
+                for (int64_t r = r0; r < r1; ++r) out[mtx * S + r] = g;
+            }
+    } else if (gran == 3) {
+        float g = 0.0f;
+        for (int64_t r = 0; r < rows; ++r)
+            if (out[r] > g) g = out[r];
+        for (int64_t r = 0; r < rows; ++r) out[r] = g;
+    }
+    return ORACLE_OK;
+}
+
+/* token_scales: NULL = Step 2 skipped (S_q = 1); else [rows] binary32, receives S_q of every row.
+ * amax_in: NULL = the scale of a row comes from its own maximum; else [rows], the maximum of the row's group. */
+int oracle_mx_quantize_grouped(const uint16_t *x, int64_t rows, int D, int fmt, int is_query, const float *amax_in,
+                               uint8_t *codes, uint8_t *scales, float *token_scales)
+{
+    if (!x || !codes || !scales || !token_scales || !amax_in || rows < 0 || D <= 0 || D % 32 != 0) return ORACLE_ERR_ARG;
+    if (!fmt_is_mx(fmt)) return ORACLE_ERR_ARG;
+    const int64_t cb = (fmt == ORACLE_FMT_E2M1) ? D / 2 : D;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        quantize_row(x + r * D, D, fmt, is_query, 1, amax_in[r], codes + r * cb, scales + r * (D / 32), token_scales + r);
+    return ORACLE_OK;
+}
+
 int oracle_mx_quantize_ex(const uint16_t *x, int64_t rows, int D, int fmt, int is_query,
                           uint8_t *codes, uint8_t *scales, float *token_scales)
 {
@@ -279,7 +340,7 @@ int oracle_mx_quantize_ex(const uint16_t *x, int64_t rows, int D, int fmt, int i
     const int64_t cb = (fmt == ORACLE_FMT_E2M1) ? D / 2 : D;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r)
-        quantize_row(x + r * D, D, fmt, is_query, token_scales != NULL, codes + r * cb, scales + r * (D / 32),
+        quantize_row(x + r * D, D, fmt, is_query, token_scales != NULL, -1.0f, codes + r * cb, scales + r * (D / 32),
                      token_scales ? token_scales + r : NULL);
     return ORACLE_OK;
 }
@@ -319,7 +380,7 @@ int oracle_mx_dequantize(const uint8_t *codes, const uint8_t *scales, int64_t ro
 /* What a row looks like to the score product in format fmt, as doubles:
  * quantized formats: quantize then decode; bf16: the values themselves (the softmax factor is
  * then applied to the score, see score_scale()). */
-static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, int per_token, double *out)
+static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, int per_token, float amax_in, double *out)
 {
     if (fmt == ORACLE_FMT_BF16) {
         for (int d = 0; d < D; ++d) out[d] = (double)oracle_bf16_to_f32(x[d]);
@@ -329,7 +390,7 @@ static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, int per
     uint8_t scales[64];
     float s_q = 1.0f;
     memset(codes, 0, sizeof codes);
-    quantize_row(x, D, fmt, is_query, per_token, codes, scales, &s_q);
+    quantize_row(x, D, fmt, is_query, per_token, amax_in, codes, scales, &s_q);
     oracle_mx_dequantize(codes, scales, 1, D, fmt, out);
     if (per_token)
         for (int d = 0; d < D; ++d) out[d] *= (double)s_q;       /* the dequantization multiplier of Step 2 */
@@ -426,7 +487,9 @@ int oracle_values_as_seen_mxfp8(const uint16_t *v, int64_t S, int D, int64_t n, 
  *           |jt - it| < band (Sec. 4.1, "Compatibility with Non-Causal Attention").
  *   per_token : queries and keys go through Alg. 2 Step 2 (row divided by S_q = rowmax / 2688 before
  *           quantization, the decoded row multiplied by S_q again), the "Per-Token" granularity of
- *           Sec. 5.3; the scores are then S_q[i] * S_q[j] * (q^ . k^).
+ *           Sec. 5.3; the scores are then S_q[i] * S_q[j] * (q^ . k^).  per_token = 2 / 3: the same with
+ *           the maximum taken over the row's tile of its head ("Per-Block") / over the whole of Q
+ *           resp. K ("Per-Tensor") instead of the row (oracle_group_amax).
  *   Reading: the printed tile ranges of the non-causal case mix index bases and the paper gives
  *   no loop for the sink window; it argues that any order that covers every tile once is valid.
  *   Here every variant visits the key tiles in ascending order, each in the format the rule
@@ -441,13 +504,13 @@ int oracle_values_as_seen_mxfp8(const uint16_t *v, int64_t S, int D, int64_t n, 
  * the output can move through flips that binary32 scores can cause. */
 static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const double *kseen_hi,
                          const uint16_t *v, const double *vseen, int64_t i, int64_t S, int D, int tile, int band, int sink,
-                         int causal, int per_token, int hi_fmt, int lo_fmt, int p_round, float *out, float *slack)
+                         int causal, int per_token, float q_amax, int hi_fmt, int lo_fmt, int p_round, float *out, float *slack)
 {
     double q_lo[512], q_hi[512], O[512], SL[512];
     double *s = (double *)malloc(sizeof(double) * (size_t)tile * 3);
     double *pt = s + tile, *ph_t = s + 2 * tile;          /* p and its rounded image for the keys of a tile */
-    row_as_seen(qrow, D, lo_fmt, 1, per_token, q_lo);
-    row_as_seen(qrow, D, hi_fmt, 1, per_token, q_hi);
+    row_as_seen(qrow, D, lo_fmt, 1, per_token, q_amax, q_lo);
+    row_as_seen(qrow, D, hi_fmt, 1, per_token, q_amax, q_hi);
     const double c = 1.4426950408889634074 / sqrt((double)D);
     const double sc_lo = (lo_fmt == ORACLE_FMT_BF16) ? c : 1.0;   /* bf16 rows are not pre-scaled */
     const double sc_hi = (hi_fmt == ORACLE_FMT_BF16) ? c : 1.0;
@@ -573,12 +636,12 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
 }
 
 /* Keys of one kv head as seen in a format, rows 0 .. n-1, [n, D] doubles. */
-static double *keys_as_seen(const uint16_t *k, int64_t n, int D, int fmt, int per_token)
+static double *keys_as_seen(const uint16_t *k, int64_t n, int D, int fmt, int per_token, const float *amax_in)
 {
     double *out = (double *)malloc(sizeof(double) * (size_t)n * (size_t)D);
     if (!out) return NULL;
 #pragma omp parallel for schedule(static)
-    for (int64_t r = 0; r < n; ++r) row_as_seen(k + r * D, D, fmt, 0, per_token, out + r * D);
+    for (int64_t r = 0; r < n; ++r) row_as_seen(k + r * D, D, fmt, 0, per_token, amax_in ? amax_in[r] : -1.0f, out + r * D);
     return out;
 }
 
@@ -609,6 +672,17 @@ int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t
             return ORACLE_ERR_ARG;
     }
     const int group = Hq / Hkv;
+    /* per_token: 0 = no Step 2; 1 = per-token; 2 = per-block (the rows of one tile of one head); 3 = per-tensor */
+    if (per_token < 0 || per_token > 3) return ORACLE_ERR_ARG;
+    float *qamax = NULL, *kamax = NULL;
+    if (per_token >= 2) {
+        qamax = (float *)malloc(sizeof(float) * (size_t)B * Hq * S);
+        kamax = (float *)malloc(sizeof(float) * (size_t)B * Hkv * S);
+        if (!qamax || !kamax || oracle_group_amax(q, (int64_t)B * Hq, S, D, 1, per_token, tile, qamax) != ORACLE_OK ||
+            oracle_group_amax(k, (int64_t)B * Hkv, S, D, 0, per_token, tile, kamax) != ORACLE_OK) {
+            free(qamax); free(kamax); return ORACLE_ERR_MEM;
+        }
+    }
     int64_t r0 = 0;
     while (r0 < n_rows) {
         /* maximal run of rows sharing (b, kv head) */
@@ -621,9 +695,10 @@ int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t
         if (!causal) imax = S - 1;
         const uint16_t *kh = k + ((int64_t)b * Hkv + hkv) * S * D;
         const uint16_t *vh = v + ((int64_t)b * Hkv + hkv) * S * D;
-        double *klo = keys_as_seen(kh, imax + 1, D, lo_fmt, per_token);
-        double *khi = (hi_fmt == lo_fmt) ? klo : keys_as_seen(kh, imax + 1, D, hi_fmt, per_token);
-        if (!klo || !khi) { free(klo); if (khi != klo) free(khi); return ORACLE_ERR_MEM; }
+        const float *kam = kamax ? kamax + ((int64_t)b * Hkv + hkv) * S : NULL;
+        double *klo = keys_as_seen(kh, imax + 1, D, lo_fmt, per_token, kam);
+        double *khi = (hi_fmt == lo_fmt) ? klo : keys_as_seen(kh, imax + 1, D, hi_fmt, per_token, kam);
+        if (!klo || !khi) { free(klo); if (khi != klo) free(khi); free(qamax); free(kamax); return ORACLE_ERR_MEM; }
         double *vseen = NULL;
         if (p_round == 2) {
             /* every key of the tiles visited (whole 32-key blocks), but none past the end of the sequence */
@@ -631,14 +706,15 @@ int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t
             if (nv > S) nv = S;
             vseen = (double *)malloc(sizeof(double) * (size_t)nv * (size_t)D);
             if (!vseen || oracle_values_as_seen_mxfp8(vh, S, D, nv, vseen, NULL) != ORACLE_OK) {
-                free(vseen); free(klo); if (khi != klo) free(khi); return ORACLE_ERR_MEM;
+                free(vseen); free(klo); if (khi != klo) free(khi); free(qamax); free(kamax); return ORACLE_ERR_MEM;
             }
         }
 #pragma omp parallel for schedule(dynamic, 1)
         for (int64_t r = r0; r < r1; ++r) {
             const int64_t hq = rows[3 * r + 1], i = rows[3 * r + 2];
             const uint16_t *qrow = q + (((int64_t)b * Hq + hq) * S + i) * D;
-            attn_one_row(qrow, klo, khi, vh, vseen, i, S, D, tile, band, sink, causal, per_token, hi_fmt, lo_fmt, p_round, out + r * D,
+            const float qam = qamax ? qamax[((int64_t)b * Hq + hq) * S + i] : -1.0f;
+            attn_one_row(qrow, klo, khi, vh, vseen, i, S, D, tile, band, sink, causal, per_token, qam, hi_fmt, lo_fmt, p_round, out + r * D,
                          slack ? slack + r * D : NULL);
         }
         if (khi != klo) free(khi);
@@ -646,6 +722,8 @@ int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t
         free(vseen);
         r0 = r1;
     }
+    free(qamax);
+    free(kamax);
     return ORACLE_OK;
 }
 

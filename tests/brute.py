@@ -66,7 +66,29 @@ def quantize_block(x32: np.ndarray, fmt: str):
     return sb, codes, dec
 
 
-def quantize_rows(bits: np.ndarray, fmt: str, is_query: bool, per_token: bool = False, return_token_scale=False):
+def group_maxima(bits: np.ndarray, is_query: bool, granularity: str, block_rows: int = 0) -> np.ndarray:
+    """bits [n_mat, S, D] -> float32 [n_mat, S]: the largest magnitude (queries: after the float32 pre-scale) in the
+    group of each row: the row, the block of block_rows rows of its matrix, or everything."""
+    n_mat, S, D = bits.shape
+    x = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    if is_query:
+        x = (x * np.float32(np.log2(np.e) / np.sqrt(np.float64(D)))).astype(np.float32)
+    a = np.abs(x)
+    out = np.zeros((n_mat, S), dtype=np.float32)
+    for m_ in range(n_mat):
+        for r in range(S):
+            if granularity == "token":
+                grp = a[m_, r]
+            elif granularity == "block":
+                r0 = (r // block_rows) * block_rows
+                grp = a[m_, r0:r0 + block_rows]
+            else:
+                grp = a
+            out[m_, r] = grp.max()
+    return out
+
+
+def quantize_rows(bits: np.ndarray, fmt: str, is_query: bool, per_token: bool = False, return_token_scale=False, amax=None):
     """bits: [rows, D] uint16.  Returns (scales[rows, D/32], codes[rows, D] unpacked, decoded[rows, D]).
     per_token: Alg. 2 Step 2: every row is first multiplied by 2688 / rowmax (float32), and the decoded row by
     rowmax / 2688 (float32); rows whose maximum is below 2^-100 are left alone."""
@@ -77,7 +99,7 @@ def quantize_rows(bits: np.ndarray, fmt: str, is_query: bool, per_token: bool = 
         x = (x * c).astype(np.float32)            # one float32 multiply per element
     s_q = np.ones(rows, dtype=np.float32)
     if per_token:
-        rmax = np.max(np.abs(x), axis=1).astype(np.float32)
+        rmax = np.max(np.abs(x), axis=1).astype(np.float32) if amax is None else np.asarray(amax, dtype=np.float32)
         ok = rmax >= np.float32(2.0 ** -100)
         inv = np.ones(rows, dtype=np.float32)
         inv[ok] = np.float32(2688.0) / rmax[ok]
@@ -137,11 +159,16 @@ def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p
     v = bf16_bits_to_f64(v_bits)
     if pv_mx:
         v = np.stack([values_in_key_blocks(v[hk]) for hk in range(Hkv)])
+    qam = kam = None
+    if per_token in ("block", "tensor"):             # coarser granularities of the Step-2 scale: group maxima first
+        qam = group_maxima(q_bits, True, per_token, tile)
+        kam = group_maxima(k_bits, False, per_token, tile)
+    pt = bool(per_token)
     for h in range(Hq):
-        _, _, q_hi = quantize_rows(q_bits[h], hi, True, per_token)
-        _, _, q_lo = quantize_rows(q_bits[h], lo, True, per_token)
-        _, _, k_hi = quantize_rows(k_bits[h // g], hi, False, per_token)
-        _, _, k_lo = quantize_rows(k_bits[h // g], lo, False, per_token)
+        _, _, q_hi = quantize_rows(q_bits[h], hi, True, pt, amax=None if qam is None else qam[h])
+        _, _, q_lo = quantize_rows(q_bits[h], lo, True, pt, amax=None if qam is None else qam[h])
+        _, _, k_hi = quantize_rows(k_bits[h // g], hi, False, pt, amax=None if kam is None else kam[h // g])
+        _, _, k_lo = quantize_rows(k_bits[h // g], lo, False, pt, amax=None if kam is None else kam[h // g])
         s_hi = q_hi @ k_hi.T
         s_lo = q_lo @ k_lo.T
         ti = np.arange(S)[:, None] // tile

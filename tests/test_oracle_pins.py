@@ -619,3 +619,43 @@ def test_mx_pv_slack_covers_binary32_scores(oracle):
     err = np.abs(got32.reshape(-1, w.D) - want)
     assert np.max(err - slack) < 2e-5
     assert np.median(slack.max(axis=1)) < 1e-5
+
+
+# ------------------------------------------------------------------ coarser granularities of the Step-2 scale (Sec. 5.3)
+
+def test_group_maxima_and_grouped_quantizer(oracle, tiny):
+    w, q, k, v = tiny
+    qh = np.ascontiguousarray(q[0])                           # [Hq, S, D]
+    for gran, br in (("token", 0), ("block", 64), ("block", 48), ("tensor", 0)):
+        for is_query in (False, True):
+            got = oracle.group_amax(qh, is_query, gran, br)
+            want = brute.group_maxima(qh, is_query, gran, br)
+            assert np.array_equal(got, want), (gran, br, is_query)
+    # the per-token granularity is the quantizer's own row maximum
+    am = oracle.group_amax(qh, True, "token")
+    c1, s1, t1 = oracle.mx_quantize_grouped(qh, oracle.FMT_E4M3, True, am)
+    c0, s0, t0 = oracle.mx_quantize(qh, oracle.FMT_E4M3, True, per_token=True)
+    assert np.array_equal(c1, c0) and np.array_equal(s1, s0) and np.array_equal(t1, t0)
+    # per-block maxima: codes, scales and S_q against the brute force
+    am = oracle.group_amax(qh, False, "block", 64)
+    for fmt, name in ((oracle.FMT_E2M1, "e2m1"), (oracle.FMT_E4M3, "e4m3")):
+        codes, scales, ts = oracle.mx_quantize_grouped(qh[0], fmt, False, am[0])
+        bs, bc, _, bt = brute.quantize_rows(qh[0], name, False, True, return_token_scale=True, amax=am[0])
+        assert np.array_equal(scales, bs) and np.array_equal(ts, bt)
+        assert np.array_equal(codes, brute.pack_fp4(bc) if name == "e2m1" else bc)
+    # a coarser group can only have a larger maximum, and every row of a block shares it
+    tok, blk, ten = (oracle.group_amax(qh, False, g, 64) for g in ("token", "block", "tensor"))
+    assert np.all(tok <= blk) and np.all(blk <= ten) and len(np.unique(ten)) == 1
+    assert all(len(np.unique(blk[h, r0:r0 + 64])) == 1 for h in range(qh.shape[0]) for r0 in range(0, w.S, 64))
+
+
+@pytest.mark.parametrize("gran", ["block", "tensor"])
+@pytest.mark.parametrize("causal,S", [(True, 256), (False, 128), (True, 200)])
+def test_granularity_attention_matches_per_element_rewrite(oracle, tiny, gran, causal, S):
+    w, q, k, v = tiny
+    q, k, v = (np.ascontiguousarray(a[:, :, :S]) for a in (q, k, v))
+    got = oracle.dma_attn(q, k, v, tile=w.tile, band=1, causal=causal, per_token=gran)[0]
+    want = brute.dma_attention(q[0], k[0], v[0], tile=w.tile, band=1, causal=causal, per_token=gran)
+    assert np.max(np.abs(got - want)) < 2e-6
+    finer = oracle.dma_attn(q, k, v, tile=w.tile, band=1, causal=causal, per_token=True)[0]
+    assert np.max(np.abs(got - finer)) > 1e-5                 # a different quantization from the per-token one
