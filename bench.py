@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--sink", type=int, default=0, help="leading key tiles in the high format (variant; default 0 = Alg. 1)")
     ap.add_argument("--non-causal", action="store_true", help="no causal mask (variant)")
     ap.add_argument("--per-token", action="store_true", help="per-token scale of Alg. 2 Step 2 (variant)")
+    ap.add_argument("--granularity", choices=["token", "block", "tensor"], default="token",
+                    help="with --per-token: the group of rows that shares a Step-2 scale (Sec. 5.3); block = one tile of one head")
     ap.add_argument("--pv-mx", action="store_true", help="P V in MXFP8-E4M3 with blocks of 32 keys (variant beyond Alg. 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=200000)
@@ -125,9 +127,14 @@ def main():
     out = torch.empty((w.B, w.Hq, w.S, w.D), dtype=torch.float32, device="cuda")
     tile = None if w.tile == 128 else w.tile
 
+    coarse = args.per_token and args.granularity != "token"
+    gran = {"token": binding.GRAN_TOKEN, "block": binding.GRAN_BLOCK, "tensor": binding.GRAN_TENSOR}[args.granularity]
+
     def step():
+        # with a coarser granularity the group maxima are part of the path: they depend on the inputs
+        ga = (binding.dma_mx_group_amax(qd, True, gran, w.tile), binding.dma_mx_group_amax(kd, False, gran, w.tile)) if coarse else None
         binding.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, tile=tile, fp8_mfma=args.fp8_mfma, sink_tiles=args.sink,
-                             causal=not args.non_causal, per_token_scale=args.per_token, pv_mx=args.pv_mx, out=out)
+                             causal=not args.non_causal, per_token_scale=args.per_token, pv_mx=args.pv_mx, group_amax=ga, out=out)
 
     # The GPU reaches its sustained clocks only after some tens of milliseconds of work (measured here: the first ~40
     # launches of the 8k workload run up to 45 % slower than the later ones, and 2 s of idling bring the slow start
@@ -201,6 +208,7 @@ def main():
                                f"band={band} (hi MXFP8-E4M3, lo MXFP4-E2M1), bf16 in, f32 out, seed {w.seed}",
                    "flops_convention": "4*B*Hq*S^2*D" if args.non_causal else "2*B*Hq*S^2*D", "fp8_mfma": bool(args.fp8_mfma),
                    "variant": {"sink_tiles": args.sink, "causal": not args.non_causal, "per_token_scale": bool(args.per_token),
+                               "scale_granularity": args.granularity if args.per_token else None,
                                "pv_mx": bool(args.pv_mx)}},
         "roofline": roofline(w, band, kernel_s, args.sink, not args.non_causal,
                              measured_config=(band == w.band and not (args.sink or args.non_causal or args.per_token or args.fp8_mfma or args.pv_mx)),

@@ -117,6 +117,12 @@ typedef struct dma_attn_opts {
     int per_token_scale;  /* 0: Alg. 2 Step 2 is the identity (default).  1: queries and keys go through Step 2 (row divided by
                              S_q = rowmax / 2688 before quantization) and the score product is multiplied by S_q of its
                              query and of its key; ignored for DMA_FMT_BF16 operands; not with fp8_mfma = 1 */
+    const void* q_group_amax;  /* only with per_token_scale = 1; device float32, 4-byte aligned.  NULL (default): per-token
+                             granularity, the scale of a row comes from its own maximum.  Otherwise q_group_amax [B, Hq, S]
+                             and k_group_amax [B, Hkv, S] (both or neither) give, for every query / key row, the maximum
+                             magnitude of the group of rows that shares its Step-2 scale (Sec. 5.3 names per-block and
+                             per-tensor granularities): S_q = that maximum / 2688.  dma_mx_group_amax produces them */
+    const void* k_group_amax;
     int fp8_mfma;         /* how MXFP8 tiles form Q K^T.
                              0 (default): the E4M3 codes and E8M0 scales are decoded exactly to bf16 and
                                multiplied on the bf16 MFMA: the product of the quantized operands is exact up to
@@ -127,6 +133,22 @@ typedef struct dma_attn_opts {
                                the largest product; twice the matrix rate of mode 0 on those tiles.
                              MXFP4 tiles always use the block-scaled FP4 MFMA, which sums exactly. */
 } dma_attn_opts;
+
+/*
+ * Group maxima for Alg. 2 Step 2 at a granularity coarser than the row (Sec. 5.3, table of quantization granularities:
+ * per-tensor, per-block, per-token; the paper names them without defining the groups).
+ *   x_bf16    [n_mat, S, D] bf16, device, 16-byte aligned; D = 64 or 128 (the head dimensions dma_attn_fwd_ex takes).
+ *   amax_f32  [n_mat * S] float32, device: for every row the largest magnitude (if is_query: after the binary32
+ *             multiplication by log2(e)/sqrt(D) of Alg. 2 Step 1) within the row's group.
+ *   granularity  DMA_GRAN_TOKEN: the row itself; DMA_GRAN_BLOCK: block_rows (> 0) consecutive rows of one [S, D] matrix,
+ *             blocks starting at multiples of block_rows (the last one may be shorter); DMA_GRAN_TENSOR: all of x.
+ * Two to four small kernels on `stream`; no allocation.
+ */
+#define DMA_GRAN_TOKEN 1
+#define DMA_GRAN_BLOCK 2
+#define DMA_GRAN_TENSOR 3
+int dma_mx_group_amax(const void* x_bf16, int64_t n_mat, int64_t S, int D, int is_query, int granularity,
+                      int64_t block_rows, void* amax_f32, void* stream);
 
 /* dma_attn_fwd with explicit options; opts == NULL means the defaults of dma_attn_fwd. */
 int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out,

@@ -17,7 +17,7 @@ FMT_MXFP8_E4M3 = 1
 FMT_MXFP4_E2M1 = 2
 FMT_MXFP8_E5M2 = 3
 
-EXPORTS = ("dma_mx_quantize", "dma_mx_quantize_token", "dma_mx_quantize_dual", "dma_attn_fwd", "dma_attn_fwd_ex",
+EXPORTS = ("dma_mx_quantize", "dma_mx_quantize_token", "dma_mx_quantize_dual", "dma_mx_group_amax", "dma_attn_fwd", "dma_attn_fwd_ex",
            "dma_attn_fwd_workspace_bytes", "dma_diag_copy", "dma_error_string", "dma_version")
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdma_mi355x.so")
@@ -32,7 +32,8 @@ class DmaError(RuntimeError):
 
 class AttnOpts(ctypes.Structure):
     _fields_ = [("tile", ctypes.c_int), ("sink_tiles", ctypes.c_int), ("pv_fmt", ctypes.c_int),
-                ("per_token_scale", ctypes.c_int), ("fp8_mfma", ctypes.c_int)]
+                ("per_token_scale", ctypes.c_int), ("q_group_amax", ctypes.c_void_p), ("k_group_amax", ctypes.c_void_p),
+                ("fp8_mfma", ctypes.c_int)]
 
 
 def lib_path() -> str:
@@ -51,6 +52,8 @@ def load() -> ctypes.CDLL:
         L.dma_mx_quantize.argtypes = [vp, i64, ci, ci, ci, vp, vp, vp]
         L.dma_mx_quantize_token.restype = ci
         L.dma_mx_quantize_token.argtypes = [vp, i64, ci, ci, ci, vp, vp, vp, vp]
+        L.dma_mx_group_amax.restype = ci
+        L.dma_mx_group_amax.argtypes = [vp, i64, i64, ci, ci, ci, i64, vp, vp]
         L.dma_mx_quantize_dual.restype = ci
         L.dma_mx_quantize_dual.argtypes = [vp, i64, ci, ci, vp, vp, vp, vp, vp]
         L.dma_attn_fwd.restype = ci
@@ -120,6 +123,22 @@ def dma_mx_quantize_token(x: torch.Tensor, fmt: int, is_query: bool):
     return codes, scales, ts
 
 
+GRAN_TOKEN, GRAN_BLOCK, GRAN_TENSOR = 1, 2, 3
+
+
+def dma_mx_group_amax(x: torch.Tensor, is_query: bool, granularity: int, block_rows: int = 0) -> torch.Tensor:
+    """x [..., S, D] bf16 -> float32 [..., S]: for every row the largest magnitude (queries: after the Step-1 pre-scale) of
+    the group that shares its Step-2 scale: the row, block_rows rows of its [S, D] matrix, or all of x."""
+    S, D = x.shape[-2], x.shape[-1]
+    n_mat = x.numel() // (S * D)
+    out = torch.empty(x.shape[:-1], dtype=torch.float32, device=x.device)
+    rc = load().dma_mx_group_amax(_dev(x, torch.bfloat16, "x"), n_mat, S, D, int(bool(is_query)), int(granularity),
+                                  int(block_rows), _dev(out, torch.float32, "amax"), _stream())
+    if rc:
+        raise DmaError(rc, "dma_mx_group_amax")
+    return out
+
+
 def dma_mx_quantize_dual(x: torch.Tensor, is_query: bool, out=None):
     """One read of x -> (codes_lo, scales_lo, codes_hi, scales_hi): MXFP4 E2M1 and MXFP8 E4M3 copies."""
     D = x.shape[-1]
@@ -139,10 +158,12 @@ def dma_mx_quantize_dual(x: torch.Tensor, is_query: bool, out=None):
 def dma_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, diag_band_tiles: int,
                  hi_fmt: int = FMT_MXFP8_E4M3, lo_fmt: int = FMT_MXFP4_E2M1, causal: bool = True,
                  tile: int | None = None, fp8_mfma: bool = False, sink_tiles: int = 0, per_token_scale: bool = False,
-                 pv_mx: bool = False, out: torch.Tensor | None = None) -> torch.Tensor:
+                 pv_mx: bool = False, group_amax=None, out: torch.Tensor | None = None) -> torch.Tensor:
     """q [B,Hq,S,D], k/v [B,Hkv,S,D] bf16 -> out [B,Hq,S,D] float32.  With tile=None, fp8_mfma=False and
     sink_tiles=0 this is dma_attn_fwd (logical tile 128); otherwise dma_attn_fwd_ex with those options.
-    pv_mx: the P V product in MXFP8-E4M3 with blocks of 32 keys (opts.pv_fmt) instead of 16-bit."""
+    pv_mx: the P V product in MXFP8-E4M3 with blocks of 32 keys (opts.pv_fmt) instead of 16-bit.
+    group_amax: (q_amax [B,Hq,S], k_amax [B,Hkv,S]) float32 from dma_mx_group_amax: with per_token_scale, the Step-2 scale
+    of a row comes from its group's maximum instead of its own."""
     B, Hq, S, D = q.shape
     Hkv = k.shape[1]
     if k.shape != (B, Hkv, S, D) or v.shape != k.shape:
@@ -152,10 +173,17 @@ def dma_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, diag_band
     args = [_dev(q, torch.bfloat16, "q"), _dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v"),
             _dev(out, torch.float32, "out"), B, Hq, Hkv, S, D, int(bool(causal)), int(diag_band_tiles),
             int(hi_fmt), int(lo_fmt)]
-    if tile is None and not fp8_mfma and not sink_tiles and not per_token_scale and not pv_mx:
+    if tile is None and not fp8_mfma and not sink_tiles and not per_token_scale and not pv_mx and group_amax is None:
         rc = load().dma_attn_fwd(*args, _stream())
     else:
+        qam = kam = None
+        if group_amax is not None:
+            qam = _dev(group_amax[0], torch.float32, "q_group_amax")
+            kam = _dev(group_amax[1], torch.float32, "k_group_amax")
+            if group_amax[0].shape != (B, Hq, S) or group_amax[1].shape != (B, Hkv, S):
+                raise ValueError("group_amax must be ([B, Hq, S], [B, Hkv, S])")
         opts = AttnOpts(tile=int(tile or 0), sink_tiles=int(sink_tiles), pv_fmt=FMT_MXFP8_E4M3 if pv_mx else FMT_BF16, per_token_scale=int(bool(per_token_scale)),
+                        q_group_amax=qam, k_group_amax=kam,
                         fp8_mfma=int(bool(fp8_mfma)))
         rc = load().dma_attn_fwd_ex(*args, ctypes.byref(opts), _stream())
     if rc:

@@ -53,6 +53,19 @@ int dma_mx_quantize_token(const void* x_bf16, int64_t rows, int D, int fmt, int 
     return quantize_one(x_bf16, rows, D, fmt, is_query, codes_u8, scales_u8, (float*)token_scales_f32, true, stream);
 }
 
+int dma_mx_group_amax(const void* x_bf16, int64_t n_mat, int64_t S, int D, int is_query, int granularity,
+                      int64_t block_rows, void* amax_f32, void* stream)
+{
+    if (n_mat < 0 || S < 0 || D <= 0) return DMA_ERR_INVALID_ARG;
+    if (granularity < DMA_GRAN_TOKEN || granularity > DMA_GRAN_TENSOR) return DMA_ERR_INVALID_ARG;
+    if (granularity == DMA_GRAN_BLOCK && block_rows <= 0) return DMA_ERR_INVALID_ARG;
+    if (D != 64 && D != 128) return DMA_ERR_UNSUPPORTED;
+    if (n_mat == 0 || S == 0) return DMA_OK;
+    if (!x_bf16 || !amax_f32 || !aligned16(x_bf16) || (reinterpret_cast<uintptr_t>(amax_f32) & 3u) != 0) return DMA_ERR_INVALID_ARG;
+    if (n_mat > ((int64_t)1 << 40) / S / D) return DMA_ERR_UNSUPPORTED;
+    return dma::launch_group_amax(x_bf16, n_mat, S, D, is_query != 0, granularity, block_rows, (float*)amax_f32, (hipStream_t)stream);
+}
+
 int dma_mx_quantize_dual(const void* x_bf16, int64_t rows, int D, int is_query, void* codes_lo_u8,
                          void* scales_lo_u8, void* codes_hi_u8, void* scales_hi_u8, void* stream)
 {
@@ -81,6 +94,8 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
     int sink = 0;
     int per_token = 0;
     int pv_mx = 0;
+    const float* q_amax = nullptr;
+    const float* k_amax = nullptr;
     if (opts) {
         if (opts->fp8_mfma != 0 && opts->fp8_mfma != 1) return DMA_ERR_INVALID_ARG;
         fp8_mfma = opts->fp8_mfma;
@@ -90,6 +105,11 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
         sink = opts->sink_tiles;
         if (opts->per_token_scale != 0 && opts->per_token_scale != 1) return DMA_ERR_INVALID_ARG;
         per_token = opts->per_token_scale;
+        if ((opts->q_group_amax == nullptr) != (opts->k_group_amax == nullptr)) return DMA_ERR_INVALID_ARG;
+        if (opts->q_group_amax && !per_token) return DMA_ERR_INVALID_ARG;
+        if ((reinterpret_cast<uintptr_t>(opts->q_group_amax) & 3u) != 0 || (reinterpret_cast<uintptr_t>(opts->k_group_amax) & 3u) != 0) return DMA_ERR_INVALID_ARG;
+        q_amax = (const float*)opts->q_group_amax;
+        k_amax = (const float*)opts->k_group_amax;
         if (opts->pv_fmt != DMA_FMT_BF16 && opts->pv_fmt != DMA_FMT_MXFP8_E4M3) return DMA_ERR_UNSUPPORTED;
         pv_mx = opts->pv_fmt == DMA_FMT_MXFP8_E4M3;
     }
@@ -105,6 +125,8 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
     a.sink = sink > n_tiles ? n_tiles : sink;
     a.causal = causal != 0;
     a.per_token = per_token;
+    a.q_amax = q_amax;
+    a.k_amax = k_amax;
     a.pv_mx = pv_mx;
     // the MX-format P V exists for the default pair (MXFP4 / MXFP8-E4M3 decoded exactly), without the per-token scale
     if (pv_mx && (per_token || fp8_mfma || lo_fmt != DMA_FMT_MXFP4_E2M1 || hi_fmt != DMA_FMT_MXFP8_E4M3)) return DMA_ERR_UNSUPPORTED;

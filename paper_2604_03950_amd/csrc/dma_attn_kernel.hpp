@@ -738,8 +738,11 @@ DMA_DEV void value_part(unsigned vsrc, int lane, v16f (&o)[C::NDB], const PTile<
 // ---------------------------------------------------------------------------------------------
 // Alg. 2 Step 2 for the keys of a tile: per chunk round the row maximum over the CPR lanes of the row, S_q into LDS
 // (one float per key at ktsdst), 1 / S_q returned for the quantization.
+// kam / given: the maximum of the group each key row belongs to, when the caller supplies group maxima (a coarser
+// granularity than the row) instead of the row's own maximum.
 template <typename C>
-DMA_DEV void key_token_scales(const v4i (&reg)[C::CPT], float (&inv_sk)[C::CPT], unsigned ktsdst, int tid)
+DMA_DEV void key_token_scales(const v4i (&reg)[C::CPT], float (&inv_sk)[C::CPT], unsigned ktsdst, int tid,
+                              const float (&kam)[C::CPT], bool given)
 {
     constexpr int KPR = C::T / C::CPR;
     tid = fresh(tid);
@@ -750,9 +753,19 @@ DMA_DEV void key_token_scales(const v4i (&reg)[C::CPT], float (&inv_sk)[C::CPT],
         float x[8];
         unpack8<false>(reg[r], 1.f, x);
         float sk;
-        token_scale(group_max<C::CPR>(amax8(x)), sk, inv_sk[r]);
+        token_scale(given ? kam[r] : group_max<C::CPR>(amax8(x)), sk, inv_sk[r]);
         if (dc == 0) lds_write<float>(ta + 4 * r * KPR, sk);
     }
+}
+
+// The group maxima of the key rows of a tile, one per chunk round of the thread (rows >= S: 0).
+template <typename C>
+DMA_DEV void load_key_amax(float (&kam)[C::CPT], const float* __restrict__ amax_head, int row0, int S, int tid)
+{
+    constexpr int KPR = C::T / C::CPR;
+    const int key0 = row0 + fresh(tid) / C::CPR;
+#pragma unroll
+    for (int r = 0; r < C::CPT; ++r) kam[r] = (key0 + r * KPR < S) ? amax_head[key0 + r * KPR] : 0.f;
 }
 
 // K and V of one key tile from registers into LDS: K in the low format if some wave computes the tile in Phase 1,
@@ -760,12 +773,12 @@ DMA_DEV void key_token_scales(const v4i (&reg)[C::CPT], float (&inv_sk)[C::CPT],
 template <typename C, int LO, int HI, bool PT, bool PVMX>
 DMA_DEV void stage_tile(const v4i (&kreg)[C::CPT], const v4i (&vreg)[C::CPT], bool any_lo, bool any_hi,
                         unsigned klo, unsigned kslo, unsigned khi, unsigned kshi, unsigned kts, unsigned vdst,
-                        const LaneOffsets<C, LO>& lo, int tid)
+                        const LaneOffsets<C, LO>& lo, int tid, const float (&kam)[C::CPT], bool kam_given)
 {
     float inv_sk[C::CPT];
 #pragma unroll
     for (int r = 0; r < C::CPT; ++r) inv_sk[r] = 1.f;
-    if constexpr (PT) key_token_scales<C>(kreg, inv_sk, kts, tid);
+    if constexpr (PT) key_token_scales<C>(kreg, inv_sk, kts, tid, kam, kam_given);
     if (any_lo) stage_k<C, LO, PT>(kreg, klo, kslo, lo.stage_k, lo.stage_s, inv_sk);
     if constexpr (LO != HI) {
         if (any_hi) stage_k<C, HI, PT>(kreg, khi, kshi, stage_k_lane<C, HI>(fresh(tid)), lo.stage_s, inv_sk);
@@ -782,8 +795,12 @@ template <int D, int BT, int TPW, int LO, int HI, bool GENERAL, bool PT, bool PV
 __global__ void __launch_bounds__((BT / 32) * TPW * 64, 2)
 dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     const uint16_t* __restrict__ v, float* __restrict__ out,
-                    int B, int Hq, int Hkv, int S, int band, int sink_arg, int causal_arg, float c, int head_block)
+                    int B, int Hq, int Hkv, int S, int band, int sink_arg, int causal_arg, float c, int head_block,
+                    const float* __restrict__ q_amax, const float* __restrict__ k_amax)
 {
+    // q_amax / k_amax (PT only, both or neither): group maxima per query row [B, Hq, S] / key row [B, Hkv, S] that replace
+    // the rows' own maxima in Alg. 2 Step 2 (a coarser granularity of the scale); null: per-token.
+    const bool amax_given = PT && q_amax != nullptr;
     const int sink = GENERAL ? sink_arg : 0;
     const bool causal = GENERAL ? (causal_arg != 0) : true;
     using C = Cfg<D, BT, TPW>;
@@ -864,6 +881,8 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         const uint16_t* khead = k + ((int64_t)b * Hkv + hkv) * S * D;
         const uint16_t* vhead = v + ((int64_t)b * Hkv + hkv) * S * D;
         float* ohead = out + ((int64_t)b * Hq + hq) * S * D;
+        const float* qam_head = amax_given ? q_amax + ((int64_t)b * Hq + hq) * S : nullptr;
+        const float* kam_head = amax_given ? k_amax + ((int64_t)b * Hkv + hkv) * S : nullptr;
 
         // ---- this wave's logical tile and the precision rule (Alg. 1: for query tile `it`, key tile jt is high
         // precision iff it lies in the diagonal window, it - jt < band; extensions: the first `sink` key tiles are high
@@ -923,6 +942,15 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         // ---- prologue: key tile 0 and the query operands (all loads in flight together), tile 0 into LDS buffer 0.
         // Invariant from here on: the K/V registers hold the tile after the one staged last, if there is one.
         v4i kreg[C::CPT], vreg[C::CPT];
+        float kam[C::CPT];                               // group maxima of the key rows in kreg (when given)
+#pragma unroll
+        for (int r = 0; r < C::CPT; ++r) kam[r] = 0.f;
+        auto load_k = [&](int jt) __attribute__((always_inline)) {                   // K tile jt (and its group maxima) into the registers
+            load_tile<C, GENERAL>(kreg, khead, jt * BT, S, tid);
+            if constexpr (PT) {
+                if (amax_given) load_key_amax<C>(kam, kam_head, jt * BT, S, tid);
+            }
+        };
         PTile<C, PVMX> pb;
         v4i qr_lo[QRLO], qr_hi[QRHI];
         int qs_lo = 0, qs_hi = 0;
@@ -930,11 +958,20 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         {
             v4i qraw[C::NKK];
             load_q_raw<C>(qraw, make_rsrc(qhead, (uint32_t)S * (D * 2)), qrow, fresh(lane) & 31, fresh(lane) >> 5);
-            load_tile<C, GENERAL>(kreg, khead, 0, S, tid);
+            load_k(0);
             load_v(vreg, vhead, 0, S, tid);
             __builtin_amdgcn_sched_barrier(0);           // every request is out before the first result is needed
             float inv_sq = 1.f;
-            if constexpr (PT) token_scale(q_row_amax<C>(qraw, c), q_sq, inv_sq);
+            if constexpr (PT) {
+                float amax;
+                if (amax_given) {
+                    const int row = qrow + (fresh(lane) & 31);
+                    amax = row < S ? qam_head[row] : 0.f;
+                } else {
+                    amax = q_row_amax<C>(qraw, c);
+                }
+                token_scale(amax, q_sq, inv_sq);
+            }
             make_q<C, LO, PT>(qr_lo, qs_lo, qraw, c, inv_sq);
             if constexpr (TWO) {
                 if (band > 0 || sink > 0) make_q<C, HI, PT>(qr_hi, qs_hi, qraw, c, inv_sq);
@@ -944,11 +981,11 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             bool any_lo, any_hi;
             needs(jt, any_lo, any_hi);
             stage_tile<C, LO, HI, PT, PVMX>(kreg, vreg, any_lo, any_hi, klo_at(buf), kslo_at(buf), khi_at(buf), kshi_at(buf), kts_at(buf),
-                                      v_at(buf), lofs, tid);
+                                      v_at(buf), lofs, tid, kam, amax_given);
         };
         stage_next(0, 0);
         if (1 < nt) {
-            load_tile<C, GENERAL>(kreg, khead, BT, S, tid);
+            load_k(1);
             load_v(vreg, vhead, BT, S, tid);
         }
         __syncthreads();
@@ -965,7 +1002,7 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             const int buf = jt & 1;
             if (jt + 1 < nt) stage_next(jt + 1, buf ^ 1);
             score_part<C, LO, false, PT, PVMX>(qr_lo, qs_lo, klo_at(buf), kslo_at(buf), lofs.score_k, lofs.score_s, kts_at(buf), q_sq, false, BT, qrow_in_tile, lane, c, m, mfloor, l, o, pb,
-                                     [&]() __attribute__((always_inline)) { if (jt + 2 < nt) load_tile<C, GENERAL>(kreg, khead, (jt + 2) * BT, S, tid); });
+                                     [&]() __attribute__((always_inline)) { if (jt + 2 < nt) load_k(jt + 2); });
             if (jt + 2 < nt) load_v(vreg, vhead, (jt + 2) * BT, S, tid);
             pv(v_at(buf), lofs, lane, o, pb);
             __syncthreads();
@@ -985,7 +1022,7 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                 }
             }
             if (jt + 2 < nt) {
-                load_tile<C, GENERAL>(kreg, khead, (jt + 2) * BT, S, tid);
+                load_k(jt + 2);
                 load_v(vreg, vhead, (jt + 2) * BT, S, tid);
             }
             if (active) pv(v_at(buf), lofs, lane, o, pb);
@@ -1088,7 +1125,7 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
         if (heads_x % hb == 0 && ((int64_t)hb * NG) % (2 * workers) == 0) { head_block = hb; break; }
     hipLaunchKernelGGL((dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT, PVMX>), dim3((unsigned)blocks), dim3(C::T), 0, stream,
                        (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, a.out, a.B, a.Hq, a.Hkv,
-                       a.S, a.band, a.sink, a.causal, c, head_block);
+                       a.S, a.band, a.sink, a.causal, c, head_block, a.q_amax, a.k_amax);
     return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
 }
 

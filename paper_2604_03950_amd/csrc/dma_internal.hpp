@@ -19,6 +19,10 @@ int launch_mx_quantize(const void* x, int64_t rows, int D, int mode, int is_quer
 
 int launch_diag_copy(const void* src, void* dst, int64_t bytes, hipStream_t stream);
 
+// Group maxima for Alg. 2 Step 2 (granularity 1 = row, 2 = block of block_rows rows per [S, D] matrix, 3 = everything).
+int launch_group_amax(const void* x, int64_t n_mat, int64_t S, int D, int is_query, int granularity, int64_t block_rows,
+                      float* amax, hipStream_t stream);
+
 struct AttnArgs {
     const void* q;
     const void* k;
@@ -30,6 +34,8 @@ struct AttnArgs {
     int sink;        // leading key tiles in the high format
     int causal;
     int per_token;   // Alg. 2 Step 2 on queries and keys
+    const float* q_amax;   // with per_token: group maxima per query row [B, Hq, S] instead of the row's own (or null)
+    const float* k_amax;   // ... per key row [B, Hkv, S]
     int pv_mx;       // P V in MXFP8-E4M3 with blocks of 32 keys instead of 16-bit
     int hi_fmt, lo_fmt;
 };

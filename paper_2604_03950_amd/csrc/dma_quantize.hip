@@ -6,6 +6,7 @@
 // byte is written by the first lane of each quad.
 #include "dma_device.hpp"
 #include "dma_internal.hpp"
+#include <math.h>
 
 namespace dma {
 
@@ -102,6 +103,100 @@ int launch_diag_copy(const void* src, void* dst, int64_t bytes, hipStream_t stre
     if (blocks > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
     hipLaunchKernelGGL(diag_copy_kernel, dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream, (const v4i*)src,
                        (v4i*)dst, n_chunks);
+    return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Group maxima for Alg. 2 Step 2 at a coarser granularity than the row (Sec. 5.3 names per-block and per-tensor).
+// First the maximum magnitude of every row (queries: after the pre-scale; the product is monotone, so it is taken of
+// the row maximum), then, in place, the maximum over the block of rows or over everything.
+// ---------------------------------------------------------------------------------------------
+template <int LPR>                                    // lanes per row: D / 8
+__global__ void __launch_bounds__(QUANT_THREADS)
+row_amax_kernel(const v4i* __restrict__ x, int64_t rows, float c, int prescale, float* __restrict__ out)
+{
+    const int64_t t = (int64_t)blockIdx.x * QUANT_THREADS + threadIdx.x;      // one 16-byte chunk per thread
+    const int64_t row = t / LPR;
+    float a = 0.f;
+    if (row < rows) {
+        float v[8];
+        unpack8<false>(x[t], 1.f, v);
+        a = amax8(v);
+    }
+    a = group_max<LPR>(a);
+    if (row < rows && t % LPR == 0) out[row] = prescale ? __fmul_rn(a, c) : a;
+}
+
+DMA_DEV float wave_max(float a)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) a = fmaxf(a, __shfl_xor(a, m, 64));
+    return a;
+}
+
+// One wave per (matrix, block of block_rows rows): maximum of the block, written to each of its rows.
+__global__ void __launch_bounds__(64)
+block_amax_kernel(float* __restrict__ amax, int64_t S, int64_t block_rows, int64_t blocks_per_matrix)
+{
+    const int64_t mtx = blockIdx.x / blocks_per_matrix, blk = blockIdx.x % blocks_per_matrix;
+    const int64_t r0 = blk * block_rows, r1 = (r0 + block_rows < S) ? r0 + block_rows : S;
+    float* p = amax + mtx * S;
+    float a = 0.f;
+    for (int64_t r = r0 + threadIdx.x; r < r1; r += 64) a = fmaxf(a, p[r]);
+    a = wave_max(a);
+    for (int64_t r = r0 + threadIdx.x; r < r1; r += 64) p[r] = a;
+}
+
+// Per-tensor maximum in three steps: block maxima over runs of TENSOR_RUN rows (block_amax_kernel), one workgroup that
+// reduces the first row of every run into amax[0], and a grid that copies amax[0] to every row.
+constexpr int64_t TENSOR_RUN = 1024;
+__global__ void __launch_bounds__(1024)
+tensor_reduce_kernel(float* __restrict__ amax, int64_t rows)
+{
+    __shared__ float part[16];
+    float a = 0.f;
+    for (int64_t r = (int64_t)threadIdx.x * TENSOR_RUN; r < rows; r += 1024 * TENSOR_RUN) a = fmaxf(a, amax[r]);
+    a = wave_max(a);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        a = part[0];
+#pragma unroll
+        for (int w = 1; w < 16; ++w) a = fmaxf(a, part[w]);
+        amax[0] = a;
+    }
+}
+__global__ void __launch_bounds__(QUANT_THREADS)
+broadcast_first_kernel(float* __restrict__ amax, int64_t rows)
+{
+    const int64_t r = (int64_t)blockIdx.x * QUANT_THREADS + threadIdx.x;
+    const float a = amax[0];              // row 0 is rewritten with the value it already holds
+    if (r < rows) amax[r] = a;
+}
+
+// granularity: 1 = the row, 2 = blocks of block_rows rows of each [S, D] matrix, 3 = everything.  D is 64 or 128.
+int launch_group_amax(const void* x, int64_t n_mat, int64_t S, int D, int is_query, int granularity, int64_t block_rows,
+                      float* amax, hipStream_t stream)
+{
+    const int64_t rows = n_mat * S;
+    const int64_t chunks = rows * (D / 8);
+    const int64_t blocks = (chunks + QUANT_THREADS - 1) / QUANT_THREADS;
+    if (blocks > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
+    const float c = (float)(1.4426950408889634074 / sqrt((double)D));
+    if (D == 128) hipLaunchKernelGGL(row_amax_kernel<16>, dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream, (const v4i*)x, rows, c, is_query, amax);
+    else if (D == 64) hipLaunchKernelGGL(row_amax_kernel<8>, dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream, (const v4i*)x, rows, c, is_query, amax);
+    else return DMA_ERR_UNSUPPORTED_;
+    if (granularity == 2) {
+        const int64_t bpm = (S + block_rows - 1) / block_rows;
+        if (n_mat * bpm > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
+        hipLaunchKernelGGL(block_amax_kernel, dim3((unsigned)(n_mat * bpm)), dim3(64), 0, stream, amax, S, block_rows, bpm);
+    } else if (granularity == 3) {
+        const int64_t runs = (rows + TENSOR_RUN - 1) / TENSOR_RUN;
+        if (runs > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
+        hipLaunchKernelGGL(block_amax_kernel, dim3((unsigned)runs), dim3(64), 0, stream, amax, rows, TENSOR_RUN, runs);
+        hipLaunchKernelGGL(tensor_reduce_kernel, dim3(1), dim3(1024), 0, stream, amax, rows);
+        hipLaunchKernelGGL(broadcast_first_kernel, dim3((unsigned)((rows + QUANT_THREADS - 1) / QUANT_THREADS)), dim3(QUANT_THREADS), 0, stream, amax, rows);
+    }
     return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
 }
 

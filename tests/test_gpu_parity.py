@@ -498,3 +498,41 @@ def test_attn_d128_even_tiles_all_rows(dma, oracle, S, band, lo, hi):
     w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=S, Hq=2, Hkv=1)
     q, k, v = wl.generate(w)
     run_case(dma, oracle, w, q, k, v, band, lo, hi, explicit_tile=False)
+
+
+# ------------------------------------------------------------------ coarser granularities of the Step-2 scale (Sec. 5.3)
+
+@pytest.mark.parametrize("D,S", [(64, 256), (128, 300), (128, 512)])
+def test_group_amax_bit_exact(dma, oracle, D, S):
+    """Row, block and tensor maxima (queries: after the pre-scale) against the oracle, bit for bit."""
+    base = wl.CONFIGS["tiny"] if D == 64 else wl.CONFIGS["prefill_8k"]
+    w = wl.small_variant(base, S=S, Hq=3, Hkv=3)
+    q, k, v = wl.generate(w)
+    (qd,) = to_gpu(dma, q)
+    for is_query in (False, True):
+        for gran, name, br in ((dma.GRAN_TOKEN, "token", 0), (dma.GRAN_BLOCK, "block", w.tile), (dma.GRAN_BLOCK, "block", 48),
+                               (dma.GRAN_TENSOR, "tensor", 0)):
+            got = dma.dma_mx_group_amax(qd, is_query, gran, br)
+            torch.cuda.synchronize()
+            want = oracle.group_amax(q, is_query, name, br)
+            assert np.array_equal(got.cpu().numpy(), want), (D, S, is_query, name, br)
+
+
+@pytest.mark.parametrize("gran", ["block", "tensor"])
+@pytest.mark.parametrize("cfg,S,causal,sink", [("tiny", 256, True, 0), ("tiny", 200, False, 0), ("prefill_8k", 512, True, 0),
+                                              ("prefill_8k", 640, True, 1), ("prefill_8k", 300, False, 0)])
+def test_attn_scale_granularity(dma, oracle, gran, cfg, S, causal, sink):
+    """The Step-2 scale per block (the rows of one tile of one head) and per tensor: group maxima from
+    dma_mx_group_amax, handed to the forward."""
+    w = wl.small_variant(wl.CONFIGS[cfg], S=S, Hq=2, Hkv=1)
+    q, k, v = wl.generate(w)
+    qd, kd, vd = to_gpu(dma, q, k, v)
+    gid = dma.GRAN_BLOCK if gran == "block" else dma.GRAN_TENSOR
+    qam = dma.dma_mx_group_amax(qd, True, gid, w.tile)
+    kam = dma.dma_mx_group_amax(kd, False, gid, w.tile)
+    out = dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=1, causal=causal, sink_tiles=sink, per_token_scale=True, tile=w.tile,
+                           group_amax=(qam, kam))
+    torch.cuda.synchronize()
+    rows = oracle.all_rows(w.B, w.Hq, w.S)
+    want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=w.tile, band=1, sink=sink, causal=causal, per_token=gran, with_slack=True)
+    check_out(out.cpu().numpy().reshape(-1, w.D), want, f"{w.name} granularity={gran} causal={causal} sink={sink}", slack)
