@@ -47,6 +47,11 @@ def test_argument_checks_return_before_any_launch(lib):
     assert lib.dma_mx_quantize(fake, 4, 128, 0, 0, fake, fake, None) == -1          # bf16 is not a quantized format
     assert lib.dma_mx_quantize(ctypes.c_void_p(0x1004), 4, 128, 2, 0, fake, fake, None) == -1   # misaligned
     assert lib.dma_mx_quantize_dual(fake, 4, 128, 0, fake, None, fake, fake, None) == -1
+    assert lib.dma_mx_group_amax(fake, 2, 256, 128, 0, 0, 0, fake, None) == -1       # no such granularity
+    assert lib.dma_mx_group_amax(fake, 2, 256, 128, 0, 2, 0, fake, None) == -1       # per-block needs block_rows > 0
+    assert lib.dma_mx_group_amax(fake, 2, 256, 96, 0, 1, 0, fake, None) == -2        # head dimension 64 or 128 only
+    assert lib.dma_mx_group_amax(None, 2, 256, 128, 0, 1, 0, fake, None) == -1
+    assert lib.dma_mx_group_amax(fake, 0, 256, 128, 0, 1, 0, fake, None) == 0        # nothing to do
     args = dict(B=1, Hq=4, Hkv=2, S=256, D=128, causal=1, band=1, hi=1, lo=2)
 
     def attn(**kw):
@@ -69,6 +74,8 @@ def test_argument_checks_return_before_any_launch(lib):
     assert attn_ex(per_token_scale=2) == -1
     assert attn_ex(per_token_scale=1, fp8_mfma=1) == -2   # per-token scale only on the exact product paths
     assert attn_ex(pv_fmt=2) == -2            # P V formats: bf16 or MXFP8-E4M3 only
+    assert attn_ex(per_token_scale=1, q_group_amax=0x1000) == -1     # group maxima: both or neither ...
+    assert attn_ex(q_group_amax=0x1000, k_group_amax=0x1000) == -1     # ... and only with the Step-2 scale
     assert attn_ex(pv_fmt=1, per_token_scale=1) == -2   # MX-format P V: not with the per-token scale ...
     assert attn_ex(pv_fmt=1, hi=2) == -2      # ... and only for the default format pair
     assert attn_ex(hi=3, fp8_mfma=1) == -2    # E5M2 only has the decoded-to-bf16 path
