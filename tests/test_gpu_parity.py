@@ -536,3 +536,18 @@ def test_attn_scale_granularity(dma, oracle, gran, cfg, S, causal, sink):
     rows = oracle.all_rows(w.B, w.Hq, w.S)
     want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=w.tile, band=1, sink=sink, causal=causal, per_token=gran, with_slack=True)
     check_out(out.cpu().numpy().reshape(-1, w.D), want, f"{w.name} granularity={gran} causal={causal} sink={sink}", slack)
+
+
+def test_attn_scale_granularity_full_size_sampled(dma, oracle):
+    """The benchmark configuration with the per-block Step-2 scale, on sampled rows."""
+    w = wl.CONFIGS["prefill_8k"]
+    q, k, v = wl.generate(w)
+    qd, kd, vd = to_gpu(dma, q, k, v)
+    qam = dma.dma_mx_group_amax(qd, True, dma.GRAN_BLOCK, w.tile)
+    kam = dma.dma_mx_group_amax(kd, False, dma.GRAN_BLOCK, w.tile)
+    out = dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=w.band, per_token_scale=True, group_amax=(qam, kam))
+    torch.cuda.synchronize()
+    rows = oracle.sort_rows(wl.sample_rows(w, [0, 63], [(0, 5)], 64, seed=w.seed + 9))
+    want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=w.tile, band=w.band, per_token="block", with_slack=True)
+    got = out.cpu().numpy()[rows[:, 0], rows[:, 1], rows[:, 2]]
+    check_out(got, want, "prefill_8k per-block scale, sampled rows", slack)
