@@ -551,3 +551,11 @@ def test_attn_scale_granularity_full_size_sampled(dma, oracle):
     want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=w.tile, band=w.band, per_token="block", with_slack=True)
     got = out.cpu().numpy()[rows[:, 0], rows[:, 1], rows[:, 2]]
     check_out(got, want, "prefill_8k per-block scale, sampled rows", slack)
+
+
+def test_attn_very_long_sequence_sampled(dma, oracle):
+    """S = 131072 (1024 tiles per head): the first and last tile groups and random rows of a very long sequence."""
+    w = wl.small_variant(wl.CONFIGS["gqa_32k"], S=131072, Hq=2, Hkv=1)
+    q, k, v = wl.generate(w)
+    rows = wl.sample_rows(w, [0, 1023], [(0, 1)], 24, seed=w.seed + 3)
+    run_case(dma, oracle, w, q, k, v, w.band, "e2m1", "e4m3", rows=rows, explicit_tile=False)
