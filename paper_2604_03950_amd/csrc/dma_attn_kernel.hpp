@@ -335,8 +335,10 @@ DMA_DEV void load_tile_vmx(v4i (&reg)[C::CPT], const uint16_t* __restrict__ mat,
 // k_lane / s_lane: stage_k_lane / stage_s_lane of the thread.
 template <typename C, int FMT, bool PT>
 DMA_DEV void stage_k(const v4i (&reg)[C::CPT], unsigned kdst, unsigned ksdst, unsigned k_lane, unsigned s_lane,
-                     const float (&inv_sk)[C::CPT])
+                     const float (&inv_sk)[C::CPT], const float (&bam)[C::CPT])
 {
+    // bam[r] (PT): the largest magnitude of the lane's MX block in round r before the row is scaled; rounding is monotone,
+    // so the block maximum of the scaled values is the scaled block maximum.
     constexpr int KPR = C::T / C::CPR;                       // keys per chunk round
     constexpr int STRIDE = C::template kstride<FMT>();
     const unsigned ka = pin(kdst + k_lane);
@@ -355,17 +357,20 @@ DMA_DEV void stage_k(const v4i (&reg)[C::CPT], unsigned kdst, unsigned ksdst, un
             unpack8<false>(reg[r], 1.f, x);
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[e] = __fmul_rn(x[e], inv_sk[r]);
-            const int code = e8m0_code<FMT_E2M1>(quad_max(amax8(x)));
+            const int code = e8m0_code<FMT_E2M1>(__fmul_rn(bam[r], inv_sk[r]));
             lds_write<int>(ka + r * KPR * STRIDE, encode8_e2m1(x, code));
             lds_write<uint8_t>(sa + r * KPR * C::CPR, (uint8_t)code);
         } else {
             float x[8];
             unpack8<false>(reg[r], 1.f, x);
+            float amax;
             if constexpr (PT) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) x[e] = __fmul_rn(x[e], inv_sk[r]);
+                amax = __fmul_rn(bam[r], inv_sk[r]);
+            } else {
+                amax = quad_max(amax8(x));
             }
-            const float amax = quad_max(amax8(x));
             const int code = e8m0_code<FMT>(amax);
             if constexpr (FMT == FMT_E4M3_X || FMT == FMT_E5M2_X) {
                 lds_write<v4i>(ka + r * KPR * STRIDE, quant_dequant8<FMT>(x, code));
@@ -740,21 +745,43 @@ DMA_DEV void value_part(unsigned vsrc, int lane, v16f (&o)[C::NDB], const PTile<
 // (one float per key at ktsdst), 1 / S_q returned for the quantization.
 // kam / given: the maximum of the group each key row belongs to, when the caller supplies group maxima (a coarser
 // granularity than the row) instead of the row's own maximum.
+// The two divisions of a row's scale are the expensive part and every lane of a row would repeat them: the lanes of a
+// quad take one chunk round each instead (lane q of the quad: round base + q), divide once, and hand the reciprocal to
+// the other three with a quad broadcast.
 template <typename C>
-DMA_DEV void key_token_scales(const v4i (&reg)[C::CPT], float (&inv_sk)[C::CPT], unsigned ktsdst, int tid,
+DMA_DEV void key_token_scales(const v4i (&reg)[C::CPT], float (&inv_sk)[C::CPT], float (&bam)[C::CPT], unsigned ktsdst, int tid,
                               const float (&kam)[C::CPT], bool given)
 {
     constexpr int KPR = C::T / C::CPR;
+    static_assert(C::CPR % 4 == 0, "a quad of lanes lies inside one key row");
     tid = fresh(tid);
-    const int key0 = tid / C::CPR, dc = tid % C::CPR;
-    const unsigned ta = pin(ktsdst + 4 * key0);
+    const int key0 = tid / C::CPR, dc = tid % C::CPR, ql = tid & 3;
+    float am[C::CPT];
 #pragma unroll
     for (int r = 0; r < C::CPT; ++r) {
         float x[8];
         unpack8<false>(reg[r], 1.f, x);
-        float sk;
-        token_scale(given ? kam[r] : group_max<C::CPR>(amax8(x)), sk, inv_sk[r]);
-        if (dc == 0) lds_write<float>(ta + 4 * r * KPR, sk);
+        bam[r] = quad_max(amax8(x));                     // the lane's MX block (a quad of lanes), for stage_k
+        float row = bam[r];                              // ... and on to the whole row: group_max's remaining steps
+        if constexpr (C::CPR >= 8) row = fmaxf(row, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(row), 0x141, 0xF, 0xF, true)));
+        if constexpr (C::CPR >= 16) row = fmaxf(row, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(row), 0x140, 0xF, 0xF, true)));
+        am[r] = given ? kam[r] : row;
+    }
+#pragma unroll
+    for (int base = 0; base < C::CPT; base += 4) {
+        float mine = am[base];
+#pragma unroll
+        for (int j = 1; j < 4; ++j)
+            if (base + j < C::CPT) mine = (ql == j) ? am[base + j] : mine;
+        float sk, inv;
+        token_scale(mine, sk, inv);
+        const int invb = __float_as_int(inv);
+        if (base + 0 < C::CPT) inv_sk[base + 0] = __int_as_float(__builtin_amdgcn_mov_dpp(invb, 0x00, 0xF, 0xF, true));
+        if (base + 1 < C::CPT) inv_sk[base + 1] = __int_as_float(__builtin_amdgcn_mov_dpp(invb, 0x55, 0xF, 0xF, true));
+        if (base + 2 < C::CPT) inv_sk[base + 2] = __int_as_float(__builtin_amdgcn_mov_dpp(invb, 0xAA, 0xF, 0xF, true));
+        if (base + 3 < C::CPT) inv_sk[base + 3] = __int_as_float(__builtin_amdgcn_mov_dpp(invb, 0xFF, 0xF, 0xF, true));
+        // S_q of round base + q goes to LDS from lane q of the row's first quad
+        if (dc < 4 && base + dc < C::CPT) lds_write<float>(ktsdst + 4 * (key0 + (base + dc) * KPR), sk);
     }
 }
 
@@ -775,13 +802,13 @@ DMA_DEV void stage_tile(const v4i (&kreg)[C::CPT], const v4i (&vreg)[C::CPT], bo
                         unsigned klo, unsigned kslo, unsigned khi, unsigned kshi, unsigned kts, unsigned vdst,
                         const LaneOffsets<C, LO>& lo, int tid, const float (&kam)[C::CPT], bool kam_given)
 {
-    float inv_sk[C::CPT];
+    float inv_sk[C::CPT], bam[C::CPT];
 #pragma unroll
-    for (int r = 0; r < C::CPT; ++r) inv_sk[r] = 1.f;
-    if constexpr (PT) key_token_scales<C>(kreg, inv_sk, kts, tid, kam, kam_given);
-    if (any_lo) stage_k<C, LO, PT>(kreg, klo, kslo, lo.stage_k, lo.stage_s, inv_sk);
+    for (int r = 0; r < C::CPT; ++r) inv_sk[r] = 1.f, bam[r] = 0.f;
+    if constexpr (PT) key_token_scales<C>(kreg, inv_sk, bam, kts, tid, kam, kam_given);
+    if (any_lo) stage_k<C, LO, PT>(kreg, klo, kslo, lo.stage_k, lo.stage_s, inv_sk, bam);
     if constexpr (LO != HI) {
-        if (any_hi) stage_k<C, HI, PT>(kreg, khi, kshi, stage_k_lane<C, HI>(fresh(tid)), lo.stage_s, inv_sk);
+        if (any_hi) stage_k<C, HI, PT>(kreg, khi, kshi, stage_k_lane<C, HI>(fresh(tid)), lo.stage_s, inv_sk, bam);
     }
     if constexpr (PVMX) stage_v_mx<C>(vreg, vdst, tid);
     else stage_v<C>(vreg, vdst, lo.stage_v);
