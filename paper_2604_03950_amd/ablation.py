@@ -7,7 +7,7 @@ Three tables on the seeded synthetic inputs of a workload (no dataset, no model 
   formats      the fixed-format baselines against the mixed kernel (Sec. 5.2, latency breakdown by format),
   windows      diagonal window and sink window sizes (Sec. 5.3, table of diagonal and sink sizes),
   granularity  the Step-2 scale: none, per token, per block, per tensor (Sec. 5.3, table of granularities).
-Each row gives the latency of the forward (HIP events, sustained clocks) and how close its output is to the library's
+Each row gives the latency of the forward (HIP events, sustained clocks; TFLOP/s in the causal convention 2 B Hq S^2 D) and how close its output is to the library's
 own unquantized bf16 forward on the same inputs: cosine similarity, relative L1 error, RMSE and PSNR over all output
 elements.  These are reports, not pass/fail checks; the metric formulas are the usual ones (the paper does not print
 them).  Everything runs in the HIP library; nothing here touches the CPU oracle.
@@ -79,9 +79,11 @@ def main():
     ref = forward(hi_fmt=F.FMT_BF16, lo_fmt=F.FMT_BF16).clone()
     n_tiles = -(-w.S // w.tile)
 
+    causal_flops = 2.0 * w.B * w.Hq * w.S * w.S * w.D      # causal flash-attention convention: 4 S^2 D per head, halved
+
     def row(table, name, **kw):
         us = timed(lambda: forward(**kw), args.steps)
-        rec = {"table": table, "case": name, "us": round(us, 1)}
+        rec = {"table": table, "case": name, "us": round(us, 1), "tflops": round(causal_flops / us * 1e-6, 1)}
         rec.update({m: (round(x, 6) if m != "psnr_db" else round(x, 2)) for m, x in similarity(forward(**kw), ref).items()})
         print(json.dumps(rec), flush=True)
 
@@ -105,7 +107,8 @@ def main():
             ga = (binding.dma_mx_group_amax(q, True, gran, w.tile), binding.dma_mx_group_amax(k, False, gran, w.tile))
             return forward(per_token_scale=True, group_amax=ga)
         us = timed(fn, args.steps)
-        rec = {"table": "granularity", "case": name + " (group maxima included in the time)", "us": round(us, 1)}
+        rec = {"table": "granularity", "case": name + " (group maxima included in the time)", "us": round(us, 1),
+               "tflops": round(causal_flops / us * 1e-6, 1)}
         rec.update({m: (round(x, 6) if m != "psnr_db" else round(x, 2)) for m, x in similarity(fn(), ref).items()})
         print(json.dumps(rec), flush=True)
 
