@@ -188,11 +188,18 @@ def main():
     quant_big_bytes = xb.numel() * (2 + 0.5 + 1 + 2 / 32)
     del xb, qb
 
-    # one plain copy of known size, untimed: the reference dispatch for scaling FETCH_SIZE / WRITE_SIZE under rocprofv3
+    # a plain copy of known size: the reference dispatch for scaling FETCH_SIZE / WRITE_SIZE under rocprofv3, and (timed)
+    # the streaming bandwidth a trivial kernel reaches on this machine, to set beside the quantizer's
     csrc = torch.empty(COPY_CALIBRATION_BYTES, dtype=torch.uint8, device="cuda")
     cdst = torch.empty_like(csrc)
     binding.dma_diag_copy(csrc, cdst)
     torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(3):
+        binding.dma_diag_copy(csrc, cdst)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2.0 * COPY_CALIBRATION_BYTES / (ev0.elapsed_time(ev1) * 1e-3 / 3) / 1e9
     del csrc, cdst
 
     rec = {
@@ -218,7 +225,9 @@ def main():
                       "frac": round(quant_bytes / quant_s / 1e9 / HBM_PEAK_GBS, 4),
                       "streaming": {"elements": big_rows * 128, "us": round(quant_big_s * 1e6, 1),
                                     "achieved_GBps": round(quant_big_bytes / quant_big_s / 1e9, 1),
-                                    "frac": round(quant_big_bytes / quant_big_s / 1e9 / HBM_PEAK_GBS, 4)}},
+                                    "frac": round(quant_big_bytes / quant_big_s / 1e9 / HBM_PEAK_GBS, 4),
+                                    "plain_copy_GBps": round(copy_gbps, 1),
+                                    "frac_of_plain_copy": round(quant_big_bytes / quant_big_s / 1e9 / copy_gbps, 4)}},
         "kernel_ms": round(kernel_s * 1e3, 4),
     }
     if not args.no_cpu_baseline:
