@@ -144,13 +144,35 @@ def fmt_ids(dma, oracle, name):
             "e5m2": (dma.FMT_MXFP8_E5M2, oracle.FMT_E5M2), "bf16": (dma.FMT_BF16, oracle.FMT_BF16)}[name]
 
 
+def check_whole_output(out, vd, causal, pv_mx, what):
+    """Properties of the whole output tensor that hold at any size (checked on the device, every element):
+    every row was written (the buffer starts as NaN), and every output lies in the hull of the values its row may
+    attend to -- a row of O is a weighted mean of rows of V with weights that sum to 1 up to the rounding of P
+    (2^-9 per weight in bf16; 2^-4 for P and for V in the E4M3 variant)."""
+    assert bool(torch.isfinite(out).all()), (what, "rows left unwritten or not finite")
+    B, Hq, S, D = out.shape
+    Hkv = vd.shape[1]
+    rel = 0.15 if pv_mx else 0.004
+    for hk in range(Hkv):                      # one kv head at a time keeps the temporaries small
+        vf = vd[:, hk].float()                                                   # [B, S, D]
+        if causal:
+            hi, lo = torch.cummax(vf, dim=1).values, torch.cummin(vf, dim=1).values
+        else:
+            hi, lo = vf.amax(dim=1, keepdim=True).expand_as(vf), vf.amin(dim=1, keepdim=True).expand_as(vf)
+        slack = rel * torch.maximum(hi.abs(), lo.abs()) + 1e-6
+        o = out[:, hk * (Hq // Hkv):(hk + 1) * (Hq // Hkv)]                       # [B, g, S, D]
+        assert bool((o <= (hi + slack)[:, None]).all()) and bool((o >= (lo - slack)[:, None]).all()), (what, "outside the hull of V", hk)
+
+
 def run_case(dma, oracle, w, q, k, v, band, lo, hi, rows=None, explicit_tile=True, sink=0, causal=True, per_token=False,
              pv_mx=False, max_abs_bar=None, rel_bar=None):
     qd, kd, vd = to_gpu(dma, q, k, v)
     (lo_g, lo_o), (hi_g, hi_o) = fmt_ids(dma, oracle, lo), fmt_ids(dma, oracle, hi)
-    out = dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, hi_fmt=hi_g, lo_fmt=lo_g, causal=causal, sink_tiles=sink,
-                           per_token_scale=per_token, pv_mx=pv_mx, tile=w.tile if explicit_tile else None)
+    out = torch.full((w.B, w.Hq, w.S, w.D), float("nan"), dtype=torch.float32, device="cuda")
+    dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, hi_fmt=hi_g, lo_fmt=lo_g, causal=causal, sink_tiles=sink,
+                     per_token_scale=per_token, pv_mx=pv_mx, tile=w.tile if explicit_tile else None, out=out)
     torch.cuda.synchronize()
+    check_whole_output(out, vd, causal, pv_mx, f"{w.name} band={band} sink={sink} causal={causal}")
     out = out.cpu().numpy()
     kw = dict(tile=w.tile, band=band, hi_fmt=hi_o, lo_fmt=lo_o, p_round=True, sink=sink, causal=causal, per_token=per_token, pv_mx=pv_mx)
     rows = oracle.all_rows(w.B, w.Hq, w.S) if rows is None else oracle.sort_rows(rows)
@@ -266,8 +288,10 @@ def test_attn_batched_4k_band_sweep(dma, oracle):
     rows = oracle.sort_rows(wl.sample_rows(w, [0, 15, 31], [(0, 0), (3, 7), (7, 31)], 64, seed=w.seed + 1))
     ref = oracle.ref_attn_rows(q, k, v, rows)
     for band in (0, 1, 2, 4, 8):
-        out = dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band)
+        out = torch.full((w.B, w.Hq, w.S, w.D), float("nan"), dtype=torch.float32, device="cuda")
+        dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, out=out)
         torch.cuda.synchronize()
+        check_whole_output(out, vd, True, False, f"{w.name} band={band}")
         got = out.cpu().numpy()[rows[:, 0], rows[:, 1], rows[:, 2]]
         want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=128, band=band, with_slack=True)
         check_out(got, want, f"{w.name} band={band}", slack)
@@ -545,8 +569,10 @@ def test_attn_scale_granularity_full_size_sampled(dma, oracle):
     qd, kd, vd = to_gpu(dma, q, k, v)
     qam = dma.dma_mx_group_amax(qd, True, dma.GRAN_BLOCK, w.tile)
     kam = dma.dma_mx_group_amax(kd, False, dma.GRAN_BLOCK, w.tile)
-    out = dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=w.band, per_token_scale=True, group_amax=(qam, kam))
+    out = torch.full((w.B, w.Hq, w.S, w.D), float("nan"), dtype=torch.float32, device="cuda")
+    dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=w.band, per_token_scale=True, group_amax=(qam, kam), out=out)
     torch.cuda.synchronize()
+    check_whole_output(out, vd, True, False, "prefill_8k per-block scale")
     rows = oracle.sort_rows(wl.sample_rows(w, [0, 63], [(0, 5)], 64, seed=w.seed + 9))
     want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=w.tile, band=w.band, per_token="block", with_slack=True)
     got = out.cpu().numpy()[rows[:, 0], rows[:, 1], rows[:, 2]]

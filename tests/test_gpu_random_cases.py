@@ -55,9 +55,11 @@ def test_random_cases(dma, oracle, seed):
         if per_token and gran != "token":
             gid = dma.GRAN_BLOCK if gran == "block" else dma.GRAN_TENSOR
             group_amax = (dma.dma_mx_group_amax(qd, True, gid, tile), dma.dma_mx_group_amax(kd, False, gid, tile))
-        out = dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, hi_fmt=fm[hi][0], lo_fmt=fm[lo][0], causal=causal,
-                               sink_tiles=sink, per_token_scale=per_token, pv_mx=pv_mx, group_amax=group_amax, tile=tile)
+        out = torch.full((w.B, w.Hq, w.S, w.D), float("nan"), dtype=torch.float32, device="cuda")    # unwritten rows stay NaN
+        dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, hi_fmt=fm[hi][0], lo_fmt=fm[lo][0], causal=causal,
+                         sink_tiles=sink, per_token_scale=per_token, pv_mx=pv_mx, group_amax=group_amax, tile=tile, out=out)
         torch.cuda.synchronize()
+        assert bool(torch.isfinite(out).all()), what
         rows = oracle.all_rows(w.B, w.Hq, w.S)
         if len(rows) > 1500:
             pick = np.random.Generator(np.random.Philox(100 * seed + it)).choice(len(rows), 1500, replace=False)
