@@ -5,7 +5,9 @@
 
 A step is one pass of the whole hot path (in-kernel MX quantization of Q/K, diagonal-tiled QK^T,
 online softmax, PV, normalisation = one dma_attn_fwd call) over one batch of synthetic bf16 inputs
-already resident in HBM.  Prints ONE JSON line (see the design doc for every field).
+already resident in HBM.  Prints ONE JSON line: value = 2 B Hq S^2 D / wall time per step (TFLOP/s, causal
+convention); roofline = executed tile flops / kernel time against the format-weighted MFMA peak; quantizer = the
+standalone dual quantizer's bandwidth; cpu_baseline = the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -111,7 +113,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1. "
-              "DESIGN.md describes how the path would shard.", file=sys.stderr)
+              "The path shards over (batch, kv head) units without any exchange.", file=sys.stderr)
         sys.exit(2)
 
     import torch
