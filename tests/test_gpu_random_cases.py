@@ -71,3 +71,43 @@ def test_random_cases(dma, oracle, seed):
         err = np.abs(got - want)
         rel = float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
         assert float(np.max(err - slack)) <= MAX_ABS and rel <= REL_L2, (what, float(err.max()), rel)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_midsize_cases(dma, oracle, seed):
+    """Mid-size shapes with odd head counts and batches: more work items than workgroups (several rounds of the static
+    schedule, with and without the per-XCD split), lengths that are not whole tiles.  Every row must be written; 600
+    uniformly drawn rows go to the oracle."""
+    rnd = random.Random(seed)
+    tile = 128
+    for it in range(4):
+        hkv = rnd.choice([3, 5, 7, 8, 12, 16])
+        group = rnd.choice([1, 2, 3, 4])
+        batch = rnd.choice([1, 2, 3, 5])
+        S = rnd.choice([1024, 1536, 2048, 2304, 3072, rnd.randint(900, 3000)])
+        w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=S, Hq=hkv * group, Hkv=hkv, B=batch, seed=1000 * seed + it)
+        q, k, v = wl.generate(w)
+        band = rnd.choice([0, 1, 2, 3])
+        sink = rnd.choice([0, 0, 1])
+        causal = rnd.random() < 0.7
+        per_token = rnd.random() < 0.25
+        pv_mx = (not per_token) and rnd.random() < 0.25
+        what = (f"seed {seed} case {it}: B={batch} Hq={w.Hq} Hkv={hkv} S={S} band={band} sink={sink} causal={causal} "
+                f"per_token={per_token} pv_mx={pv_mx}")
+        print(what, flush=True)
+        qd, kd, vd = (dma.bits_to_bf16_tensor(a) for a in (q, k, v))
+        out = torch.full((w.B, w.Hq, w.S, w.D), float("nan"), dtype=torch.float32, device="cuda")
+        dma.dma_attn_fwd(qd, kd, vd, diag_band_tiles=band, causal=causal, sink_tiles=sink, per_token_scale=per_token,
+                         pv_mx=pv_mx, out=out)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out).all()), what
+        rows = oracle.all_rows(w.B, w.Hq, w.S)
+        pick = np.random.Generator(np.random.Philox(1000 * seed + it)).choice(len(rows), 600, replace=False)
+        rows = oracle.sort_rows(rows[np.sort(pick)])
+        want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=tile, band=band, sink=sink, causal=causal, per_token=per_token,
+                                           pv_mx=pv_mx, with_slack=True)
+        got = out.cpu().numpy()[rows[:, 0], rows[:, 1], rows[:, 2]].astype(np.float64)
+        err = np.abs(got - want)
+        rel = float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
+        assert float(np.max(err - slack)) <= MAX_ABS and rel <= REL_L2, (what, float(err.max()), rel)
