@@ -742,7 +742,8 @@ DMA_DEV void value_part(unsigned vsrc, int lane, v16f (&o)[C::NDB], const PTile<
 // The kernel
 // ---------------------------------------------------------------------------------------------
 // Alg. 2 Step 2 for the keys of a tile: per chunk round the row maximum over the CPR lanes of the row, S_q into LDS
-// (one float per key at ktsdst), 1 / S_q returned for the quantization.
+// (one float per key at ktsdst), 1 / S_q returned for the quantization (inv_sk), and with it the largest magnitude of
+// the lane's MX block before the scaling (bam), from which stage_k gets the block's shared scale without a second pass.
 // kam / given: the maximum of the group each key row belongs to, when the caller supplies group maxima (a coarser
 // granularity than the row) instead of the row's own maximum.
 // The two divisions of a row's scale are the expensive part and every lane of a row would repeat them: the lanes of a
