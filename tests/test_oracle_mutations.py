@@ -41,6 +41,12 @@ MUTATIONS = [
     ("row sum from the rounded P", r"psum \+= pt\[t\];", "psum += oracle_round_to_bf16(pt[t]);", "skeleton"),
     ("key tiles visited in descending order", r"for \(int64_t jt = 0; jt < n_tiles; \+\+jt\) \{\n        const int64_t dist",
      "for (int64_t jt = n_tiles - 1; jt >= 0; --jt) {\n        const int64_t dist", "mixed"),
+    ("sink window one tile too wide", r"jt < \(int64_t\)sink", "jt <= (int64_t)sink", "mixed"),
+    ("e_max of E5M2 off by one", r"ORACLE_FMT_E5M2 \? 15 : 8;", "ORACLE_FMT_E5M2 ? 14 : 8;", "e5m2"),
+    ("window without the causal mask looks back only", r"\(it >= jt\) \? it - jt : jt - it", "it - jt", "noncausal"),
+    ("per-token scale divides by 448 instead of 448 * 6", r"amax / 2688\.0f, b = 2688\.0f / amax", "amax / 448.0f, b = 448.0f / amax", "token"),
+    ("MX-format P V in blocks of 16 keys", r"for \(int t0 = 0; t0 < tile; t0 \+= 32\) \{\n                const int n = \(tile - t0 < 32\) \? tile - t0 : 32;",
+     "for (int t0 = 0; t0 < tile; t0 += 16) {\n                const int n = (tile - t0 < 16) ? tile - t0 : 16;", "pv_mx"),
 ]
 
 
@@ -62,6 +68,14 @@ def run_pin(which, oracle, tiny):
         pins.test_e2m1_grid_roundtrip_and_ties(oracle)
     elif which == "e2m1_paper":
         pins.test_e2m1_paper_examples(oracle)
+    elif which == "e5m2":
+        pins.test_e5m2_shared_scale_and_blocks(oracle)
+    elif which == "noncausal":
+        pins.test_noncausal_mixed_tiles_match_per_element_rewrite(oracle, tiny, 1, 0, True)
+    elif which == "token":
+        pins.test_token_scale_fixed_points(oracle)
+    elif which == "pv_mx":
+        pins.test_mx_pv_matches_per_element_rewrite(oracle, tiny, 1, True, 256)
     else:
         raise KeyError(which)
 
@@ -95,7 +109,8 @@ def tiny():
 
 def test_unmodified_copy_passes_the_pins_used_here(tmp_path, tiny):
     oracle = private_oracle(tmp_path, "oracle_copy")
-    for which in ("skeleton", "mixed", "all_high", "e8m0", "prescale", "bf16", "e2m1_grid", "e2m1_paper"):
+    for which in ("skeleton", "mixed", "all_high", "e8m0", "prescale", "bf16", "e2m1_grid", "e2m1_paper", "e5m2", "noncausal",
+                  "token", "pv_mx"):
         run_pin(which, oracle, tiny)
 
 
