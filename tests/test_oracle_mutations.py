@@ -47,6 +47,15 @@ MUTATIONS = [
     ("per-token scale divides by 448 instead of 448 * 6", r"amax / 2688\.0f, b = 2688\.0f / amax", "amax / 448.0f, b = 448.0f / amax", "token"),
     ("MX-format P V in blocks of 16 keys", r"for \(int t0 = 0; t0 < tile; t0 \+= 32\) \{\n                const int n = \(tile - t0 < 32\) \? tile - t0 : 32;",
      "for (int t0 = 0; t0 < tile; t0 += 16) {\n                const int n = (tile - t0 < 16) ? tile - t0 : 16;", "pv_mx"),
+    ("FP4 nibbles packed the other way round", r"if \(d & 1\) codes\[d >> 1\] = \(uint8_t\)\(codes\[d >> 1\] \| \(cd << 4\)\);\n                else       codes\[d >> 1\] = cd;",
+     "if (d & 1) codes[d >> 1] = (uint8_t)(codes[d >> 1] | cd);\n                else       codes[d >> 1] = (uint8_t)(cd << 4);", "packing"),
+    ("E2M1 clamps at 4 instead of 6", r"fmt == ORACLE_FMT_E2M1 \? 6\.0 :", "fmt == ORACLE_FMT_E2M1 ? 4.0 :", "saturating"),
+    ("E4M3 saturates at 480 (code 0x7F)", r"if \(mag > 0x7E\) mag = 0x7E;", "if (mag > 0x7F) mag = 0x7F;", "e4m3_fixed"),
+    ("E4M3 subnormals truncated", r"mag = \(int\)nearbyint\(ldexp\(a, 9\)\);", "mag = (int)floor(ldexp(a, 9));", "e4m3_fixed"),
+    ("E4M3 mantissa carry lost", r"if \(m == 8\) \{ e \+= 1; m = 0; \}", "if (m == 8) { m = 7; }", "e4m3_brute"),
+    ("shared scale from blocks of 16", r"float v = oracle_bf16_to_f32\(x\[blk \* 32 \+ t\]\);\n            if \(is_query\) \{\n                volatile float prod = v \* c;     /\* one binary32 multiply, rounded once \*/",
+     "float v = oracle_bf16_to_f32(x[blk * 32 + t % 16]);\n            if (is_query) {\n                volatile float prod = v * c;     /* one binary32 multiply, rounded once */", "tiny_quant"),
+    ("sign of an underflowed element dropped", r"int neg = signbit\(xs\[t\]\) \? 1 : 0;", "int neg = (xs[t] < 0.0f && fabsf(xs[t]) > 0x1p-20f) ? 1 : 0;", "edge_blocks"),
 ]
 
 
@@ -68,6 +77,18 @@ def run_pin(which, oracle, tiny):
         pins.test_e2m1_grid_roundtrip_and_ties(oracle)
     elif which == "e2m1_paper":
         pins.test_e2m1_paper_examples(oracle)
+    elif which == "packing":
+        pins.test_packing_nibbles(oracle)
+    elif which == "saturating":
+        pins.test_saturating_block(oracle)
+    elif which == "e4m3_fixed":
+        pins.test_e4m3_codes_roundtrip_and_fixed_points(oracle)
+    elif which == "e4m3_brute":
+        pins.test_e4m3_bruteforce_all_bf16(oracle)
+    elif which == "tiny_quant":
+        pins.test_quantizer_matches_bruteforce_on_tiny_workload(oracle)
+    elif which == "edge_blocks":
+        pins.test_edge_blocks(oracle)
     elif which == "e5m2":
         pins.test_e5m2_shared_scale_and_blocks(oracle)
     elif which == "noncausal":
@@ -110,7 +131,7 @@ def tiny():
 def test_unmodified_copy_passes_the_pins_used_here(tmp_path, tiny):
     oracle = private_oracle(tmp_path, "oracle_copy")
     for which in ("skeleton", "mixed", "all_high", "e8m0", "prescale", "bf16", "e2m1_grid", "e2m1_paper", "e5m2", "noncausal",
-                  "token", "pv_mx"):
+                  "token", "pv_mx", "packing", "saturating", "e4m3_fixed", "e4m3_brute", "tiny_quant", "edge_blocks"):
         run_pin(which, oracle, tiny)
 
 

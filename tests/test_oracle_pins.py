@@ -46,6 +46,8 @@ def test_e2m1_grid_roundtrip_and_ties(oracle):
     for x, want in [(0.2501, 0.5), (1.2501, 1.5), (5.0001, 6.0), (0.7501, 1.0)]:
         assert oracle.e2m1_decode(oracle.e2m1_encode(x)) == want
     assert oracle.e2m1_encode(-0.0) == 8 and oracle.e2m1_encode(-0.1) == 8    # sign survives underflow
+    for big, code in ((7.0, 7), (7.9, 7), (100.0, 7), (-1e9, 15)):             # beyond the top: saturates to +-6
+        assert oracle.e2m1_encode(big) == code
 
 
 def test_e2m1_bruteforce_all_bf16(oracle):
@@ -71,6 +73,8 @@ def test_e4m3_codes_roundtrip_and_fixed_points(oracle):
     assert oracle.e4m3_encode(1.1875) == 0x3A              # tie 1.125 / 1.25 -> even mantissa
     assert oracle.e4m3_encode(1.96875) == 0x40             # rounds up across the binade
     assert oracle.e4m3_encode(464.0) == 0x7E               # would round past the top: saturates
+    for big in (472.0, 480.0, 512.0, 1e9, -480.0):          # 0x7F / 0xFF (the NaN pattern) is never produced
+        assert oracle.e4m3_encode(big) == (0xFE if big < 0 else 0x7E)
 
 
 def test_e4m3_bruteforce_all_bf16(oracle):
@@ -350,6 +354,8 @@ def test_e5m2_codes_roundtrip_and_fixed_points(oracle):
         assert abs(v) == brute.E5M2_GRID[code & 0x7F]
         assert oracle.e5m2_encode(v) == code
     assert oracle.e5m2_decode(0x7B) == 57344.0 and oracle.e5m2_encode(57344.0) == 0x7B
+    for big, code in ((61440.0, 0x7B), (1e9, 0x7B), (-65536.0, 0xFB)):      # no infinity or NaN code is ever produced
+        assert oracle.e5m2_encode(big) == code
     assert oracle.e5m2_decode(0x3C) == 1.0 and oracle.e5m2_decode(0x04) == 2.0 ** -14
     assert oracle.e5m2_encode(2.0 ** -16) == 0x01
     assert oracle.e5m2_encode(2.0 ** -17) == 0x00          # tie between 0 and 2^-16 -> even
