@@ -7,7 +7,9 @@
  *     tensor); the library allocates nothing, keeps no state between calls and writes only to the
  *     output buffers named below.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue their
- *     kernels on it and return without waiting.
+ *     kernels on it and return without waiting.  They issue nothing but kernel launches (no
+ *     allocation, copy, memset or synchronisation), so a stream under HIP graph capture records
+ *     them and the graph can be replayed.
  *   - Return value: DMA_OK (0) or a negative error code.  On error nothing has been enqueued.
  *     No C++ exception crosses the boundary.  dma_error_string() maps a code to a static string.
  *   - bf16 tensors are dense and row-major with the head dimension D innermost.

@@ -126,12 +126,14 @@ def dma_mx_quantize_token(x: torch.Tensor, fmt: int, is_query: bool):
 GRAN_TOKEN, GRAN_BLOCK, GRAN_TENSOR = 1, 2, 3
 
 
-def dma_mx_group_amax(x: torch.Tensor, is_query: bool, granularity: int, block_rows: int = 0) -> torch.Tensor:
+def dma_mx_group_amax(x: torch.Tensor, is_query: bool, granularity: int, block_rows: int = 0,
+                      out: torch.Tensor | None = None) -> torch.Tensor:
     """x [..., S, D] bf16 -> float32 [..., S]: for every row the largest magnitude (queries: after the Step-1 pre-scale) of
     the group that shares its Step-2 scale: the row, block_rows rows of its [S, D] matrix, or all of x."""
     S, D = x.shape[-2], x.shape[-1]
     n_mat = x.numel() // (S * D)
-    out = torch.empty(x.shape[:-1], dtype=torch.float32, device=x.device)
+    if out is None:
+        out = torch.empty(x.shape[:-1], dtype=torch.float32, device=x.device)
     rc = load().dma_mx_group_amax(_dev(x, torch.bfloat16, "x"), n_mat, S, D, int(bool(is_query)), int(granularity),
                                   int(block_rows), _dev(out, torch.float32, "amax"), _stream())
     if rc:
