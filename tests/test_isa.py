@@ -4,6 +4,7 @@ The packed-bf16 FP4 convert of the K staging takes its four source dwords out of
 that code made the compiler name the tuple's first register in all four converts (wrong codes, caught by the parity
 tests at the time); this test pins the generated code: every group of four converts into one destination reads four
 different source registers.  (The compiler is the image's; the check guards edits of the source.)
+The same listing must hold no packed binary32 arithmetic: the library is built with those forms switched off.
 """
 import os
 import re
@@ -21,7 +22,10 @@ def test_fp4_convert_groups_read_four_registers(tmp_path, lo, hi):
     cmd = ["hipcc"] + flags + [f"-DDMA_LO={lo}", f"-DDMA_HI={hi}", "-S", "--cuda-device-only", "-o", str(out),
                               os.path.join(B.CSRC, "dma_attn_inst.hip")]
     subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
-    lines = [ln.strip() for ln in open(out) if "v_cvt_scalef32_pk_fp4_bf16" in ln]
+    text = open(out).read()
+    # the build flags keep the packed binary32 add / multiply / fused multiply-add forms out of the generated code
+    assert not re.search(r"\bv_pk_(add|mul|fma)_f32\b", text)
+    lines = [ln.strip() for ln in text.splitlines() if "v_cvt_scalef32_pk_fp4_bf16" in ln]
     assert len(lines) >= 16 and len(lines) % 4 == 0
     want_sel = ["", "[0,0,1,0]", "[0,0,0,1]", "[0,0,1,1]"]
     for i in range(0, len(lines), 4):
