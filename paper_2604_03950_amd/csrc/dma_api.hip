@@ -114,7 +114,9 @@ int dma_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int 
         pv_mx = opts->pv_fmt == DMA_FMT_MXFP8_E4M3;
     }
     if (tile != 64 && tile != 128) return DMA_ERR_UNSUPPORTED;
-    if ((int64_t)S * D * 4 >= ((int64_t)1 << 32)) return DMA_ERR_UNSUPPORTED;      // one head of the output must fit a 4 GiB buffer resource
+    // one head of the output must fit a 4 GiB buffer resource, rows of a partial or filled-up last tile group included
+    // (their offsets must not wrap around before the resource's bounds drop them)
+    if (((int64_t)S + 2 * tile) * D * 4 >= ((int64_t)1 << 32)) return DMA_ERR_UNSUPPORTED;
     if ((int64_t)B * Hq * S * D > (int64_t)1 << 40) return DMA_ERR_UNSUPPORTED;
     dma::AttnArgs a;
     a.q = q; a.k = k; a.v = v; a.out = (float*)out;

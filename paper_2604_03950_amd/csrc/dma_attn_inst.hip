@@ -15,12 +15,13 @@ namespace dma {
 int DMA_PAIR_NAME(DMA_LO, DMA_HI)(const AttnArgs& a, hipStream_t stream)
 {
     if (a.D == 128 && a.tile == 128) {
-        // two logical tiles per workgroup (256 query rows share each K/V tile) whenever they pair up
-        if (((a.S + 127) / 128) % 2 == 0) return launch_instance<128, 128, 2, DMA_LO, DMA_HI>(a, stream);
+        // two logical tiles per workgroup (256 query rows share each K/V tile); with an odd number of tiles the last
+        // pair is filled up with a tile past the end of the sequence.  One tile per workgroup only for a single tile.
+        if (a.S > 128) return launch_instance<128, 128, 2, DMA_LO, DMA_HI>(a, stream);
         return launch_instance<128, 128, 1, DMA_LO, DMA_HI>(a, stream);
     }
     if (a.D == 64 && a.tile == 64) {
-        if (((a.S + 63) / 64) % 2 == 0) return launch_instance<64, 64, 2, DMA_LO, DMA_HI>(a, stream);
+        if (a.S > 64) return launch_instance<64, 64, 2, DMA_LO, DMA_HI>(a, stream);
         return launch_instance<64, 64, 1, DMA_LO, DMA_HI>(a, stream);
     }
     return DMA_ERR_UNSUPPORTED_;

@@ -884,8 +884,12 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     // everything), so the workers move from block to block together and share few K/V streams at a time.  When the
     // (batch, kv head) units divide over the 8 XCDs (workgroup i runs on XCD i % 8), each XCD keeps its own units, so
     // the K/V stream of a unit stays in one L2.
-    const int N = (S + BT - 1) / BT;     // logical tiles per sequence, the last one may be partial (host guarantees N % TPW == 0)
-    const int NG = N / TPW;              // tile groups
+    // Logical tiles per sequence; the last one may be partial.  When N is not a multiple of TPW (GENERAL instances only)
+    // the last group is filled up with query tiles that lie wholly past the end of the sequence: their rows load as
+    // zeros, their stores are dropped by the bounds of the output's buffer resource, and under the causal mask they
+    // alone visit key tile N, which loads as zeros too.  They cost one extra step in one item per head.
+    const int N = (S + BT - 1) / BT;
+    const int NG = (N + TPW - 1) / TPW;  // tile groups
     const int group = Hq / Hkv;
     const int units = B * Hkv;
     const bool by_xcd = (units % 8 == 0) && (gridDim.x % 8 == 0);
@@ -1128,8 +1132,8 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
 {
     using C = Cfg<D, BT, TPW>;
     const int N = (a.S + BT - 1) / BT;
-    const int64_t items = (int64_t)a.B * a.Hq * (N / TPW);
-    if (N % TPW != 0 || items <= 0 || items > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
+    const int64_t items = (int64_t)a.B * a.Hq * ((N + TPW - 1) / TPW);
+    if ((!GENERAL && N % TPW != 0) || items <= 0 || items > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
     const int cus = compute_units();
     if (cus <= 0) return DMA_ERR_HIP_;
     // as many workgroups as the chip holds at once (one per CU for the D = 128 instances), each walking its share
@@ -1145,7 +1149,7 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
     const int64_t blocks = items < slots ? items : slots;
     const float c = (float)(1.4426950408889634074 / sqrt((double)D));
     // ranking blocks: the fewest heads that fill an even number of rounds (mirrors the kernel's view of the grid)
-    const int units = a.B * a.Hkv, group = a.Hq / a.Hkv, NG = N / TPW;
+    const int units = a.B * a.Hkv, group = a.Hq / a.Hkv, NG = (N + TPW - 1) / TPW;
     const bool by_xcd = (units % 8 == 0) && (blocks % 8 == 0);
     const int workers = (int)(by_xcd ? blocks / 8 : blocks);
     const int heads_x = by_xcd ? (units / 8) * group : a.B * a.Hq;
@@ -1158,7 +1162,7 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
     return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
 }
 
-// Alg. 1 as printed (causal, no sink window, sequence a whole number of tiles) runs the straight-line instance, whose
+// Alg. 1 as printed (causal, no sink window, sequence a whole number of tile groups) runs the straight-line instance, whose
 // tile loads are unbounded; the sink window, the non-causal variant, the per-token scale and a partial last tile run
 // the general one, whose loads are bounded by buffer resources (unquantized operands have no per-token scale).
 template <int D, int BT, int TPW, int LO, int HI>
@@ -1168,7 +1172,7 @@ static int launch_instance(const AttnArgs& a, hipStream_t stream)
         // the MX-format P V is built for the default pair only, without the per-token scale
         if constexpr (LO == FMT_E2M1 && HI == FMT_E4M3_X) {
             if (a.per_token) return DMA_ERR_UNSUPPORTED_;
-            if (a.causal && a.sink == 0 && a.S % BT == 0) return launch_variant<D, BT, TPW, LO, HI, false, false, true>(a, stream);
+            if (a.causal && a.sink == 0 && a.S % (BT * TPW) == 0) return launch_variant<D, BT, TPW, LO, HI, false, false, true>(a, stream);
             return launch_variant<D, BT, TPW, LO, HI, true, false, true>(a, stream);
         } else {
             return DMA_ERR_UNSUPPORTED_;
@@ -1177,7 +1181,7 @@ static int launch_instance(const AttnArgs& a, hipStream_t stream)
     if constexpr (LO != FMT_BF16) {
         if (a.per_token) return launch_variant<D, BT, TPW, LO, HI, true, true>(a, stream);
     }
-    if (a.causal && a.sink == 0 && a.S % BT == 0) return launch_variant<D, BT, TPW, LO, HI, false, false>(a, stream);
+    if (a.causal && a.sink == 0 && a.S % (BT * TPW) == 0) return launch_variant<D, BT, TPW, LO, HI, false, false>(a, stream);
     return launch_variant<D, BT, TPW, LO, HI, true, false>(a, stream);
 }
 

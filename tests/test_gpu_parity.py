@@ -309,7 +309,7 @@ def test_attn_heavy_tail_16k_modes(dma, oracle):
 
 
 def test_attn_odd_tile_count(dma, oracle):
-    """An odd number of query tiles uses the one-tile-per-workgroup instance."""
+    """An odd number of query tiles: the last pair of tiles is filled up with a tile past the end of the sequence."""
     w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=384, Hq=3, Hkv=3)
     q, k, v = wl.generate(w)
     for band, lo, hi in ((2, "e2m1", "e4m3"), (0, "e2m1", "e2m1")):
@@ -365,7 +365,7 @@ def test_attn_sink_window(dma, oracle, band, sink):
     w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=768, Hq=2, Hkv=2)
     q, k, v = wl.generate(w)
     run_case(dma, oracle, w, q, k, v, band, "e2m1", "e4m3", sink=sink)
-    w = wl.small_variant(wl.CONFIGS["gqa_32k"], S=640, Hq=8, Hkv=2)        # odd tile count: one tile per workgroup
+    w = wl.small_variant(wl.CONFIGS["gqa_32k"], S=640, Hq=8, Hkv=2)        # odd tile count: the last pair holds one real tile
     q, k, v = wl.generate(w)
     run_case(dma, oracle, w, q, k, v, band, "e2m1", "e4m3", sink=sink)
     run_case(dma, oracle, w, q, k, v, band, "e2m1", "e2m1", sink=sink)      # one format: the sink changes nothing
