@@ -93,7 +93,7 @@ int dma_mx_quantize_dual(const void* x_bf16, int64_t rows, int D, int is_query,
  *   Key tiles are visited in ascending order in every variant.
  *   The logical tile is B_M = B_N = 128 for dma_attn_fwd and D must be 128.  S >= 1 is arbitrary: the last tile may be
  *   partial (Sec. 3.2 tiles the sequence with a ceiling); keys past the end do not exist and rows past the end are
- *   not written.  S * D * 4 must stay below 4 GiB.
+ *   not written.  (S + 2 * tile) * D * 4 must stay below 4 GiB (else DMA_ERR_UNSUPPORTED).
  *
  *   Per key tile: scores in base 2 (the factor log2(e)/sqrt(D) is folded into Q before quantization;
  *   for BF16 it multiplies the binary32 score), keys after the query masked to -inf on the diagonal

@@ -63,6 +63,7 @@ def test_argument_checks_return_before_any_launch(lib):
     assert attn(hi=7) == -1
     assert attn(B=0) == -1
     assert attn(S=1 << 23) == -2              # one head of the output would not fit a 4 GiB buffer resource
+    assert attn(S=(1 << 23) - 200) == -2      # ... nor may the rows of a filled-up last tile pair wrap around its offsets
     assert attn(D=96) == -2                   # no kernel for this head dimension
     assert attn(hi=2, lo=1) == -2             # unsupported format pair
     assert lib.dma_attn_fwd(None, fake, fake, fake, 1, 4, 2, 256, 128, 1, 1, 1, 2, None) == -1
