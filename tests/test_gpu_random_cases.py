@@ -85,7 +85,7 @@ def test_random_midsize_cases(dma, oracle, seed):
         hkv = rnd.choice([3, 5, 7, 8, 12, 16])
         group = rnd.choice([1, 2, 3, 4])
         batch = rnd.choice([1, 2, 3, 5])
-        S = rnd.choice([1024, 1536, 2048, 2304, 3072, rnd.randint(900, 3000)])
+        S = rnd.choice([1024, 1152, 1536, 2048, 2432, 3072, rnd.randint(900, 3000)])    # even and odd tile counts
         w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=S, Hq=hkv * group, Hkv=hkv, B=batch, seed=1000 * seed + it)
         q, k, v = wl.generate(w)
         band = rnd.choice([0, 1, 2, 3])
