@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch from the rocprofv3 --pmc runs summarised in profiles/ (FETCH_SIZE + WRITE_SIZE,
 # scaled by the same counters on a copy kernel of known size); None where not measured.
-MEASURED_TRAFFIC_BYTES = {"prefill_8k": 432.2e6,      # profiles/dma_attn_fwd_prefill_8k.md, section 2
-                          "gqa_32k": 2.297e9}         # profiles/dma_attn_fwd_gqa_32k.md, section 2
+MEASURED_TRAFFIC_BYTES = {"prefill_8k": 406.5e6,      # profiles/dma_attn_fwd_prefill_8k.md, section 2
+                          "gqa_32k": 2.284e9}         # profiles/dma_attn_fwd_gqa_32k.md, section 2
 RAMP_MS = 60.0                        # untimed work before the timed region (clock ramp-up), see main()
 COPY_CALIBRATION_BYTES = 1 << 29      # dma_diag_copy reads and writes this many bytes once per run
 

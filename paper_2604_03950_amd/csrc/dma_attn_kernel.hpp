@@ -99,7 +99,8 @@ DMA_DEV v4i buffer_load16(rsrc_t r, unsigned byte_offset)
 }
 DMA_DEV void buffer_store16(rsrc_t r, unsigned byte_offset, v4f v)
 {
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), r, (int)byte_offset, 0, 0);
+    // non-temporal: the output is written once and read by nobody here, it should not push K/V lines out of the L2
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), r, (int)byte_offset, 0, 2);
 }
 
 // qmat: the [S, D] bf16 query matrix of the head (resource over its S rows); rows >= S read as zero.
