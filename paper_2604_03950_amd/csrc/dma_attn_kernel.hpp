@@ -24,6 +24,7 @@
 // work of the other, and together they reach the full vector issue rate, which one wave alone does not.
 #pragma once
 
+#include <atomic>
 #include "dma_device.hpp"
 #include "dma_internal.hpp"
 
@@ -1117,15 +1118,15 @@ dma_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
 // Number of compute units of the current device (cached per device).
 inline int compute_units()
 {
-    static int cached[64] = {0};
+    static std::atomic<int> cached[64];               // zero-initialised; every writer stores the same value
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 template <int D, int BT, int TPW, int LO, int HI, bool GENERAL, bool PT, bool PVMX = false>
@@ -1139,13 +1140,14 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
     if (cus <= 0) return DMA_ERR_HIP_;
     // as many workgroups as the chip holds at once (one per CU for the D = 128 instances), each walking its share
     // of the work items
-    static int resident = 0;              // per instance; the same on every device of one kind
-    if (resident == 0) {
+    // per instance, the same on every device of one kind; initialised once, also when several host threads launch
+    static const int resident = [] {
         int n = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT, PVMX>, C::T, 0) != hipSuccess || n <= 0)
-            return DMA_ERR_HIP_;
-        resident = n;
-    }
+            return -1;
+        return n;
+    }();
+    if (resident <= 0) return DMA_ERR_HIP_;
     const int64_t slots = (int64_t)cus * resident;
     const int64_t blocks = items < slots ? items : slots;
     const float c = (float)(1.4426950408889634074 / sqrt((double)D));
