@@ -76,7 +76,15 @@ def lib() -> ctypes.CDLL:
         L.oracle_dma_attn_rows_ex.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                               ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                              ctypes.c_int, i64p, ctypes.c_int64, f32p, f32p]
+                                              ctypes.c_int, i64p, ctypes.c_int64, f32p]
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        L.oracle_dma_attn_row_alt.restype = ctypes.c_int
+        L.oracle_dma_attn_row_alt.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                              i64p, i32p, ctypes.c_int64, f32p, ctypes.c_double, ctypes.c_int64,
+                                              i64p, i32p, f64p, f64p, i64p]
         L.oracle_ref_attn_rows.restype = ctypes.c_int
         L.oracle_ref_attn_rows.argtypes = [u16p, u16p, u16p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            ctypes.c_int64, ctypes.c_int, i64p, ctypes.c_int64, f64p]
@@ -204,28 +212,79 @@ def sort_rows(rows) -> np.ndarray:
 
 def dma_attn_rows(q_bits, k_bits, v_bits, rows, *, tile: int, band: int, hi_fmt: int = FMT_E4M3,
                   lo_fmt: int = FMT_E2M1, p_round: bool = True, sink: int = 0, causal: bool = True,
-                  per_token: bool = False, with_slack: bool = False, pv_mx: bool = False):
+                  per_token: bool = False, pv_mx: bool = False):
     """Diagonal-tiled attention output for the given (b, hq, i) rows -> float32 [n_rows, D].
     sink: number of leading key tiles kept in the high format; causal=False: every key tile is visited and the
     high-precision window is |jt - it| < band.  per_token: Alg. 2 Step 2 on queries and keys (True / "token": from the
-    row's own maximum; "block": from the maximum of the row's tile of its head; "tensor": from the maximum of Q resp. K).  with_slack: also return, per output element, how far the
-    value can move when probabilities that lie within binary32 score noise of a bf16 rounding midpoint round
-    the other way (see attn_one_row in dma_oracle.c).  pv_mx: the MX-format P V product (P and V in MXFP8-E4M3 with
-    blocks of 32 keys) instead of the 16-bit one; the slack then covers E4M3 rounding flips and block-scale flips."""
+    row's own maximum; "block": from the maximum of the row's tile of its head; "tensor": from the maximum of Q resp. K).
+    pv_mx: the MX-format P V product (P and V in MXFP8-E4M3 with blocks of 32 keys) instead of the 16-bit one."""
     q, k, v = _as_bits(q_bits), _as_bits(k_bits), _as_bits(v_bits)
     B, Hq, S, D = q.shape
     Hkv = k.shape[1]
     assert k.shape == (B, Hkv, S, D) and v.shape == k.shape
     r = np.ascontiguousarray(np.asarray(rows, dtype=np.int64).reshape(-1, 3))
     out = np.empty((r.shape[0], D), dtype=np.float32)
-    slack = np.zeros((r.shape[0], D), dtype=np.float32) if with_slack else None
     _check(lib().oracle_dma_attn_rows_ex(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
                                          B, Hq, Hkv, S, D, tile, band, int(sink), int(bool(causal)), granularity_id(per_token),
                                          hi_fmt, lo_fmt,
                                          2 if pv_mx else int(bool(p_round)), _p(r, ctypes.c_int64), r.shape[0],
-                                         _p(out, ctypes.c_float), _p(slack, ctypes.c_float) if with_slack else None),
+                                         _p(out, ctypes.c_float)),
            "oracle_dma_attn_rows_ex")
-    return (out, slack) if with_slack else out
+    return out
+
+
+# Rounding decisions a parity test may ask to see taken the other way (dma_attn_row_alt)
+ALT_NEIGHBOUR, ALT_SCALE_UP, ALT_SCALE_DOWN = 1, 2, 3
+
+
+def _row_alt(q_bits, k_bits, v_bits, row, alts, cand, *, tile, band, hi_fmt=FMT_E4M3, lo_fmt=FMT_E2M1, sink=0, causal=True,
+             per_token=False, pv_mx=False):
+    q, k, v = _as_bits(q_bits), _as_bits(k_bits), _as_bits(v_bits)
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    b, hq, i = (int(x) for x in row)
+    keys = np.ascontiguousarray([a[0] for a in alts], dtype=np.int64)
+    kinds = np.ascontiguousarray([a[1] for a in alts], dtype=np.int32)
+    out = np.empty(D, dtype=np.float32)
+    if cand is None:
+        min_move, max_cand, ck, cn, cm, cr, nc = 0.0, 0, None, None, None, None, None
+    else:
+        min_move, max_cand = cand
+        ck = np.zeros(max_cand, dtype=np.int64)
+        cn = np.zeros(max_cand, dtype=np.int32)
+        cm = np.zeros((max_cand, D), dtype=np.float64)
+        cr = np.zeros(max_cand, dtype=np.float64)
+        nc = np.zeros(1, dtype=np.int64)
+    _check(lib().oracle_dma_attn_row_alt(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
+                                         B, Hq, Hkv, S, D, tile, band, int(sink), int(bool(causal)), granularity_id(per_token),
+                                         hi_fmt, lo_fmt, 2 if pv_mx else 1, b, hq, i,
+                                         _p(keys, ctypes.c_int64) if len(alts) else None,
+                                         _p(kinds, ctypes.c_int32) if len(alts) else None, len(alts), _p(out, ctypes.c_float),
+                                         float(min_move), int(max_cand),
+                                         None if ck is None else _p(ck, ctypes.c_int64),
+                                         None if cn is None else _p(cn, ctypes.c_int32),
+                                         None if cm is None else _p(cm, ctypes.c_double),
+                                         None if cr is None else _p(cr, ctypes.c_double),
+                                         None if nc is None else _p(nc, ctypes.c_int64)),
+           "oracle_dma_attn_row_alt")
+    if cand is None:
+        return out
+    n = int(min(nc[0], max_cand))
+    return out, [(int(ck[t]), int(cn[t])) for t in range(n)], cm[:n], int(nc[0]), cr[:n]
+
+
+def dma_attn_row_alt(q_bits, k_bits, v_bits, row, alts, **kw) -> np.ndarray:
+    """The row (b, hq, i) with the rounding decisions `alts` = [(key, ALT_*), ...] taken the other way -> float32 [D].
+    Keywords as dma_attn_rows (the probabilities are always rounded: p_round is not one of them)."""
+    return _row_alt(q_bits, k_bits, v_bits, row, list(alts), None, **kw)
+
+
+def dma_attn_row_candidates(q_bits, k_bits, v_bits, row, *, min_move: float = 0.0, max_cand: int = 16, **kw):
+    """The rounding decisions of the row (b, hq, i) that an implementation with binary32 scores may take the other way
+    (see oracle_dma_attn_row_alt in dma_oracle.c): (row output float32 [D], [(key, ALT_*), ...] with the largest effect first
+    (at most max_cand), their first-order effect on the output float64 [n, D], the number of all such decisions whose
+    effect reaches min_move, and per listed decision the share of the noise allowance it uses, 0 .. 1)."""
+    return _row_alt(q_bits, k_bits, v_bits, row, [], (min_move, max_cand), **kw)
 
 
 GRANULARITY = {False: 0, None: 0, True: 1, "token": 1, "block": 2, "tensor": 3}

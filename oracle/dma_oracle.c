@@ -406,8 +406,10 @@ static void row_as_seen(const uint16_t *x, int D, int fmt, int is_query, int per
  * nearest even).  Keys at or beyond S count as zeros. */
 
 /* One block of n <= 32 real values: its scale byte and what the block looks like after
- * quantize + decode.  x holds binary32-representable values or probabilities in [0, 1]. */
-static int block_e4m3_as_seen(const double *x, int n, double *seen)
+ * quantize + decode.  x holds binary32-representable values or probabilities in [0, 1].
+ * shift (0 except for the alternatives a parity test asks for, see row_alts) is added to the
+ * scale byte the rule gives before the byte is clamped. */
+static int block_e4m3_as_seen(const double *x, int n, int shift, double *seen)
 {
     double amax = 0.0;
     for (int t = 0; t < n; ++t)
@@ -416,7 +418,7 @@ static int block_e4m3_as_seen(const double *x, int n, double *seen)
     if (amax > 0.0) {
         int ex;
         (void)frexp(amax, &ex);
-        biased = (long)(ex - 1) - 8 + 127;          /* floor(log2 amax) - e_max, biased */
+        biased = (long)(ex - 1) - 8 + 127 + shift;  /* floor(log2 amax) - e_max, biased */
         if (biased < 0) biased = 0;
         if (biased > 254) biased = 254;
     }
@@ -443,7 +445,7 @@ int oracle_values_as_seen_mxfp8(const uint16_t *v, int64_t S, int D, int64_t n, 
                 const int64_t j = b * 32 + t;
                 x[t] = (j < S) ? (double)oracle_bf16_to_f32(v[j * D + d]) : 0.0;
             }
-            const int sc = block_e4m3_as_seen(x, 32, y);
+            const int sc = block_e4m3_as_seen(x, 32, 0, y);
             if (scales) scales[b * D + d] = (uint8_t)sc;
             for (int t = 0; t < 32; ++t) {
                 const int64_t j = b * 32 + t;
@@ -453,6 +455,68 @@ int oracle_values_as_seen_mxfp8(const uint16_t *v, int64_t S, int D, int64_t n, 
     }
     return ORACLE_OK;
 }
+
+/* ------------------------------------------------------------------------------------------ */
+/* Alternative roundings (for the parity tests; no part of the method)                          */
+/* ------------------------------------------------------------------------------------------ */
+/* Rounding a probability for the second product is a decision taken on a floating-point value.
+ * An implementation that forms the scores in binary32 sees a p that differs from the double p by
+ * a few units in the last place of the score, and where the double p lies that close to the
+ * midpoint of two representable numbers it legitimately picks the other one.  A parity test that
+ * meets such a row asks for the row again with named decisions taken the other way (row_alts),
+ * and compares the implementation with THAT result at the plain bar; which decisions are open to
+ * this is decided by oracle_dma_attn_row_candidates() further down, not here.
+ *   ORACLE_ALT_NEIGHBOUR   the probability of that key takes the other of its two neighbours
+ *   ORACLE_ALT_SCALE_UP / _DOWN   (MX-format P V) the 32-key block of that key takes a shared
+ *                          scale one binade coarser / finer than the rule gives */
+#define ORACLE_ALT_NEIGHBOUR 1
+#define ORACLE_ALT_SCALE_UP 2
+#define ORACLE_ALT_SCALE_DOWN 3
+typedef struct { int64_t n; const int64_t *key; const int32_t *kind; } row_alts;
+
+static int alt_neighbour(const row_alts *alt, int64_t j)
+{
+    for (int64_t f = 0; alt && f < alt->n; ++f)
+        if (alt->key[f] == j && alt->kind[f] == ORACLE_ALT_NEIGHBOUR) return 1;
+    return 0;
+}
+static int alt_scale_shift(const row_alts *alt, int64_t j0, int n)      /* for the block of keys j0 .. j0+n-1 */
+{
+    for (int64_t f = 0; alt && f < alt->n; ++f)
+        if (alt->key[f] >= j0 && alt->key[f] < j0 + n && alt->kind[f] != ORACLE_ALT_NEIGHBOUR)
+            return alt->kind[f] == ORACLE_ALT_SCALE_UP ? 1 : -1;
+    return 0;
+}
+/* rounded = p rounded to a grid of spacing 2^quantum around p: the grid point on the other side of p. */
+static double other_grid_point(double p, double rounded, int quantum)
+{
+    const double lower = ldexp(floor(ldexp(p, -quantum)), quantum);
+    if (lower == p) return rounded;                                      /* p is a grid point: nothing to decide */
+    return (rounded == lower) ? lower + ldexp(1.0, quantum) : lower;
+}
+static int bf16_quantum(double p)                                      /* spacing of bf16 numbers at p > 0 is 2^this */
+{
+    int ex;
+    (void)frexp(p, &ex);
+    return (ex - 1) - 7 < -133 ? -133 : (ex - 1) - 7;
+}
+static int e4m3_quantum(double y)                                      /* spacing of E4M3 numbers at y > 0 is 2^this */
+{
+    int ex;
+    (void)frexp(y, &ex);
+    return (ex - 1) - 3 < -9 ? -9 : (ex - 1) - 3;
+}
+/* p seen as `seen` through an E4M3 block with scale byte sc: the other neighbour (none if p is clamped). */
+static double e4m3_other_neighbour(double p, int sc, double seen)
+{
+    const double y = ldexp(p, 127 - sc);
+    if (!(y > 0.0) || y >= 448.0) return seen;
+    return ldexp(other_grid_point(y, ldexp(seen, 127 - sc), e4m3_quantum(y)), sc - 127);
+}
+
+/* What a parity test may ask to see of a row besides its output: per key j the score s_j (masked
+ * keys: -inf) and the running maximum m' its tile ended with; the final m and l. */
+typedef struct { double *s, *m; double m_final, l_final; } row_trace;
 
 /* ------------------------------------------------------------------------------------------ */
 /* Diagonal-tiled attention for a list of query rows (Alg. 1 + Sec. 3.2)                       */
@@ -494,19 +558,13 @@ int oracle_values_as_seen_mxfp8(const uint16_t *v, int64_t S, int D, int64_t n, 
  *   no loop for the sink window; it argues that any order that covers every tile once is valid.
  *   Here every variant visits the key tiles in ascending order, each in the format the rule
  *   above gives it; for causal attention without a sink this is exactly Phase 1 then Phase 2. */
-/* Rounding slack (optional output, for the parity tests).  Rounding p to bf16 is a decision taken on
- * a floating-point value; an implementation that forms the score in binary32 sees a p that differs
- * from the double-precision p by about p * ln2 * |ds|, |ds| a few binary32 units of the score's
- * magnitude, and legitimately rounds the other way when p lies that close to the midpoint of two
- * bf16 numbers.  Such a flip moves the numerator of output d by one bf16 spacing of p times v_jd and
- * leaves l alone.  slack[d] = sum over the keys whose p lies within 2^-20 * (|s_j| + |m| + 1) * ln2 * p
- * of a midpoint of (spacing_j * |v_jd|), carried through the rescaling like O, divided by l: the most
- * the output can move through flips that binary32 scores can cause. */
+/* alt / trace: NULL except when a parity test asks (see row_alts, row_trace above). */
 static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const double *kseen_hi,
                          const uint16_t *v, const double *vseen, int64_t i, int64_t S, int D, int tile, int band, int sink,
-                         int causal, int per_token, float q_amax, int hi_fmt, int lo_fmt, int p_round, float *out, float *slack)
+                         int causal, int per_token, float q_amax, int hi_fmt, int lo_fmt, int p_round, float *out,
+                         const row_alts *alt, row_trace *trace)
 {
-    double q_lo[512], q_hi[512], O[512], SL[512];
+    double q_lo[512], q_hi[512], O[512];
     double *s = (double *)malloc(sizeof(double) * (size_t)tile * 3);
     double *pt = s + tile, *ph_t = s + 2 * tile;          /* p and its rounded image for the keys of a tile */
     row_as_seen(qrow, D, lo_fmt, 1, per_token, q_amax, q_lo);
@@ -516,7 +574,7 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
     const double sc_hi = (hi_fmt == ORACLE_FMT_BF16) ? c : 1.0;
 
     double m = -INFINITY, l = 1.0;
-    for (int d = 0; d < D; ++d) { O[d] = 0.0; SL[d] = 0.0; }
+    for (int d = 0; d < D; ++d) O[d] = 0.0;
 
     const int64_t it = i / tile;
     const int64_t n_tiles = causal ? it + 1 : (S + tile - 1) / tile;   /* the last tile may be partial: keys >= S do not exist */
@@ -544,59 +602,20 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
         const double mnew = (tmax > m) ? tmax : m;
         const double alpha = exp2(m - mnew);
         double psum = 0.0;
-        for (int d = 0; d < D; ++d) { O[d] *= alpha; SL[d] *= alpha; }
+        for (int d = 0; d < D; ++d) O[d] *= alpha;
         for (int t = 0; t < tile; ++t) {
             int64_t j = jt * tile + t;
             pt[t] = ((causal && j > i) || j >= S) ? 0.0 : exp2(s[t] - mnew);   /* 2^(-inf) = 0 */
             psum += pt[t];
+            if (trace && j < S) { trace->s[j] = s[t]; trace->m[j] = mnew; }
         }
         if (p_round == 2) {
             /* MX-format P V: blocks of 32 keys of the tile */
             for (int t0 = 0; t0 < tile; t0 += 32) {
                 const int n = (tile - t0 < 32) ? tile - t0 : 32;
-                const int sc = block_e4m3_as_seen(pt + t0, n, ph_t + t0);
-                if (!slack) continue;
-                /* slack: the block's scale is decided by floor(max_j (s_j - m')); an implementation with binary32
-                 * scores may see that maximum on the other side of an integer when it lies within the score noise
-                 * of one, and then the whole block is rounded one binade coarser or finer: at most 2^-3 of each
-                 * p_j, or one subnormal step.  The row maximum itself gives exactly 0 on both sides. */
-                double xmax = -INFINITY, second = m - mnew;
-                for (int t = 0; t < tile; ++t) {
-                    const int64_t j = jt * tile + t;
-                    if ((causal && j > i) || j >= S) continue;
-                    const double x = s[t] - mnew;
-                    if (t >= t0 && t < t0 + n) { if (x > xmax) xmax = x; }
-                    else if (x > second) second = x;
-                }
-                if (xmax == -INFINITY) continue;
-                const double eps_x = ldexp(fabs(xmax + mnew) + fabs(mnew) + 1.0, -20);
-                const double frac = fabs(xmax - nearbyint(xmax));
-                const int scale_unsure = (xmax == 0.0) ? (second >= -eps_x) : (frac <= eps_x);
-                for (int t = t0; t < t0 + n; ++t) {
-                    const int64_t j = jt * tile + t;
-                    const double p = pt[t];
-                    if (!(p > 0.0)) continue;
-                    const double *vr = vseen + j * D;
-                    const double unit = ldexp(1.0, sc - 127);
-                    if (scale_unsure) {
-                        const double e = ldexp(p, -3) + ldexp(unit, -8);
-                        for (int d = 0; d < D; ++d) SL[d] += e * fabs(vr[d]);
-                        continue;
-                    }
-                    /* rounding flip of one element: spacing of E4M3 numbers at y = p / 2^scale (2^-9 for subnormals) */
-                    double y = p / unit;
-                    if (y >= 448.0) continue;                         /* clamped either way */
-                    int ex;
-                    (void)frexp(y, &ex);
-                    int quantum = (ex - 1) - 3;
-                    if (quantum < -9) quantum = -9;
-                    const double sp = ldexp(1.0, quantum);
-                    const double r = y / sp;
-                    const double dist = fabs(r - floor(r) - 0.5) * sp * unit;
-                    const double eps = ldexp(fabs(s[t]) + fabs(mnew) + 1.0, -20) * 0.6931471805599453 * p;
-                    if (dist <= eps)
-                        for (int d = 0; d < D; ++d) SL[d] += sp * unit * fabs(vr[d]);
-                }
+                const int bsc = block_e4m3_as_seen(pt + t0, n, alt_scale_shift(alt, jt * tile + t0, n), ph_t + t0);
+                for (int t = t0; alt && t < t0 + n; ++t)
+                    if (alt_neighbour(alt, jt * tile + t)) ph_t[t] = e4m3_other_neighbour(pt[t], bsc, ph_t[t]);
             }
             for (int t = 0; t < tile; ++t) {
                 const int64_t j = jt * tile + t;
@@ -610,28 +629,16 @@ static void attn_one_row(const uint16_t *qrow, const double *kseen_lo, const dou
                 if ((causal && j > i) || j >= S) continue; /* p = 2^(-inf) = 0 */
                 double p = pt[t];
                 double ph = p_round ? oracle_round_to_bf16(p) : p;
+                if (p_round && p > 0.0 && alt_neighbour(alt, j)) ph = other_grid_point(p, ph, bf16_quantum(p));
                 const uint16_t *vr = v + j * D;
                 for (int d = 0; d < D; ++d) O[d] += ph * (double)oracle_bf16_to_f32(vr[d]);
-                if (slack && p_round && p > 0.0) {
-                    int ex;
-                    (void)frexp(p, &ex);
-                    int quantum = (ex - 1) - 7;
-                    if (quantum < -133) quantum = -133;
-                    const double sp = ldexp(1.0, quantum);                 /* spacing of bf16 numbers at p */
-                    const double r = p / sp;
-                    const double dist = fabs(r - floor(r) - 0.5) * sp;     /* distance of p to the nearest midpoint */
-                    const double eps = ldexp(fabs(s[t]) + fabs(mnew) + 1.0, -20) * 0.6931471805599453 * p;
-                    if (dist <= eps)
-                        for (int d = 0; d < D; ++d) SL[d] += sp * fabs((double)oracle_bf16_to_f32(vr[d]));
-                }
             }
         }
         l = alpha * l + psum;
         m = mnew;
     }
     for (int d = 0; d < D; ++d) out[d] = (float)(O[d] / l);
-    if (slack)
-        for (int d = 0; d < D; ++d) slack[d] = (float)(SL[d] / l);
+    if (trace) { trace->m_final = m; trace->l_final = l; }
     free(s);
 }
 
@@ -645,6 +652,64 @@ static double *keys_as_seen(const uint16_t *k, int64_t n, int D, int fmt, int pe
     return out;
 }
 
+/* The keys (both formats) and, for the MX-format P V, the values of one kv head as the products see
+ * them, rows 0 .. n-1; and the group maxima of a coarser Step-2 granularity. */
+typedef struct { double *klo, *khi, *vseen; } head_view;
+static void head_view_free(head_view *h)
+{
+    if (h->khi != h->klo) free(h->khi);
+    free(h->klo);
+    free(h->vseen);
+    h->klo = h->khi = h->vseen = NULL;
+}
+/* imax: the last key any of the rows to come will look at. */
+static int head_view_make(head_view *h, const uint16_t *kh, const uint16_t *vh, int64_t S, int D, int tile, int64_t imax,
+                          int per_token, const float *kam, int hi_fmt, int lo_fmt, int p_round)
+{
+    h->vseen = NULL;
+    h->klo = keys_as_seen(kh, imax + 1, D, lo_fmt, per_token, kam);
+    h->khi = (hi_fmt == lo_fmt) ? h->klo : keys_as_seen(kh, imax + 1, D, hi_fmt, per_token, kam);
+    if (!h->klo || !h->khi) { head_view_free(h); return ORACLE_ERR_MEM; }
+    if (p_round == 2) {
+        /* every key of the tiles visited (whole 32-key blocks), but none past the end of the sequence */
+        int64_t nv = ((imax + tile) / tile) * tile;
+        if (nv > S) nv = S;
+        h->vseen = (double *)malloc(sizeof(double) * (size_t)nv * (size_t)D);
+        if (!h->vseen || oracle_values_as_seen_mxfp8(vh, S, D, nv, h->vseen, NULL) != ORACLE_OK) { head_view_free(h); return ORACLE_ERR_MEM; }
+    }
+    return ORACLE_OK;
+}
+static int attn_args_ok(const void *q, const void *k, const void *v, int B, int Hq, int Hkv, int64_t S, int D, int tile,
+                        int band, int sink, int per_token, int hi_fmt, int lo_fmt, int p_round)
+{
+    if (!q || !k || !v || sink < 0) return 0;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || S <= 0 || D <= 0 || D % 32 != 0 || D > 512) return 0;
+    if (tile <= 0 || band < 0) return 0;
+    if (p_round < 0 || p_round > 2 || (p_round == 2 && tile % 32 != 0)) return 0;
+    /* per_token: 0 = no Step 2; 1 = per-token; 2 = per-block (the rows of one tile of one head); 3 = per-tensor */
+    if (per_token < 0 || per_token > 3) return 0;
+    for (int f = 0; f < 2; ++f) {
+        int fm = f ? hi_fmt : lo_fmt;
+        if (fm != ORACLE_FMT_BF16 && !fmt_is_mx(fm)) return 0;
+    }
+    return 1;
+}
+/* Group maxima of all of Q and K for the per-block / per-tensor granularities (NULL, NULL otherwise). */
+static int group_maxima_make(const uint16_t *q, const uint16_t *k, int B, int Hq, int Hkv, int64_t S, int D, int tile,
+                             int per_token, float **qamax, float **kamax)
+{
+    *qamax = *kamax = NULL;
+    if (per_token < 2) return ORACLE_OK;
+    *qamax = (float *)malloc(sizeof(float) * (size_t)B * Hq * S);
+    *kamax = (float *)malloc(sizeof(float) * (size_t)B * Hkv * S);
+    if (!*qamax || !*kamax || oracle_group_amax(q, (int64_t)B * Hq, S, D, 1, per_token, tile, *qamax) != ORACLE_OK ||
+        oracle_group_amax(k, (int64_t)B * Hkv, S, D, 0, per_token, tile, *kamax) != ORACLE_OK) {
+        free(*qamax); free(*kamax); *qamax = *kamax = NULL;
+        return ORACLE_ERR_MEM;
+    }
+    return ORACLE_OK;
+}
+
 /*
  * q: [B, Hq, S, D] bf16; k, v: [B, Hkv, S, D] bf16 (contiguous, D innermost; q head h uses kv
  * head h / (Hq/Hkv)).  rows: n_rows triples (b, hq, i).  out: [n_rows, D] float, in the order
@@ -654,35 +719,18 @@ static double *keys_as_seen(const uint16_t *k, int64_t n, int D, int fmt, int pe
 int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq,
                             int Hkv, int64_t S, int D, int tile, int band, int sink, int causal,
                             int per_token, int hi_fmt, int lo_fmt, int p_round, const int64_t *rows,
-                            int64_t n_rows, float *out, float *slack)
+                            int64_t n_rows, float *out)
 {
-    if (!q || !k || !v || !out || (!rows && n_rows > 0)) return ORACLE_ERR_ARG;
-    if (sink < 0) return ORACLE_ERR_ARG;
-    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || S <= 0 || D <= 0 || D % 32 != 0 || D > 512)
-        return ORACLE_ERR_ARG;
-    if (tile <= 0 || band < 0) return ORACLE_ERR_ARG;
-    if (p_round < 0 || p_round > 2 || (p_round == 2 && tile % 32 != 0)) return ORACLE_ERR_ARG;
-    for (int f = 0; f < 2; ++f) {
-        int fm = f ? hi_fmt : lo_fmt;
-        if (fm != ORACLE_FMT_BF16 && !fmt_is_mx(fm)) return ORACLE_ERR_ARG;
-    }
+    if (!out || (!rows && n_rows > 0)) return ORACLE_ERR_ARG;
+    if (!attn_args_ok(q, k, v, B, Hq, Hkv, S, D, tile, band, sink, per_token, hi_fmt, lo_fmt, p_round)) return ORACLE_ERR_ARG;
     for (int64_t r = 0; r < n_rows; ++r) {
         if (rows[3 * r] < 0 || rows[3 * r] >= B || rows[3 * r + 1] < 0 || rows[3 * r + 1] >= Hq ||
             rows[3 * r + 2] < 0 || rows[3 * r + 2] >= S)
             return ORACLE_ERR_ARG;
     }
     const int group = Hq / Hkv;
-    /* per_token: 0 = no Step 2; 1 = per-token; 2 = per-block (the rows of one tile of one head); 3 = per-tensor */
-    if (per_token < 0 || per_token > 3) return ORACLE_ERR_ARG;
-    float *qamax = NULL, *kamax = NULL;
-    if (per_token >= 2) {
-        qamax = (float *)malloc(sizeof(float) * (size_t)B * Hq * S);
-        kamax = (float *)malloc(sizeof(float) * (size_t)B * Hkv * S);
-        if (!qamax || !kamax || oracle_group_amax(q, (int64_t)B * Hq, S, D, 1, per_token, tile, qamax) != ORACLE_OK ||
-            oracle_group_amax(k, (int64_t)B * Hkv, S, D, 0, per_token, tile, kamax) != ORACLE_OK) {
-            free(qamax); free(kamax); return ORACLE_ERR_MEM;
-        }
-    }
+    float *qamax, *kamax;
+    if (group_maxima_make(q, k, B, Hq, Hkv, S, D, tile, per_token, &qamax, &kamax) != ORACLE_OK) return ORACLE_ERR_MEM;
     int64_t r0 = 0;
     while (r0 < n_rows) {
         /* maximal run of rows sharing (b, kv head) */
@@ -696,35 +744,208 @@ int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t
         const uint16_t *kh = k + ((int64_t)b * Hkv + hkv) * S * D;
         const uint16_t *vh = v + ((int64_t)b * Hkv + hkv) * S * D;
         const float *kam = kamax ? kamax + ((int64_t)b * Hkv + hkv) * S : NULL;
-        double *klo = keys_as_seen(kh, imax + 1, D, lo_fmt, per_token, kam);
-        double *khi = (hi_fmt == lo_fmt) ? klo : keys_as_seen(kh, imax + 1, D, hi_fmt, per_token, kam);
-        if (!klo || !khi) { free(klo); if (khi != klo) free(khi); free(qamax); free(kamax); return ORACLE_ERR_MEM; }
-        double *vseen = NULL;
-        if (p_round == 2) {
-            /* every key of the tiles visited (whole 32-key blocks), but none past the end of the sequence */
-            int64_t nv = ((imax + tile) / tile) * tile;
-            if (nv > S) nv = S;
-            vseen = (double *)malloc(sizeof(double) * (size_t)nv * (size_t)D);
-            if (!vseen || oracle_values_as_seen_mxfp8(vh, S, D, nv, vseen, NULL) != ORACLE_OK) {
-                free(vseen); free(klo); if (khi != klo) free(khi); free(qamax); free(kamax); return ORACLE_ERR_MEM;
-            }
+        head_view hv;
+        if (head_view_make(&hv, kh, vh, S, D, tile, imax, per_token, kam, hi_fmt, lo_fmt, p_round) != ORACLE_OK) {
+            free(qamax); free(kamax); return ORACLE_ERR_MEM;
         }
 #pragma omp parallel for schedule(dynamic, 1)
         for (int64_t r = r0; r < r1; ++r) {
             const int64_t hq = rows[3 * r + 1], i = rows[3 * r + 2];
             const uint16_t *qrow = q + (((int64_t)b * Hq + hq) * S + i) * D;
             const float qam = qamax ? qamax[((int64_t)b * Hq + hq) * S + i] : -1.0f;
-            attn_one_row(qrow, klo, khi, vh, vseen, i, S, D, tile, band, sink, causal, per_token, qam, hi_fmt, lo_fmt, p_round, out + r * D,
-                         slack ? slack + r * D : NULL);
+            attn_one_row(qrow, hv.klo, hv.khi, vh, hv.vseen, i, S, D, tile, band, sink, causal, per_token, qam, hi_fmt, lo_fmt, p_round,
+                         out + r * D, NULL, NULL);
         }
-        if (khi != klo) free(khi);
-        free(klo);
-        free(vseen);
+        head_view_free(&hv);
         r0 = r1;
     }
     free(qamax);
     free(kamax);
     return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Parity-test support: which rounding decisions of a row are open, and the row with some of     */
+/* them taken the other way.  Test infrastructure; no part of the method.                        */
+/* ------------------------------------------------------------------------------------------ */
+/* Score noise allowed to an implementation with binary32 scores, in units of the score: the score
+ * and the running maximum are binary32 numbers that went through a handful of roundings each
+ * (accumulation from -m, the moves of the maximum), so the exponent s - m' carries an error of a few
+ * units in the last place of max(|s|, |m'|): 2^-22 (|s| + |m'| + 1) is two to four such units.
+ * (Measured: the decisions the MI355X kernel takes the other way need at most a quarter of it.) */
+static double score_noise(double s, double m) { return ldexp(fabs(s) + fabs(m) + 1.0, -22); }
+
+/* One row (b, hq, i), everything else as oracle_dma_attn_rows_ex.
+ * alt_key / alt_kind [n_alt]: decisions to take the other way (ORACLE_ALT_*); out [D] receives the row.
+ * With cand_* non-NULL the open decisions of the row as the method rounds it (n_alt must be 0) are listed, largest
+ * effect first: cand_key / cand_kind [max_cand]; cand_move [max_cand, D] = how taking that one decision the other way
+ * moves out[d] (to first order: the row sum does not change, decisions do not interact except inside one MX block);
+ * cand_margin [max_cand] = how much of the noise allowance the decision uses (0: p sits on the midpoint; 1: it is only
+ * just open); *n_cand = how many there are with max_d |move| >= min_move (all of them counted, the first max_cand listed).
+ * A decision is open when
+ *   bf16 P (p_round = 1): p_j lies within score_noise * ln2 * p_j of the midpoint of its two bf16 neighbours;
+ *   MX-format P V (p_round = 2): the same against the E4M3 grid of the block's scale (kind NEIGHBOUR); and the
+ *   block's scale itself when the block maximum of s - m' lies within score_noise of an integer (one binade
+ *   finer if it may fall below that integer: SCALE_DOWN; coarser if it may reach it: SCALE_UP), or, for the block
+ *   that holds the row maximum (s - m' = 0 exactly), when another key of the row comes that close to the maximum. */
+int oracle_dma_attn_row_alt(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq, int Hkv, int64_t S,
+                            int D, int tile, int band, int sink, int causal, int per_token, int hi_fmt, int lo_fmt,
+                            int p_round, int64_t b, int64_t hq, int64_t i, const int64_t *alt_key,
+                            const int32_t *alt_kind, int64_t n_alt, float *out, double min_move, int64_t max_cand,
+                            int64_t *cand_key, int32_t *cand_kind, double *cand_move, double *cand_margin, int64_t *n_cand)
+{
+    if (!out || n_alt < 0 || (n_alt > 0 && (!alt_key || !alt_kind))) return ORACLE_ERR_ARG;
+    if (!attn_args_ok(q, k, v, B, Hq, Hkv, S, D, tile, band, sink, per_token, hi_fmt, lo_fmt, p_round)) return ORACLE_ERR_ARG;
+    if (b < 0 || b >= B || hq < 0 || hq >= Hq || i < 0 || i >= S) return ORACLE_ERR_ARG;
+    const int want_cand = cand_key != NULL;
+    if (want_cand && (!cand_kind || !cand_move || !cand_margin || !n_cand || max_cand < 0 || n_alt != 0 || p_round == 0)) return ORACLE_ERR_ARG;
+    const int64_t hkv = hq / (Hq / Hkv);
+    const int64_t imax = causal ? i : S - 1;
+    const uint16_t *kh = k + ((int64_t)b * Hkv + hkv) * S * D;
+    const uint16_t *vh = v + ((int64_t)b * Hkv + hkv) * S * D;
+    float *qamax, *kamax;
+    if (group_maxima_make(q, k, B, Hq, Hkv, S, D, tile, per_token, &qamax, &kamax) != ORACLE_OK) return ORACLE_ERR_MEM;
+    head_view hv;
+    if (head_view_make(&hv, kh, vh, S, D, tile, imax, per_token, kamax ? kamax + ((int64_t)b * Hkv + hkv) * S : NULL, hi_fmt,
+                       lo_fmt, p_round) != ORACLE_OK) {
+        free(qamax); free(kamax); return ORACLE_ERR_MEM;
+    }
+    const uint16_t *qrow = q + (((int64_t)b * Hq + hq) * S + i) * D;
+    const float qam = qamax ? qamax[((int64_t)b * Hq + hq) * S + i] : -1.0f;
+    const row_alts alt = { n_alt, alt_key, alt_kind };
+    const int64_t n_keys = ((imax / tile) + 1) * tile < S ? ((imax / tile) + 1) * tile : S;   /* keys of the tiles visited */
+    row_trace tr = { NULL, NULL, 0.0, 0.0 };
+    int rc = ORACLE_OK;
+    if (want_cand) {
+        tr.s = (double *)malloc(sizeof(double) * (size_t)n_keys * 2);
+        if (!tr.s) rc = ORACLE_ERR_MEM;
+        tr.m = tr.s + n_keys;
+    }
+    if (rc == ORACLE_OK)
+        attn_one_row(qrow, hv.klo, hv.khi, vh, hv.vseen, i, S, D, tile, band, sink, causal, per_token, qam, hi_fmt, lo_fmt, p_round,
+                     out, n_alt ? &alt : NULL, want_cand ? &tr : NULL);
+    if (rc == ORACLE_OK && want_cand) {
+        /* the open decisions, from the trace: (key, kind, largest |move|), then the largest ones in full */
+        int64_t found = 0, cap = 64;
+        int64_t *ck = (int64_t *)malloc(sizeof(int64_t) * (size_t)cap);
+        int32_t *cn = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap);
+        double *cm = (double *)malloc(sizeof(double) * (size_t)cap * (size_t)D);
+        double *cr = (double *)malloc(sizeof(double) * (size_t)cap);
+        double *mv = (double *)malloc(sizeof(double) * (size_t)D);
+        double pblk[32], seen0[32], seen1[32];
+        for (int64_t j0 = 0; j0 < n_keys && ck && cn && cm && cr && mv; j0 += 32) {
+            /* keys j0 .. j0+nb-1: for the MX-format P V (tile % 32 == 0) one block of one key tile, sharing m' */
+            const int nb = (int)((n_keys - j0 < 32) ? n_keys - j0 : 32);
+            for (int pass = 0; pass < 2; ++pass) {            /* pass 0: single probabilities; pass 1: the block's scale */
+                if (pass == 1 && p_round != 2) break;
+                int bsc = 0, shift = 0;
+                double used = 0.0;                              /* share of the noise allowance this decision needs */
+                const double mblk = tr.m[j0];
+                const double carry = exp2(mblk - tr.m_final) / tr.l_final;     /* what one unit of this tile's numerator is worth in out */
+                if (p_round == 2) {
+                    double xmax = -INFINITY, second = -INFINITY;
+                    for (int t = 0; t < 32; ++t) pblk[t] = (t < nb && tr.s[j0 + t] > -INFINITY) ? exp2(tr.s[j0 + t] - mblk) : 0.0;
+                    bsc = block_e4m3_as_seen(pblk, 32, 0, seen0);
+                    if (pass == 1) {
+                        for (int t = 0; t < nb; ++t)
+                            if (tr.s[j0 + t] - mblk > xmax) xmax = tr.s[j0 + t] - mblk;
+                        if (xmax == -INFINITY) continue;
+                        /* the largest s - m' of the row outside this block, among the keys seen so far and the old maximum */
+                        const int64_t tile0 = (j0 / tile) * tile, tile1 = (tile0 + tile < n_keys) ? tile0 + tile : n_keys;
+                        for (int64_t j = 0; j < tile1; ++j)
+                            if ((j < j0 || j >= j0 + nb) && tr.s[j] - mblk > second) second = tr.s[j] - mblk;
+                        const double noise = score_noise(xmax + mblk, mblk);
+                        if (xmax == 0.0) { shift = (second >= -noise) ? -1 : 0; used = -second / noise; }
+                        else if (xmax - floor(xmax) <= noise) { shift = -1; used = (xmax - floor(xmax)) / noise; }
+                        else if (ceil(xmax) - xmax <= noise) { shift = 1; used = (ceil(xmax) - xmax) / noise; }
+                        if (shift == 0) continue;
+                        (void)block_e4m3_as_seen(pblk, 32, shift, seen1);
+                    }
+                }
+                for (int t = 0; t < (pass == 0 ? nb : 1); ++t) {
+                    const int64_t j = j0 + t;
+                    int32_t kind;
+                    double big = 0.0;
+                    if (pass == 1) {
+                        kind = shift > 0 ? ORACLE_ALT_SCALE_UP : ORACLE_ALT_SCALE_DOWN;
+                        for (int d = 0; d < D; ++d) {
+                            double acc = 0.0;
+                            for (int u = 0; u < nb; ++u) acc += (seen1[u] - seen0[u]) * hv.vseen[(j0 + u) * D + d];
+                            mv[d] = acc * carry;
+                            if (fabs(mv[d]) > big) big = fabs(mv[d]);
+                        }
+                    } else {
+                        if (!(tr.s[j] > -INFINITY)) continue;
+                        const double mj = tr.m[j];
+                        const double p = exp2(tr.s[j] - mj);
+                        if (!(p > 0.0)) continue;
+                        const double carry_j = exp2(mj - tr.m_final) / tr.l_final;
+                        double rounded, other, spacing;
+                        if (p_round == 2) {
+                            const double y = ldexp(p, 127 - bsc);
+                            if (y >= 448.0) continue;
+                            spacing = ldexp(1.0, e4m3_quantum(y) + bsc - 127);
+                            rounded = seen0[t];
+                            other = e4m3_other_neighbour(p, bsc, rounded);
+                        } else {
+                            spacing = ldexp(1.0, bf16_quantum(p));
+                            rounded = oracle_round_to_bf16(p);
+                            other = other_grid_point(p, rounded, bf16_quantum(p));
+                        }
+                        if (other == rounded) continue;
+                        const double r = p / spacing;
+                        const double to_midpoint = fabs(r - floor(r) - 0.5) * spacing;
+                        const double allowance = score_noise(tr.s[j], mj) * 0.6931471805599453 * p;
+                        if (to_midpoint > allowance) continue;
+                        used = to_midpoint / allowance;
+                        kind = ORACLE_ALT_NEIGHBOUR;
+                        for (int d = 0; d < D; ++d) {
+                            const double vv = (p_round == 2) ? hv.vseen[j * D + d] : (double)oracle_bf16_to_f32(vh[j * D + d]);
+                            mv[d] = (other - rounded) * vv * carry_j;
+                            if (fabs(mv[d]) > big) big = fabs(mv[d]);
+                        }
+                    }
+                    if (big < min_move) continue;
+                    if (found == cap) {
+                        cap *= 2;
+                        ck = (int64_t *)realloc(ck, sizeof(int64_t) * (size_t)cap);
+                        cn = (int32_t *)realloc(cn, sizeof(int32_t) * (size_t)cap);
+                        cm = (double *)realloc(cm, sizeof(double) * (size_t)cap * (size_t)D);
+                        cr = (double *)realloc(cr, sizeof(double) * (size_t)cap);
+                        if (!ck || !cn || !cm || !cr) break;
+                    }
+                    ck[found] = j; cn[found] = kind; cr[found] = used;
+                    memcpy(cm + found * D, mv, sizeof(double) * (size_t)D);
+                    ++found;
+                }
+            }
+        }
+        if (!ck || !cn || !cm || !cr || !mv) {
+            rc = ORACLE_ERR_MEM;
+        } else {
+            /* selection sort of the first max_cand by largest |move| */
+            *n_cand = found;
+            for (int64_t a = 0; a < found && a < max_cand; ++a) {
+                int64_t best = -1;
+                double bestv = -1.0;
+                for (int64_t c2 = 0; c2 < found; ++c2) {
+                    if (cn[c2] == 0) continue;
+                    double big = 0.0;
+                    for (int d = 0; d < D; ++d) if (fabs(cm[c2 * D + d]) > big) big = fabs(cm[c2 * D + d]);
+                    if (big > bestv) { bestv = big; best = c2; }
+                }
+                cand_key[a] = ck[best]; cand_kind[a] = cn[best]; cand_margin[a] = cr[best];
+                memcpy(cand_move + a * D, cm + best * D, sizeof(double) * (size_t)D);
+                cn[best] = 0;                                  /* taken */
+            }
+        }
+        free(ck); free(cn); free(cm); free(cr); free(mv);
+    }
+    free(tr.s);
+    head_view_free(&hv);
+    free(qamax);
+    free(kamax);
+    return rc;
 }
 
 /* Alg. 1 as printed: causal, no sink window. */
@@ -733,7 +954,7 @@ int oracle_dma_attn_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v
                          int p_round, const int64_t *rows, int64_t n_rows, float *out)
 {
     return oracle_dma_attn_rows_ex(q, k, v, B, Hq, Hkv, S, D, tile, band, 0, 1, 0, hi_fmt, lo_fmt, p_round, rows,
-                                   n_rows, out, NULL);
+                                   n_rows, out);
 }
 
 /* ------------------------------------------------------------------------------------------ */

@@ -141,8 +141,17 @@ def round_bf16_nearest_of_two(p: np.ndarray) -> np.ndarray:
     return out
 
 
+def other_bf16_neighbour(p: np.ndarray, rounded: np.ndarray) -> np.ndarray:
+    """For positive doubles p and their bf16 roundings: the bf16 number on the other side of p (p itself if exact)."""
+    p = np.asarray(p, dtype=np.float64)
+    _, ex = np.frexp(p)
+    q = np.maximum(np.exp2((ex - 1 - 7).astype(np.float64)), 2.0 ** -133)
+    lo = np.floor(p / q) * q
+    return np.where(lo == p, rounded, np.where(rounded == lo, lo + q, lo))
+
+
 def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p_round=True, sink=0, causal=True,
-                  score_dtype=np.float64, per_token=False, pv_mx=False):
+                  score_dtype=np.float64, per_token=False, pv_mx=False, binary32_exponent=False, other_way=None, probe=None):
     """Per-element rewrite of the diagonal-tiled attention for q[Hq,S,D], k,v[Hkv,S,D] (one batch).
 
     For every visible pair (i, j) the score comes from the format of the tile pair (i // tile, j // tile):
@@ -151,7 +160,15 @@ def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p
     rounded to bf16, otherwise it is a plain base-2 row softmax.  causal=False: every key is visible.
     score_dtype=np.float32 rounds every score to binary32 first (what an implementation with binary32 scores sees).
     pv_mx: instead of the bf16 rounding, every block of 32 consecutive keys (aligned to multiples of 32, masked keys
-    and keys past the end counting as zeros) of a row's probabilities, and of every column of V, is an MXFP8-E4M3 block."""
+    and keys past the end counting as zeros) of a row's probabilities, and of every column of V, is an MXFP8-E4M3 block.
+    binary32_exponent: the probability that gets rounded is formed the way a binary32 implementation forms it (the row
+    sum still adds the double-precision p, so only rounding decisions change).  True: the running maximum and the
+    difference s - m' rounded to binary32, then 2^x rounded to binary32.  "chain": a running binary32 accumulator per
+    key that starts at minus the binary32 running maximum and adds the exact partial product of one MX block after
+    the other, rounding after each; the running maximum itself is a binary32 number that moves by binary32 additions;
+    the accumulator is shifted by a binary32 subtraction when the maximum moves; then 2^x rounded to binary32.
+    other_way: {(h, i): [keys]}: those probabilities of row i of head h take the OTHER of their two bf16 neighbours.
+    probe: a dict that receives, per (h, i), the rounded probabilities of the row as they enter the second product."""
     Hq, S, D = q_bits.shape
     Hkv = k_bits.shape[0]
     g = Hq // Hkv
@@ -173,7 +190,13 @@ def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p
         s_lo = q_lo @ k_lo.T
         ti = np.arange(S)[:, None] // tile
         tj = np.arange(S)[None, :] // tile
-        s = np.where((np.abs(ti - tj) < band) | (tj < sink), s_hi, s_lo).astype(score_dtype).astype(np.float64)
+        use_hi = (np.abs(ti - tj) < band) | (tj < sink)
+        s = np.where(use_hi, s_hi, s_lo).astype(score_dtype).astype(np.float64)
+        if binary32_exponent == "chain":
+            nb = D // 32
+            parts = np.where(use_hi[:, :, None],
+                             np.einsum("ibd,jbd->ijb", q_hi.reshape(S, nb, 32), k_hi.reshape(S, nb, 32)),
+                             np.einsum("ibd,jbd->ijb", q_lo.reshape(S, nb, 32), k_lo.reshape(S, nb, 32)))
         for i in range(S):
             nk = i + 1 if causal else S                  # keys this row sees
             si = s[i, :nk]
@@ -187,15 +210,39 @@ def dma_attention(q_bits, k_bits, v_bits, *, tile, band, hi="e4m3", lo="e2m1", p
             mj = run[np.arange(nk) // tile]              # maximum in force when key j was processed
             mfin = run[-1]
             p_at = np.exp2(si - mj)
+            p_seen = p_at                                # the value the rounding decision is taken on
+            if binary32_exponent == "chain":
+                x32 = np.zeros(nk, dtype=np.float32)
+                m_run, first = np.float32(0.0), True
+                for t in range(nt):
+                    j0, j1 = t * tile, min((t + 1) * tile, nk)
+                    acc = np.full(j1 - j0, -m_run, dtype=np.float32)
+                    for b in range(nb):
+                        acc = (acc.astype(np.float64) + parts[i, j0:j1, b]).astype(np.float32)
+                    delta = acc.max() if first else max(acc.max(), np.float32(0.0))
+                    if delta != 0:
+                        acc = (acc - np.float32(delta)).astype(np.float32)
+                        m_run = np.float32(m_run + np.float32(delta))
+                    x32[j0:j1] = acc
+                    first = False
+                p_seen = np.exp2(x32.astype(np.float64)).astype(np.float32).astype(np.float64)
+            elif binary32_exponent:
+                x32 = (si.astype(np.float32) - mj.astype(np.float32)).astype(np.float32)
+                p_seen = np.exp2(x32.astype(np.float64)).astype(np.float32).astype(np.float64)
             if pv_mx:
                 p_hat = np.zeros(nk)
                 for b0 in range(0, nk, 32):
                     blk = np.zeros(32)
                     n = min(32, nk - b0)
-                    blk[:n] = p_at[b0:b0 + n]
+                    blk[:n] = p_seen[b0:b0 + n]
                     p_hat[b0:b0 + n] = quantize_block(blk, "e4m3")[2][:n]
             else:
-                p_hat = round_bf16_nearest_of_two(p_at)
+                p_hat = round_bf16_nearest_of_two(p_seen)
+                if other_way and (h, i) in other_way:
+                    jj = np.asarray(other_way[(h, i)], dtype=np.int64)
+                    p_hat[jj] = other_bf16_neighbour(p_at[jj], p_hat[jj])
+            if probe is not None:
+                probe[(h, i)] = p_hat.copy()
             w_num = p_hat * np.exp2(mj - mfin)
             w_den = (p_at * np.exp2(mj - mfin)).sum()
             out[h, i] = (w_num @ v[h // g, :nk]) / w_den

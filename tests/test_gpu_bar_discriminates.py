@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import parity
 import test_oracle_mutations as tm
 from paper_2604_03950_amd import workloads as wl
 
@@ -33,16 +34,18 @@ def gpu_outputs():
 
 
 def within_bar(oracle, cases):
+    """The bar of tests/parity.py, with `oracle` (a private copy) as the reference."""
     ok = True
     for w, q, k, v, out in cases:
         rows = oracle.all_rows(w.B, w.Hq, w.S)
-        want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=w.tile, band=1, sink=1, with_slack=True)
+        kw = dict(tile=w.tile, band=1, sink=1)
+        want = oracle.dma_attn_rows(q, k, v, rows, **kw)
         got = out[rows[:, 0], rows[:, 1], rows[:, 2]]
-        err = np.abs(got - want)
-        rel = float(np.linalg.norm(got - want) / np.linalg.norm(want))
-        excess = float(np.max(err - slack))
-        print(f"    {w.name}: max-abs beyond slack {excess:.2e}, rel-L2 {rel:.2e}", flush=True)
-        ok = ok and excess <= MAX_ABS and rel <= REL_L2            # a NaN on either side compares false: outside the bar
+        try:
+            parity.compare(got, want, rows, f"    {w.name}", oracle, (q, k, v), kw, max_abs=MAX_ABS, rel_l2=REL_L2)
+        except AssertionError as e:            # a NaN on either side fails the comparison too
+            print(f"    {w.name}: outside the bar: {str(e)[:200]}", flush=True)
+            ok = False
     return ok
 
 

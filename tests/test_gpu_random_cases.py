@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 import torch
 
+import parity
 from paper_2604_03950_amd import workloads as wl
 
 MAX_ABS, REL_L2 = 2e-3, 1e-3
@@ -64,13 +65,11 @@ def test_random_cases(dma, oracle, seed):
         if len(rows) > 1500:
             pick = np.random.Generator(np.random.Philox(100 * seed + it)).choice(len(rows), 1500, replace=False)
             rows = oracle.sort_rows(rows[np.sort(pick)])
-        want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=tile, band=band, hi_fmt=fm[hi][1], lo_fmt=fm[lo][1], sink=sink,
-                                           causal=causal, per_token=(gran if per_token else False), pv_mx=pv_mx, with_slack=True)
+        kw = dict(tile=tile, band=band, hi_fmt=fm[hi][1], lo_fmt=fm[lo][1], sink=sink, causal=causal,
+                  per_token=(gran if per_token else False), pv_mx=pv_mx)
+        want = oracle.dma_attn_rows(q, k, v, rows, **kw)
         got = out.cpu().numpy()[rows[:, 0], rows[:, 1], rows[:, 2]].astype(np.float64)
-        assert np.all(np.isfinite(got)), what
-        err = np.abs(got - want)
-        rel = float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
-        assert float(np.max(err - slack)) <= MAX_ABS and rel <= REL_L2, (what, float(err.max()), rel)
+        parity.compare(got, want, rows, "    result", oracle, (q, k, v), kw, max_abs=MAX_ABS, rel_l2=REL_L2)
 
 
 @pytest.mark.gpu
@@ -105,9 +104,7 @@ def test_random_midsize_cases(dma, oracle, seed):
         rows = oracle.all_rows(w.B, w.Hq, w.S)
         pick = np.random.Generator(np.random.Philox(1000 * seed + it)).choice(len(rows), 600, replace=False)
         rows = oracle.sort_rows(rows[np.sort(pick)])
-        want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=tile, band=band, sink=sink, causal=causal, per_token=per_token,
-                                           pv_mx=pv_mx, with_slack=True)
+        kw = dict(tile=tile, band=band, sink=sink, causal=causal, per_token=per_token, pv_mx=pv_mx)
+        want = oracle.dma_attn_rows(q, k, v, rows, **kw)
         got = out.cpu().numpy()[rows[:, 0], rows[:, 1], rows[:, 2]].astype(np.float64)
-        err = np.abs(got - want)
-        rel = float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
-        assert float(np.max(err - slack)) <= MAX_ABS and rel <= REL_L2, (what, float(err.max()), rel)
+        parity.compare(got, want, rows, "    result", oracle, (q, k, v), kw, max_abs=MAX_ABS, rel_l2=REL_L2)

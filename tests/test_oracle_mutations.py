@@ -23,7 +23,7 @@ MUTATIONS = [
     ("window one tile too wide", r"dist < \(int64_t\)band", "dist <= (int64_t)band", "mixed"),
     ("rescale factor inverted", r"exp2\(m - mnew\)", "exp2(mnew - m)", "skeleton"),
     ("running sum not rescaled", r"l = alpha \* l \+ psum;", "l = l + psum;", "skeleton"),
-    ("accumulator not rescaled", r"\{ O\[d\] \*= alpha; SL\[d\] \*= alpha; \}", "{ SL[d] *= alpha; }", "skeleton"),
+    ("accumulator not rescaled", r"for \(int d = 0; d < D; \+\+d\) O\[d\] \*= alpha;", ";", "skeleton"),
     ("e_max of E2M1 off by one", r"fmt == ORACLE_FMT_E2M1 \? 2 :", "fmt == ORACLE_FMT_E2M1 ? 3 :", "e8m0"),
     ("e_max of E4M3 off by one", r"ORACLE_FMT_E5M2 \? 15 : 8;", "ORACLE_FMT_E5M2 ? 15 : 7;", "e8m0"),
     ("softmax factor 1/D instead of 1/sqrt(D)", r"const double c = 1\.4426950408889634074 / sqrt\(\(double\)D\);",
@@ -55,6 +55,10 @@ MUTATIONS = [
     ("E4M3 mantissa carry lost", r"if \(m == 8\) \{ e \+= 1; m = 0; \}", "if (m == 8) { m = 7; }", "e4m3_brute"),
     ("shared scale from blocks of 16", r"float v = oracle_bf16_to_f32\(x\[blk \* 32 \+ t\]\);\n            if \(is_query\) \{\n                volatile float prod = v \* c;     /\* one binary32 multiply, rounded once \*/",
      "float v = oracle_bf16_to_f32(x[blk * 32 + t % 16]);\n            if (is_query) {\n                volatile float prod = v * c;     /* one binary32 multiply, rounded once */", "tiny_quant"),
+    ("noise allowance of the open decisions four times larger", r"ldexp\(fabs\(s\) \+ fabs\(m\) \+ 1\.0, -22\)",
+     "ldexp(fabs(s) + fabs(m) + 1.0, -20)", "open"),
+    ("a decision taken the other way lands on the same neighbour", r"return \(rounded == lower\) \? lower \+ ldexp\(1\.0, quantum\) : lower;",
+     "return rounded;", "other_way"),
     ("sign of an underflowed element dropped", r"int neg = signbit\(xs\[t\]\) \? 1 : 0;", "int neg = (xs[t] < 0.0f && fabsf(xs[t]) > 0x1p-20f) ? 1 : 0;", "edge_blocks"),
 ]
 
@@ -95,6 +99,10 @@ def run_pin(which, oracle, tiny):
         pins.test_noncausal_mixed_tiles_match_per_element_rewrite(oracle, tiny, 1, 0, True)
     elif which == "token":
         pins.test_token_scale_fixed_points(oracle)
+    elif which == "open":
+        pins.test_open_decisions_cover_a_binary32_implementation_and_little_more(oracle)
+    elif which == "other_way":
+        pins.test_row_with_decisions_taken_the_other_way_matches_per_element_rewrite(oracle, tiny)
     elif which == "pv_mx":
         pins.test_mx_pv_matches_per_element_rewrite(oracle, tiny, 1, True, 256)
     else:
@@ -131,7 +139,7 @@ def tiny():
 def test_unmodified_copy_passes_the_pins_used_here(tmp_path, tiny):
     oracle = private_oracle(tmp_path, "oracle_copy")
     for which in ("skeleton", "mixed", "all_high", "e8m0", "prescale", "bf16", "e2m1_grid", "e2m1_paper", "e5m2", "noncausal",
-                  "token", "pv_mx", "packing", "saturating", "e4m3_fixed", "e4m3_brute", "tiny_quant", "edge_blocks"):
+                  "token", "pv_mx", "packing", "saturating", "e4m3_fixed", "e4m3_brute", "tiny_quant", "edge_blocks", "other_way"):
         run_pin(which, oracle, tiny)
 
 

@@ -470,24 +470,111 @@ def test_e5m2_high_format_in_attention(oracle, tiny):
     assert np.max(np.abs(got - want)) < 2e-6
 
 
-def test_rounding_slack_covers_binary32_scores(oracle):
-    """The slack the oracle reports must cover what changes when every score is first rounded to binary32 (which
-    flips the bf16 rounding of probabilities that sit on a midpoint), and must be zero for most elements."""
-    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=512, Hq=2, Hkv=1)
+def test_row_with_decisions_taken_the_other_way_matches_per_element_rewrite(oracle, tiny):
+    """oracle.dma_attn_row_alt: named probabilities take the other of their two bf16 neighbours; against the per-element
+    rewrite, which picks the other neighbour by comparing the two.  No decision named = the plain row."""
+    w = wl.small_variant(wl.CONFIGS["heavy_tail_16k"], S=256, Hq=2, Hkv=2)      # no channel outliers: a softmax with several sizeable terms
     q, k, v = wl.generate(w)
+    probe = {}
+    brute.dma_attention(q[0], k[0], v[0], tile=w.tile, band=1, probe=probe)
+    for h, i in ((0, 3), (1, 70), (0, 200), (1, 255)):
+        keys = sorted(int(j) for j in np.argsort(-probe[(h, i)])[:4])     # the row's largest probabilities (one of them is 1)
+        got = oracle.dma_attn_row_alt(q, k, v, (0, h, i), [(j, oracle.ALT_NEIGHBOUR) for j in keys], tile=w.tile, band=1)
+        want = brute.dma_attention(q[0], k[0], v[0], tile=w.tile, band=1, other_way={(h, i): keys})[h, i]
+        plain = oracle.dma_attn_rows(q, k, v, [(0, h, i)], tile=w.tile, band=1)[0]
+        assert np.max(np.abs(got - want)) < 2e-6
+        assert np.array_equal(oracle.dma_attn_row_alt(q, k, v, (0, h, i), [], tile=w.tile, band=1), plain)
+        assert np.max(np.abs(got - plain)) > 0          # the named decisions do change the row
+    # a probability that is a bf16 number has no other neighbour: row 0 attends to key 0 with p = 1
+    assert np.array_equal(oracle.dma_attn_row_alt(q, k, v, (0, 0, 0), [(0, oracle.ALT_NEIGHBOUR)], tile=w.tile, band=1),
+                          oracle.dma_attn_rows(q, k, v, [(0, 0, 0)], tile=w.tile, band=1)[0])
+    assert oracle.round_to_bf16(0.501953125) == 0.5           # a tie goes to the even neighbour
+
+
+def test_open_decisions_cover_a_binary32_implementation_and_little_more(oracle):
+    """The decisions the oracle calls open (oracle.dma_attn_row_candidates) against an emulation that forms 2^(s - m') the
+    way a binary32 implementation does (a binary32 accumulator per key that starts at minus the running maximum and
+    is rounded after every MX block, a running maximum moved by binary32 additions, 2^x rounded to binary32):
+    lower side: every probability the emulation rounds differently is among them, and their first-order effect predicts
+    the emulation's output; upper side: they are not many more than the emulation's own flips -- a noise allowance
+    four times as generous would list about four times as many and fail here."""
+    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=384, Hq=2, Hkv=1)
+    q, k, v = wl.generate(w)
+    kw = dict(tile=128, band=2)
+    p64, p32 = {}, {}
+    brute.dma_attention(q[0], k[0], v[0], probe=p64, **kw)
+    out32 = brute.dma_attention(q[0], k[0], v[0], probe=p32, score_dtype=np.float32, binary32_exponent="chain", **kw)
+    n_flipped = n_open = 0
+    for h in range(w.Hq):
+        for i in range(w.S):
+            out, cands, moves, n_all, _ = oracle.dma_attn_row_candidates(q, k, v, (0, h, i), min_move=0.0, max_cand=4096, **kw)
+            assert n_all == len(cands)
+            flipped = set(np.flatnonzero(p64[(h, i)] != p32[(h, i)]).tolist())
+            open_keys = {j for j, kind in cands if kind == oracle.ALT_NEIGHBOUR}
+            assert flipped <= open_keys, (h, i, sorted(flipped - open_keys))
+            n_flipped += len(flipped)
+            n_open += len(open_keys)
+            # the emulation's row = the oracle's row + the moves of exactly the flipped decisions (+ the smooth part)
+            pred = out.astype(np.float64) + sum((moves[t] for t, (j, _) in enumerate(cands) if j in flipped), np.zeros(w.D))
+            assert np.max(np.abs(out32[h, i] - pred)) < 2e-5
+            if flipped:
+                alt = oracle.dma_attn_row_alt(q, k, v, (0, h, i), [(j, oracle.ALT_NEIGHBOUR) for j in sorted(flipped)], **kw)
+                assert np.max(np.abs(out32[h, i] - alt)) < 2e-5
+    print(f"binary32 emulation flips {n_flipped} roundings; the oracle calls {n_open} open", flush=True)
+    assert n_flipped >= 10
+    assert n_open <= OPEN_TO_FLIPPED_LIMIT * n_flipped
+
+
+# open decisions per flip of the binary32 emulation on the case above
+OPEN_TO_FLIPPED_LIMIT = 100
+
+
+def test_parity_bar_explains_flips_and_nothing_else(oracle):
+    """tests/parity.py on the CPU.  An output that equals the oracle except that a few rows took one of their open
+    decisions the other way passes the plain bar (those rows are found, explained and counted); an output that is wrong
+    by as much in a way no open decision produces fails; so do too many such rows."""
+    import parity
+    w = wl.small_variant(wl.CONFIGS["heavy_tail_16k"], S=512, Hq=2, Hkv=1)     # no channel outliers: a softmax with several sizeable terms
+    q, k, v = wl.generate(w)
+    kw = dict(tile=128, band=1)
+    bar = 1e-4                                  # 20 times tighter than the GPU's, so that single decisions matter on this small case
     rows = oracle.all_rows(w.B, w.Hq, w.S)
-    for band, hi, lo, bhi, blo in ((2, oracle.FMT_E4M3, oracle.FMT_E2M1, "e4m3", "e2m1"),
-                                   (0, oracle.FMT_E4M3, oracle.FMT_E4M3, "e4m3", "e4m3")):
-        want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=128, band=band, hi_fmt=hi, lo_fmt=lo, with_slack=True)
-        assert np.array_equal(want, oracle.dma_attn_rows(q, k, v, rows, tile=128, band=band, hi_fmt=hi, lo_fmt=lo))
-        got32 = brute.dma_attention(q[0], k[0], v[0], tile=128, band=band, hi=bhi, lo=blo, score_dtype=np.float32)
-        err = np.abs(got32.reshape(-1, w.D) - want)
-        assert np.max(err - slack) < 2e-5          # what is left is the smooth effect of the score rounding
-        assert np.median(slack.max(axis=1)) < 1e-6 and np.mean(slack) < 2e-4
-    # a probability exactly on a midpoint: two keys, scores 0 and log2(1 + 2^-8) - 1 ... built from p directly:
-    # one tile, key 0 has p = 1, key 1 has p = 0.501953125 = midpoint of bf16 neighbours 0.5 and 0.50390625
-    # (spacing 2^-8); check through the slack of a row whose second score is log2 of that midpoint
-    assert oracle.round_to_bf16(0.501953125) == 0.5           # the tie goes to the even neighbour
+    want = oracle.dma_attn_rows(q, k, v, rows, **kw)
+    got32 = brute.dma_attention(q[0], k[0], v[0], score_dtype=np.float32, binary32_exponent="chain", **kw).reshape(-1, w.D)
+    st = parity.compare(got32, want, rows, "binary32 emulation", oracle, (q, k, v), kw, max_abs=bar, alt_fraction=0.2)
+    assert st["alt_rows"] == 0                  # its own flips are all on small probabilities here
+    # rows with an open decision that moves the output by several bars
+    movers = []
+    for r, row in enumerate(rows):
+        out, cands, moves, _, _ = oracle.dma_attn_row_candidates(q, k, v, row, min_move=3 * bar, max_cand=4, **kw)
+        if cands:
+            movers.append((r, out, cands, moves))
+    assert len(movers) >= 3
+    got = want.copy()
+    for r, out, cands, moves in movers[:3]:
+        got[r] = oracle.dma_attn_row_alt(q, k, v, rows[r], [cands[0]], **kw)
+    st = parity.compare(got, want, rows, "three rows with one decision the other way", oracle, (q, k, v), kw, max_abs=bar, alt_fraction=0.2)
+    assert st["alt_rows"] == 3 and st["max_abs_after_alt"] <= 1e-6 and st["raw_max_abs"] >= 3 * bar
+    # the same with one more element moved by a few bars: no open decision moves one element alone
+    bad = got.copy()
+    bad[movers[0][0], 5] += 4 * bar
+    with pytest.raises(AssertionError):
+        parity.compare(bad, want, rows, "one element off", oracle, (q, k, v), kw, max_abs=bar, alt_fraction=0.2)
+    # a row without an open decision of that size, moved as far
+    quiet = [r for r in range(len(rows)) if r not in {m[0] for m in movers}][-1]
+    bad = want.copy()
+    bad[quiet] += movers[0][3][0]
+    with pytest.raises(AssertionError):
+        parity.compare(bad, want, rows, "a row with nothing open", oracle, (q, k, v), kw, max_abs=bar, alt_fraction=0.2)
+    # a row moved along one of its own open decisions, but twice as far: not a rounding the method can produce
+    r, out, cands, moves = movers[0]
+    twice = want.copy()
+    twice[r] = out + 2.0 * moves[0]
+    with pytest.raises(AssertionError):
+        parity.compare(twice, want, rows, "twice the step", oracle, (q, k, v), kw, max_abs=bar, alt_fraction=0.2)
+    # too many rows beyond the bar is a failure even though every one of them can be explained
+    with pytest.raises(AssertionError):
+        parity.compare(got, want, rows, "limit", oracle, (q, k, v), kw, max_abs=bar, alt_fraction=0.0)
 
 
 # ------------------------------------------------------------------ per-token scale (Alg. 2 Step 2)
@@ -613,18 +700,81 @@ def test_mx_pv_closed_form_with_exact_blocks(oracle):
     assert np.max(np.abs(got - want) / (np.abs(want) + 1e-30)) < 1e-6
 
 
-def test_mx_pv_slack_covers_binary32_scores(oracle):
-    """As for the bf16 rounding: what changes when the scores are first rounded to binary32 (E4M3 rounding flips of
-    single probabilities, and the scale byte of a block whose maximum sits on a power of two) stays within the slack."""
-    w = wl.small_variant(wl.CONFIGS["prefill_8k"], S=256, Hq=2, Hkv=1)
+def test_mx_pv_open_decisions_explain_binary32_scores(oracle):
+    """As for the bf16 rounding, for the MX-format P V: the emulation with binary32 exponents stays within the bar, and an
+    output in which a few rows took an open decision the other way (the E4M3 rounding of one probability, or the
+    scale byte of a block whose maximum sits next to a power of two) is explained row by row."""
+    import parity
+    w = wl.small_variant(wl.CONFIGS["heavy_tail_16k"], S=384, Hq=2, Hkv=1)
     q, k, v = wl.generate(w)
+    kw = dict(tile=128, band=1, pv_mx=True)
+    bar = 1e-4
     rows = oracle.all_rows(w.B, w.Hq, w.S)
-    want, slack = oracle.dma_attn_rows(q, k, v, rows, tile=128, band=1, with_slack=True, pv_mx=True)
-    assert np.array_equal(want, oracle.dma_attn_rows(q, k, v, rows, tile=128, band=1, pv_mx=True))
-    got32 = brute.dma_attention(q[0], k[0], v[0], tile=128, band=1, score_dtype=np.float32, pv_mx=True)
-    err = np.abs(got32.reshape(-1, w.D) - want)
-    assert np.max(err - slack) < 2e-5
-    assert np.median(slack.max(axis=1)) < 1e-5
+    want = oracle.dma_attn_rows(q, k, v, rows, **kw)
+    got32 = brute.dma_attention(q[0], k[0], v[0], score_dtype=np.float32, binary32_exponent="chain", **kw).reshape(-1, w.D)
+    parity.compare(got32, want, rows, "binary32 emulation, MX-format P V", oracle, (q, k, v), kw, max_abs=5 * bar, alt_fraction=0.5)
+    picked = []
+    for r, row in enumerate(rows):
+        out, cands, moves, _, _ = oracle.dma_attn_row_candidates(q, k, v, row, min_move=3 * bar, max_cand=8, **kw)
+        if cands and len(picked) < 4:
+            picked.append((r, cands[0]))
+    assert len(picked) == 4
+    got = want.copy()
+    for r, c in picked:
+        got[r] = oracle.dma_attn_row_alt(q, k, v, rows[r], [c], **kw)
+    st = parity.compare(got, want, rows, "rows with one decision the other way", oracle, (q, k, v), kw, max_abs=bar, alt_fraction=0.5)
+    assert st["alt_rows"] == 4 and st["max_abs_after_alt"] <= 1e-6
+    # a probability that is NOT open, rounded the other way, moves the row by many bars and is not accepted
+    r = picked[0][0]
+    probe = {}
+    brute.dma_attention(q[0], k[0], v[0], tile=128, band=1, pv_mx=True, probe=probe)
+    bad = want.copy()
+    for j in np.argsort(-probe[(int(rows[r][1]), int(rows[r][2]))])[:16]:      # the largest probability of that row that is not an E4M3 number
+        bad[r] = oracle.dma_attn_row_alt(q, k, v, rows[r], [(int(j), oracle.ALT_NEIGHBOUR)], **kw)
+        if np.max(np.abs(bad[r] - want[r])) > 3 * bar:
+            break
+    assert np.max(np.abs(bad[r] - want[r])) > 3 * bar
+    with pytest.raises(AssertionError):
+        parity.compare(bad, want, rows, "a closed decision taken the other way", oracle, (q, k, v), kw, max_abs=bar, alt_fraction=0.5)
+
+
+def test_mx_pv_scale_decisions(oracle):
+    """ALT_SCALE_UP / _DOWN move the shared scale of one 32-key block of P by one binade: against the per-element
+    rewrite of the block with the scale byte changed by hand."""
+    w = wl.small_variant(wl.CONFIGS["heavy_tail_16k"], S=128, Hq=1, Hkv=1)      # a softmax with several sizeable terms
+    q, k, v = wl.generate(w)
+    kw = dict(tile=128, band=1, pv_mx=True)
+    i = 100
+    base = oracle.dma_attn_rows(q, k, v, [(0, 0, i)], **kw)[0].astype(np.float64)
+    probe = {}
+    brute.dma_attention(q[0], k[0], v[0], tile=128, band=1, pv_mx=True, probe=probe)
+    vseen = brute.values_in_key_blocks(brute.bf16_bits_to_f64(v[0, 0]))
+    p_hat = probe[(0, i)]
+    # one key tile, high format throughout (band 1): the exact probabilities of the row from the rewrite's quantizer
+    s_hi = brute.quantize_rows(q[0, 0], "e4m3", True)[2] @ brute.quantize_rows(k[0, 0], "e4m3", False)[2].T
+    si = s_hi[i, :i + 1]
+    p = np.exp2(si - si.max())
+    for kind, shift in ((oracle.ALT_SCALE_UP, 1), (oracle.ALT_SCALE_DOWN, -1)):
+        got = oracle.dma_attn_row_alt(q, k, v, (0, 0, i), [(40, kind)], **kw).astype(np.float64)
+        # the block of keys 32..63 with its scale moved by one binade, element by element
+        blk = p[32:64]
+        ex = brute.floor_log2(float(blk.max())) - 8 + shift
+        y = np.minimum(blk / 2.0 ** ex, 448.0)
+        seen = np.array([brute.E4M3_GRID[brute.nearest_code(brute.E4M3_GRID, a)] for a in y]) * 2.0 ** ex
+        delta = ((seen - p_hat[32:64]) @ vseen[32:64]) / p.sum()
+        assert np.max(np.abs((got - base) - delta)) < 2e-6
+        # a finer scale clamps the block's largest element at 448; a coarser one only costs subnormal bits, often none
+        assert kind == oracle.ALT_SCALE_UP or np.max(np.abs(got - base)) > 1e-5
+    # ALT_NEIGHBOUR in this format: the other E4M3 neighbour of one probability at its block's scale
+    j = 32 + int(np.argsort(-p[32:64])[1])
+    ex = brute.floor_log2(float(p[32:64].max())) - 8
+    y = p[j] / 2.0 ** ex
+    below = brute.E4M3_GRID[brute.E4M3_GRID <= y].max()
+    above = brute.E4M3_GRID[brute.E4M3_GRID > y].min()
+    assert below < y < above and p_hat[j] / 2.0 ** ex in (below, above)
+    other = (above if p_hat[j] / 2.0 ** ex == below else below) * 2.0 ** ex
+    got = oracle.dma_attn_row_alt(q, k, v, (0, 0, i), [(j, oracle.ALT_NEIGHBOUR)], **kw).astype(np.float64)
+    assert np.max(np.abs((got - base) - (other - p_hat[j]) * vseen[j] / p.sum())) < 2e-6
 
 
 # ------------------------------------------------------------------ coarser granularities of the Step-2 scale (Sec. 5.3)
