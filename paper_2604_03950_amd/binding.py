@@ -18,7 +18,7 @@ FMT_MXFP4_E2M1 = 2
 FMT_MXFP8_E5M2 = 3
 
 EXPORTS = ("dma_mx_quantize", "dma_mx_quantize_token", "dma_mx_quantize_dual", "dma_mx_group_amax", "dma_attn_fwd", "dma_attn_fwd_ex",
-           "dma_attn_fwd_workspace_bytes", "dma_diag_copy", "dma_error_string", "dma_version")
+           "dma_attn_fwd_workspace_bytes", "dma_diag_copy", "dma_diag_mfma", "dma_error_string", "dma_version")
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdma_mi355x.so")
 _lib = None
@@ -64,6 +64,8 @@ def load() -> ctypes.CDLL:
         L.dma_attn_fwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
         L.dma_diag_copy.restype = ci
         L.dma_diag_copy.argtypes = [vp, vp, i64, vp]
+        L.dma_diag_mfma.restype = ci
+        L.dma_diag_mfma.argtypes = [vp, vp, vp, vp, ci, vp, vp]
         L.dma_error_string.restype = ctypes.c_char_p
         L.dma_error_string.argtypes = [ci]
         L.dma_version.restype = ci
@@ -84,9 +86,13 @@ def _stream() -> int:
     return int(torch.cuda.current_stream().cuda_stream)
 
 
-def _dev(t: torch.Tensor, dtype, what: str) -> int:
+def _dev(t: torch.Tensor, dtype, what: str, shape=None) -> int:
+    """Device pointer of a contiguous GPU tensor of the given dtype (and, for buffers the kernels write, shape: an
+    undersized caller buffer would otherwise be written past its end)."""
     if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
         raise ValueError(f"{what}: need a contiguous {dtype} tensor on the GPU")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{what}: shape {tuple(t.shape)}, expected {tuple(shape)}")
     return t.data_ptr()
 
 
@@ -101,7 +107,8 @@ def dma_mx_quantize(x: torch.Tensor, fmt: int, is_query: bool, codes: torch.Tens
     if scales is None:
         scales = torch.empty(x.shape[:-1] + (D // 32,), dtype=torch.uint8, device=x.device)
     rc = load().dma_mx_quantize(_dev(x, torch.bfloat16, "x"), rows, D, fmt, int(bool(is_query)),
-                                _dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"), _stream())
+                                _dev(codes, torch.uint8, "codes", x.shape[:-1] + (cb,)),
+                                _dev(scales, torch.uint8, "scales", x.shape[:-1] + (D // 32,)), _stream())
     if rc:
         raise DmaError(rc, "dma_mx_quantize")
     return codes, scales
@@ -135,7 +142,7 @@ def dma_mx_group_amax(x: torch.Tensor, is_query: bool, granularity: int, block_r
     if out is None:
         out = torch.empty(x.shape[:-1], dtype=torch.float32, device=x.device)
     rc = load().dma_mx_group_amax(_dev(x, torch.bfloat16, "x"), n_mat, S, D, int(bool(is_query)), int(granularity),
-                                  int(block_rows), _dev(out, torch.float32, "amax"), _stream())
+                                  int(block_rows), _dev(out, torch.float32, "amax", x.shape[:-1]), _stream())
     if rc:
         raise DmaError(rc, "dma_mx_group_amax")
     return out
@@ -150,8 +157,10 @@ def dma_mx_quantize_dual(x: torch.Tensor, is_query: bool, out=None):
         out = (mk(D // 2), mk(D // 32), mk(D), mk(D // 32))
     c4, s4, c8, s8 = out
     rc = load().dma_mx_quantize_dual(_dev(x, torch.bfloat16, "x"), rows, D, int(bool(is_query)),
-                                     _dev(c4, torch.uint8, "codes_lo"), _dev(s4, torch.uint8, "scales_lo"),
-                                     _dev(c8, torch.uint8, "codes_hi"), _dev(s8, torch.uint8, "scales_hi"), _stream())
+                                     _dev(c4, torch.uint8, "codes_lo", x.shape[:-1] + (D // 2,)),
+                                     _dev(s4, torch.uint8, "scales_lo", x.shape[:-1] + (D // 32,)),
+                                     _dev(c8, torch.uint8, "codes_hi", x.shape[:-1] + (D,)),
+                                     _dev(s8, torch.uint8, "scales_hi", x.shape[:-1] + (D // 32,)), _stream())
     if rc:
         raise DmaError(rc, "dma_mx_quantize_dual")
     return out
@@ -173,7 +182,7 @@ def dma_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, diag_band
     if out is None:
         out = torch.empty((B, Hq, S, D), dtype=torch.float32, device=q.device)
     args = [_dev(q, torch.bfloat16, "q"), _dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v"),
-            _dev(out, torch.float32, "out"), B, Hq, Hkv, S, D, int(bool(causal)), int(diag_band_tiles),
+            _dev(out, torch.float32, "out", (B, Hq, S, D)), B, Hq, Hkv, S, D, int(bool(causal)), int(diag_band_tiles),
             int(hi_fmt), int(lo_fmt)]
     if tile is None and not fp8_mfma and not sink_tiles and not per_token_scale and not pv_mx and group_amax is None:
         rc = load().dma_attn_fwd(*args, _stream())
@@ -201,6 +210,22 @@ def dma_diag_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
     rc = load().dma_diag_copy(src.data_ptr(), dst.data_ptr(), n, _stream())
     if rc:
         raise DmaError(rc, "dma_diag_copy")
+
+
+def dma_diag_mfma(a: torch.Tensor, b: torch.Tensor, a_scales: torch.Tensor | None, b_scales: torch.Tensor | None, fmt: int) -> torch.Tensor:
+    """One 32 x 32 x 64 product on the matrix instruction of format fmt (diagnostic): a, b uint8 [32, 64] (E4M3 codes) or
+    [32, 32] (packed E2M1 codes) with scales uint8 [32, 2], or bf16 [32, 64] without scales -> float32 [32, 32]."""
+    if fmt == FMT_BF16:
+        pa, pb, psa, psb = _dev(a, torch.bfloat16, "a", (32, 64)), _dev(b, torch.bfloat16, "b", (32, 64)), None, None
+    else:
+        cols = 32 if fmt == FMT_MXFP4_E2M1 else 64
+        pa, pb = _dev(a, torch.uint8, "a", (32, cols)), _dev(b, torch.uint8, "b", (32, cols))
+        psa, psb = _dev(a_scales, torch.uint8, "a_scales", (32, 2)), _dev(b_scales, torch.uint8, "b_scales", (32, 2))
+    out = torch.empty((32, 32), dtype=torch.float32, device=a.device)
+    rc = load().dma_diag_mfma(pa, pb, psa, psb, int(fmt), out.data_ptr(), _stream())
+    if rc:
+        raise DmaError(rc, "dma_diag_mfma")
+    return out
 
 
 def bits_to_bf16_tensor(bits, device="cuda") -> torch.Tensor:

@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdma_mi355x.so")
-SOURCES = ["dma_api.hip", "dma_quantize.hip", "dma_attn_fwd.hip"]
+SOURCES = ["dma_api.hip", "dma_quantize.hip", "dma_attn_fwd.hip", "dma_diag.hip"]
 HEADERS = ["dma_device.hpp", "dma_internal.hpp", "dma_attn_kernel.hpp", os.path.join("..", "..", "include", "dma.h")]
 # (low, high) format pairs of the fused forward, as product-path ids of dma_device.hpp: dma_attn_inst.hip is compiled
 # once per pair (the list mirrors the declarations in dma_attn_fwd.hip)
@@ -24,6 +24,19 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
+
+
+def source_digest() -> str:
+    """SHA-256 over the kernel sources and the public header (file names and contents, sorted by name): what a profile
+    summary records so that a figure measured on one version of the kernels is not quoted for another."""
+    import hashlib
+    h = hashlib.sha256()
+    names = sorted(n for n in os.listdir(CSRC) if n.endswith((".hip", ".hpp")))
+    for path in [os.path.join(CSRC, n) for n in names] + [os.path.join(HERE, "..", "include", "dma.h")]:
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
 
 
 def _stale(obj: str, deps: list[str]) -> bool:
@@ -67,4 +80,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(force="--incremental" not in sys.argv, verbose="-v" in sys.argv))
+    if "--digest" in sys.argv:
+        print(source_digest())
+    else:
+        print(build(force="--incremental" not in sys.argv, verbose="-v" in sys.argv))

@@ -158,6 +158,14 @@ int dma_diag_copy(const void* src, void* dst, int64_t bytes, void* stream)
     return dma::launch_diag_copy(src, dst, bytes, (hipStream_t)stream);
 }
 
+int dma_diag_mfma(const void* a, const void* b, const void* a_scales, const void* b_scales, int fmt, void* out_f32, void* stream)
+{
+    if (fmt != DMA_FMT_BF16 && fmt != DMA_FMT_MXFP8_E4M3 && fmt != DMA_FMT_MXFP4_E2M1) return DMA_ERR_INVALID_ARG;
+    if (!a || !b || !out_f32 || !aligned16(a) || !aligned16(b) || !aligned16(out_f32)) return DMA_ERR_INVALID_ARG;
+    if (fmt != DMA_FMT_BF16 && (!a_scales || !b_scales)) return DMA_ERR_INVALID_ARG;
+    return dma::launch_diag_mfma(a, b, a_scales, b_scales, fmt, (float*)out_f32, (hipStream_t)stream);     // public ids 0, 1, 2 = product paths 0, 1, 2
+}
+
 const char* dma_error_string(int code)
 {
     switch (code) {

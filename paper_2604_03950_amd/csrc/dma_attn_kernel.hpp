@@ -1140,14 +1140,15 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
     if (cus <= 0) return DMA_ERR_HIP_;
     // as many workgroups as the chip holds at once (one per CU for the D = 128 instances), each walking its share
     // of the work items
-    // per instance, the same on every device of one kind; initialised once, also when several host threads launch
-    static const int resident = [] {
-        int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT, PVMX>, C::T, 0) != hipSuccess || n <= 0)
-            return -1;
-        return n;
-    }();
-    if (resident <= 0) return DMA_ERR_HIP_;
+    // per instance, the same on every device of one kind; kept once a query has succeeded (a failed query is repeated by
+    // the next call); every writer stores the same value, so several host threads may launch at once
+    static std::atomic<int> resident_cache{0};
+    int resident = resident_cache.load(std::memory_order_relaxed);
+    if (resident == 0) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT, PVMX>, C::T, 0) != hipSuccess || resident <= 0)
+            return DMA_ERR_HIP_;
+        resident_cache.store(resident, std::memory_order_relaxed);
+    }
     const int64_t slots = (int64_t)cus * resident;
     const int64_t blocks = items < slots ? items : slots;
     const float c = (float)(1.4426950408889634074 / sqrt((double)D));
@@ -1159,10 +1160,9 @@ static int launch_variant(const AttnArgs& a, hipStream_t stream)
     int head_block = heads_x;
     for (int hb = 1; hb < heads_x; ++hb)
         if (heads_x % hb == 0 && ((int64_t)hb * NG) % (2 * workers) == 0) { head_block = hb; break; }
-    hipLaunchKernelGGL((dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT, PVMX>), dim3((unsigned)blocks), dim3(C::T), 0, stream,
-                       (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, a.out, a.B, a.Hq, a.Hkv,
-                       a.S, a.band, a.sink, a.causal, c, head_block, a.q_amax, a.k_amax);
-    return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
+    return launch(dma_attn_fwd_kernel<D, BT, TPW, LO, HI, GENERAL, PT, PVMX>, dim3((unsigned)blocks), dim3(C::T), stream,
+                  (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, a.out, a.B, a.Hq, a.Hkv,
+                  a.S, a.band, a.sink, a.causal, c, head_block, a.q_amax, a.k_amax);
 }
 
 // Alg. 1 as printed (causal, no sink window, sequence a whole number of tile groups) runs the straight-line instance, whose

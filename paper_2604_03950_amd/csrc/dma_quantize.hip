@@ -79,12 +79,10 @@ static int launch_mode(const void* x, int64_t rows, int D, int is_query, void* c
     const int lpr = D / 8;
     if (PER_TOKEN && (lpr > 64 || (lpr & (lpr - 1)) != 0)) return DMA_ERR_UNSUPPORTED_;
     if (is_query)
-        hipLaunchKernelGGL((mx_quantize_kernel<MODE, true, PER_TOKEN>), dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream,
-                           (const v4i*)x, n_chunks, c, (int*)c4, (uint8_t*)s4, (v2i*)c8, (uint8_t*)s8, ts, lpr);
-    else
-        hipLaunchKernelGGL((mx_quantize_kernel<MODE, false, PER_TOKEN>), dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream,
-                           (const v4i*)x, n_chunks, c, (int*)c4, (uint8_t*)s4, (v2i*)c8, (uint8_t*)s8, ts, lpr);
-    return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
+        return launch(mx_quantize_kernel<MODE, true, PER_TOKEN>, dim3((unsigned)blocks), dim3(QUANT_THREADS), stream,
+                      (const v4i*)x, n_chunks, c, (int*)c4, (uint8_t*)s4, (v2i*)c8, (uint8_t*)s8, ts, lpr);
+    return launch(mx_quantize_kernel<MODE, false, PER_TOKEN>, dim3((unsigned)blocks), dim3(QUANT_THREADS), stream,
+                  (const v4i*)x, n_chunks, c, (int*)c4, (uint8_t*)s4, (v2i*)c8, (uint8_t*)s8, ts, lpr);
 }
 
 // Plain copy, 16 bytes per lane: the reference kernel for calibrating HBM traffic counters.
@@ -101,9 +99,7 @@ int launch_diag_copy(const void* src, void* dst, int64_t bytes, hipStream_t stre
     if (n_chunks == 0) return DMA_OK_;
     const int64_t blocks = (n_chunks + QUANT_THREADS - 1) / QUANT_THREADS;
     if (blocks > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
-    hipLaunchKernelGGL(diag_copy_kernel, dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream, (const v4i*)src,
-                       (v4i*)dst, n_chunks);
-    return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
+    return launch(diag_copy_kernel, dim3((unsigned)blocks), dim3(QUANT_THREADS), stream, (const v4i*)src, (v4i*)dst, n_chunks);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -183,21 +179,21 @@ int launch_group_amax(const void* x, int64_t n_mat, int64_t S, int D, int is_que
     const int64_t blocks = (chunks + QUANT_THREADS - 1) / QUANT_THREADS;
     if (blocks > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
     const float c = (float)(1.4426950408889634074 / sqrt((double)D));
-    if (D == 128) hipLaunchKernelGGL(row_amax_kernel<16>, dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream, (const v4i*)x, rows, c, is_query, amax);
-    else if (D == 64) hipLaunchKernelGGL(row_amax_kernel<8>, dim3((unsigned)blocks), dim3(QUANT_THREADS), 0, stream, (const v4i*)x, rows, c, is_query, amax);
-    else return DMA_ERR_UNSUPPORTED_;
-    if (granularity == 2) {
-        const int64_t bpm = (S + block_rows - 1) / block_rows;
-        if (n_mat * bpm > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
-        hipLaunchKernelGGL(block_amax_kernel, dim3((unsigned)(n_mat * bpm)), dim3(64), 0, stream, amax, S, block_rows, bpm);
-    } else if (granularity == 3) {
-        const int64_t runs = (rows + TENSOR_RUN - 1) / TENSOR_RUN;
-        if (runs > 0x7fffffffLL) return DMA_ERR_UNSUPPORTED_;
-        hipLaunchKernelGGL(block_amax_kernel, dim3((unsigned)runs), dim3(64), 0, stream, amax, rows, TENSOR_RUN, runs);
-        hipLaunchKernelGGL(tensor_reduce_kernel, dim3(1), dim3(1024), 0, stream, amax, rows);
-        hipLaunchKernelGGL(broadcast_first_kernel, dim3((unsigned)((rows + QUANT_THREADS - 1) / QUANT_THREADS)), dim3(QUANT_THREADS), 0, stream, amax, rows);
+    // every size check comes before the first launch: on error nothing has been enqueued
+    const int64_t bpm = granularity == 2 ? (S + block_rows - 1) / block_rows : 0;
+    const int64_t runs = (rows + TENSOR_RUN - 1) / TENSOR_RUN;
+    if (D != 128 && D != 64) return DMA_ERR_UNSUPPORTED_;
+    if ((granularity == 2 && n_mat * bpm > 0x7fffffffLL) || (granularity == 3 && runs > 0x7fffffffLL)) return DMA_ERR_UNSUPPORTED_;
+    int rc = D == 128 ? launch(row_amax_kernel<16>, dim3((unsigned)blocks), dim3(QUANT_THREADS), stream, (const v4i*)x, rows, c, is_query, amax)
+                      : launch(row_amax_kernel<8>, dim3((unsigned)blocks), dim3(QUANT_THREADS), stream, (const v4i*)x, rows, c, is_query, amax);
+    if (rc == DMA_OK_ && granularity == 2)
+        rc = launch(block_amax_kernel, dim3((unsigned)(n_mat * bpm)), dim3(64), stream, amax, S, block_rows, bpm);
+    if (granularity == 3) {
+        if (rc == DMA_OK_) rc = launch(block_amax_kernel, dim3((unsigned)runs), dim3(64), stream, amax, rows, TENSOR_RUN, runs);
+        if (rc == DMA_OK_) rc = launch(tensor_reduce_kernel, dim3(1), dim3(1024), stream, amax, rows);
+        if (rc == DMA_OK_) rc = launch(broadcast_first_kernel, dim3((unsigned)((rows + QUANT_THREADS - 1) / QUANT_THREADS)), dim3(QUANT_THREADS), stream, amax, rows);
     }
-    return hipGetLastError() == hipSuccess ? DMA_OK_ : DMA_ERR_HIP_;
+    return rc;
 }
 
 int launch_mx_quantize(const void* x, int64_t rows, int D, int mode, int is_query, void* c4, void* s4,
