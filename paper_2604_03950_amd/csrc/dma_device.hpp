@@ -148,19 +148,19 @@ DMA_DEV int encode8_e2m1(const float (&x)[8], int code)
 }
 
 // The same from eight packed bf16 (no pre-scale): the convert reads the bf16 pairs directly.
-// Each source dword is first pinned into a VGPR of its own: with the elements of the 128-bit vector named directly in
-// the builtins this compiler emits the FIRST register of the source tuple for all four converts (wrong codes).
+// The four converts are written as instructions rather than through the builtin: with the elements of the 128-bit
+// vector named in the builtin this compiler emits the FIRST register of the source tuple for all four converts (wrong
+// codes), and pinning each element into a register of its own costs a move per element; an instruction operand taken
+// from a vector element is allocated as the sub-register it is.
 // tests/test_isa.py checks the generated code of every instance for four distinct source registers per group.
 DMA_DEV int encode8_e2m1_bf16(const v4i& w, int code)
 {
     const float sc = cvt_scale_operand(code);
-    int w0 = w[0], w1 = w[1], w2 = w[2], w3 = w[3];
-    asm volatile("" : "+v"(w0), "+v"(w1), "+v"(w2), "+v"(w3));
     unsigned r = 0;
-    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(v2bf, w0), sc, 0);
-    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(v2bf, w1), sc, 1);
-    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(v2bf, w2), sc, 2);
-    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_bf16(r, __builtin_bit_cast(v2bf, w3), sc, 3);
+    asm("v_cvt_scalef32_pk_fp4_bf16 %0, %1, %2" : "+v"(r) : "v"(w[0]), "v"(sc));
+    asm("v_cvt_scalef32_pk_fp4_bf16 %0, %1, %2 op_sel:[0,0,1,0]" : "+v"(r) : "v"(w[1]), "v"(sc));
+    asm("v_cvt_scalef32_pk_fp4_bf16 %0, %1, %2 op_sel:[0,0,0,1]" : "+v"(r) : "v"(w[2]), "v"(sc));
+    asm("v_cvt_scalef32_pk_fp4_bf16 %0, %1, %2 op_sel:[0,0,1,1]" : "+v"(r) : "v"(w[3]), "v"(sc));
     return (int)r;
 }
 
