@@ -82,3 +82,10 @@ def test_argument_checks_return_before_any_launch(lib):
     assert attn_ex(hi=3, fp8_mfma=1) == -2    # E5M2 only has the decoded-to-bf16 path
     assert attn_ex(fp8_mfma=2) == -1
     assert lib.dma_attn_fwd_workspace_bytes(1, 32, 8, 32768, 128) == 0
+    # the diagnostics
+    assert lib.dma_diag_mfma(fake, fake, fake, fake, 3, fake, None) == -1            # E5M2 has no instruction path of its own
+    assert lib.dma_diag_mfma(fake, fake, None, fake, 1, fake, None) == -1            # MX formats need both scale arrays
+    assert lib.dma_diag_mfma(None, fake, None, None, 0, fake, None) == -1
+    assert lib.dma_diag_mfma(fake, ctypes.c_void_p(0x1008), None, None, 0, fake, None) == -1   # misaligned
+    assert lib.dma_diag_copy(fake, fake, 24, None) == -1                             # not a multiple of 16 bytes
+    assert lib.dma_diag_copy(fake, fake, 0, None) == 0
