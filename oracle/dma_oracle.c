@@ -775,19 +775,123 @@ int oracle_dma_attn_rows_ex(const uint16_t *q, const uint16_t *k, const uint16_t
  * (Measured: the decisions the MI355X kernel takes the other way need at most a quarter of it.) */
 static double score_noise(double s, double m) { return ldexp(fabs(s) + fabs(m) + 1.0, -22); }
 
-/* One row (b, hq, i), everything else as oracle_dma_attn_rows_ex.
- * alt_key / alt_kind [n_alt]: decisions to take the other way (ORACLE_ALT_*); out [D] receives the row.
- * With cand_* non-NULL the open decisions of the row as the method rounds it (n_alt must be 0) are listed, largest
- * effect first: cand_key / cand_kind [max_cand]; cand_move [max_cand, D] = how taking that one decision the other way
- * moves out[d] (to first order: the row sum does not change, decisions do not interact except inside one MX block);
- * cand_margin [max_cand] = how much of the noise allowance the decision uses (0: p sits on the midpoint; 1: it is only
- * just open); *n_cand = how many there are with max_d |move| >= min_move (all of them counted, the first max_cand listed).
- * A decision is open when
+/* A growing list of open decisions: key, kind, share of the noise allowance used, move of out[0..D). */
+typedef struct { int64_t n, cap; int D; int64_t *key; int32_t *kind; double *used, *move; int failed; } open_list;
+static void open_list_add(open_list *L, int64_t key, int32_t kind, double used, const double *move)
+{
+    if (L->failed) return;
+    if (L->n == L->cap) {
+        const int64_t cap = L->cap ? 2 * L->cap : 64;
+        int64_t *k2 = (int64_t *)realloc(L->key, sizeof(int64_t) * (size_t)cap);
+        if (k2) L->key = k2;
+        int32_t *n2 = (int32_t *)realloc(L->kind, sizeof(int32_t) * (size_t)cap);
+        if (n2) L->kind = n2;
+        double *u2 = (double *)realloc(L->used, sizeof(double) * (size_t)cap);
+        if (u2) L->used = u2;
+        double *m2 = (double *)realloc(L->move, sizeof(double) * (size_t)cap * (size_t)L->D);
+        if (m2) L->move = m2;
+        if (!k2 || !n2 || !u2 || !m2) { L->failed = 1; return; }
+        L->cap = cap;
+    }
+    L->key[L->n] = key; L->kind[L->n] = kind; L->used[L->n] = used;
+    memcpy(L->move + L->n * L->D, move, sizeof(double) * (size_t)L->D);
+    ++L->n;
+}
+static double largest_abs(const double *x, int n)
+{
+    double big = 0.0;
+    for (int t = 0; t < n; ++t)
+        if (fabs(x[t]) > big) big = fabs(x[t]);
+    return big;
+}
+
+/* The open decisions of one row, from its trace (scores tr->s, running maxima tr->m, final m and l).
  *   bf16 P (p_round = 1): p_j lies within score_noise * ln2 * p_j of the midpoint of its two bf16 neighbours;
  *   MX-format P V (p_round = 2): the same against the E4M3 grid of the block's scale (kind NEIGHBOUR); and the
  *   block's scale itself when the block maximum of s - m' lies within score_noise of an integer (one binade
  *   finer if it may fall below that integer: SCALE_DOWN; coarser if it may reach it: SCALE_UP), or, for the block
- *   that holds the row maximum (s - m' = 0 exactly), when another key of the row comes that close to the maximum. */
+ *   that holds the row maximum (s - m' = 0 exactly), when another key of the row comes that close to the maximum.
+ * The move of a decision is its first-order effect on out[]: (new weight - old weight) * value * 2^(m' - m_final) / l
+ * (the row sum adds the unrounded p and does not change).  values[j*D + d]: what key j contributes per unit weight. */
+static void list_open_decisions(const row_trace *tr, int64_t n_keys, int tile, int D, int p_round, const double *values,
+                                double min_move, open_list *L)
+{
+    double *mv = (double *)malloc(sizeof(double) * (size_t)D);
+    if (!mv) { L->failed = 1; return; }
+    /* single probabilities */
+    for (int64_t j = 0; j < n_keys; ++j) {
+        if (!(tr->s[j] > -INFINITY)) continue;                       /* masked */
+        const double mj = tr->m[j];
+        const double p = exp2(tr->s[j] - mj);
+        if (!(p > 0.0)) continue;
+        double rounded, other, spacing;
+        if (p_round == 2) {
+            /* the E4M3 grid at the scale of the key's 32-key block (keys of one block share a key tile, hence m') */
+            const int64_t j0 = (j / 32) * 32;
+            double pblk[32], seen[32];
+            for (int t = 0; t < 32; ++t)
+                pblk[t] = (j0 + t < n_keys && tr->s[j0 + t] > -INFINITY) ? exp2(tr->s[j0 + t] - mj) : 0.0;
+            const int bsc = block_e4m3_as_seen(pblk, 32, 0, seen);
+            const double y = ldexp(p, 127 - bsc);
+            if (y >= 448.0) continue;                                /* clamped either way */
+            spacing = ldexp(1.0, e4m3_quantum(y) + bsc - 127);
+            rounded = seen[j - j0];
+            other = e4m3_other_neighbour(p, bsc, rounded);
+        } else {
+            spacing = ldexp(1.0, bf16_quantum(p));
+            rounded = oracle_round_to_bf16(p);
+            other = other_grid_point(p, rounded, bf16_quantum(p));
+        }
+        if (other == rounded) continue;                              /* p is a grid point: nothing to decide */
+        const double r = p / spacing;
+        const double to_midpoint = fabs(r - floor(r) - 0.5) * spacing;
+        const double allowance = score_noise(tr->s[j], mj) * 0.6931471805599453 * p;
+        if (to_midpoint > allowance) continue;
+        const double carry = exp2(mj - tr->m_final) / tr->l_final;
+        for (int d = 0; d < D; ++d) mv[d] = (other - rounded) * values[j * D + d] * carry;
+        if (largest_abs(mv, D) >= min_move) open_list_add(L, j, ORACLE_ALT_NEIGHBOUR, to_midpoint / allowance, mv);
+    }
+    /* shared scales of the 32-key blocks of P (MX-format P V only) */
+    for (int64_t j0 = 0; p_round == 2 && j0 < n_keys; j0 += 32) {
+        const int nb = (int)((n_keys - j0 < 32) ? n_keys - j0 : 32);
+        const double mblk = tr->m[j0];
+        double xmax = -INFINITY, second = -INFINITY;
+        for (int t = 0; t < nb; ++t)
+            if (tr->s[j0 + t] - mblk > xmax) xmax = tr->s[j0 + t] - mblk;
+        if (xmax == -INFINITY) continue;                             /* every key masked */
+        /* the largest s - m' of the row outside this block among the keys seen up to this tile */
+        const int64_t tile_end = ((j0 / tile) + 1) * (int64_t)tile < n_keys ? ((j0 / tile) + 1) * (int64_t)tile : n_keys;
+        for (int64_t j = 0; j < tile_end; ++j)
+            if ((j < j0 || j >= j0 + nb) && tr->s[j] - mblk > second) second = tr->s[j] - mblk;
+        const double noise = score_noise(xmax + mblk, mblk);
+        int shift = 0;
+        double used = 0.0;
+        if (xmax == 0.0) { if (second >= -noise) { shift = -1; used = -second / noise; } }
+        else if (xmax - floor(xmax) <= noise) { shift = -1; used = (xmax - floor(xmax)) / noise; }
+        else if (ceil(xmax) - xmax <= noise) { shift = 1; used = (ceil(xmax) - xmax) / noise; }
+        if (shift == 0) continue;
+        double pblk[32], seen0[32], seen1[32];
+        for (int t = 0; t < 32; ++t) pblk[t] = (t < nb && tr->s[j0 + t] > -INFINITY) ? exp2(tr->s[j0 + t] - mblk) : 0.0;
+        (void)block_e4m3_as_seen(pblk, 32, 0, seen0);
+        (void)block_e4m3_as_seen(pblk, 32, shift, seen1);
+        const double carry = exp2(mblk - tr->m_final) / tr->l_final;
+        for (int d = 0; d < D; ++d) {
+            double acc = 0.0;
+            for (int t = 0; t < nb; ++t) acc += (seen1[t] - seen0[t]) * values[(j0 + t) * D + d];
+            mv[d] = acc * carry;
+        }
+        if (largest_abs(mv, D) >= min_move)
+            open_list_add(L, j0, shift > 0 ? ORACLE_ALT_SCALE_UP : ORACLE_ALT_SCALE_DOWN, used, mv);
+    }
+    free(mv);
+}
+
+/* One row (b, hq, i), everything else as oracle_dma_attn_rows_ex (the probabilities are rounded: p_round 1 or 2).
+ * alt_key / alt_kind [n_alt]: decisions to take the other way (ORACLE_ALT_*); out [D] receives the row.
+ * With cand_key non-NULL (then n_alt must be 0) the open decisions of the row as the method rounds it are listed too,
+ * largest move first: cand_key / cand_kind / cand_margin [max_cand] (margin = share of the noise allowance the
+ * decision uses: 0 on the midpoint, 1 only just open), cand_move [max_cand, D]; *n_cand = how many there are whose
+ * move reaches min_move in some out[d] (all of them counted, the first max_cand listed). */
 int oracle_dma_attn_row_alt(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Hq, int Hkv, int64_t S,
                             int D, int tile, int band, int sink, int causal, int per_token, int hi_fmt, int lo_fmt,
                             int p_round, int64_t b, int64_t hq, int64_t i, const int64_t *alt_key,
@@ -815,132 +919,42 @@ int oracle_dma_attn_row_alt(const uint16_t *q, const uint16_t *k, const uint16_t
     const row_alts alt = { n_alt, alt_key, alt_kind };
     const int64_t n_keys = ((imax / tile) + 1) * tile < S ? ((imax / tile) + 1) * tile : S;   /* keys of the tiles visited */
     row_trace tr = { NULL, NULL, 0.0, 0.0 };
+    double *values = NULL;
     int rc = ORACLE_OK;
     if (want_cand) {
         tr.s = (double *)malloc(sizeof(double) * (size_t)n_keys * 2);
-        if (!tr.s) rc = ORACLE_ERR_MEM;
+        values = (p_round == 2) ? hv.vseen : (double *)malloc(sizeof(double) * (size_t)n_keys * (size_t)D);
+        if (!tr.s || !values) rc = ORACLE_ERR_MEM;
         tr.m = tr.s + n_keys;
+        if (rc == ORACLE_OK && p_round != 2)
+            for (int64_t e = 0; e < n_keys * D; ++e) values[e] = (double)oracle_bf16_to_f32(vh[e]);
     }
     if (rc == ORACLE_OK)
         attn_one_row(qrow, hv.klo, hv.khi, vh, hv.vseen, i, S, D, tile, band, sink, causal, per_token, qam, hi_fmt, lo_fmt, p_round,
                      out, n_alt ? &alt : NULL, want_cand ? &tr : NULL);
     if (rc == ORACLE_OK && want_cand) {
-        /* the open decisions, from the trace: (key, kind, largest |move|), then the largest ones in full */
-        int64_t found = 0, cap = 64;
-        int64_t *ck = (int64_t *)malloc(sizeof(int64_t) * (size_t)cap);
-        int32_t *cn = (int32_t *)malloc(sizeof(int32_t) * (size_t)cap);
-        double *cm = (double *)malloc(sizeof(double) * (size_t)cap * (size_t)D);
-        double *cr = (double *)malloc(sizeof(double) * (size_t)cap);
-        double *mv = (double *)malloc(sizeof(double) * (size_t)D);
-        double pblk[32], seen0[32], seen1[32];
-        for (int64_t j0 = 0; j0 < n_keys && ck && cn && cm && cr && mv; j0 += 32) {
-            /* keys j0 .. j0+nb-1: for the MX-format P V (tile % 32 == 0) one block of one key tile, sharing m' */
-            const int nb = (int)((n_keys - j0 < 32) ? n_keys - j0 : 32);
-            for (int pass = 0; pass < 2; ++pass) {            /* pass 0: single probabilities; pass 1: the block's scale */
-                if (pass == 1 && p_round != 2) break;
-                int bsc = 0, shift = 0;
-                double used = 0.0;                              /* share of the noise allowance this decision needs */
-                const double mblk = tr.m[j0];
-                const double carry = exp2(mblk - tr.m_final) / tr.l_final;     /* what one unit of this tile's numerator is worth in out */
-                if (p_round == 2) {
-                    double xmax = -INFINITY, second = -INFINITY;
-                    for (int t = 0; t < 32; ++t) pblk[t] = (t < nb && tr.s[j0 + t] > -INFINITY) ? exp2(tr.s[j0 + t] - mblk) : 0.0;
-                    bsc = block_e4m3_as_seen(pblk, 32, 0, seen0);
-                    if (pass == 1) {
-                        for (int t = 0; t < nb; ++t)
-                            if (tr.s[j0 + t] - mblk > xmax) xmax = tr.s[j0 + t] - mblk;
-                        if (xmax == -INFINITY) continue;
-                        /* the largest s - m' of the row outside this block, among the keys seen so far and the old maximum */
-                        const int64_t tile0 = (j0 / tile) * tile, tile1 = (tile0 + tile < n_keys) ? tile0 + tile : n_keys;
-                        for (int64_t j = 0; j < tile1; ++j)
-                            if ((j < j0 || j >= j0 + nb) && tr.s[j] - mblk > second) second = tr.s[j] - mblk;
-                        const double noise = score_noise(xmax + mblk, mblk);
-                        if (xmax == 0.0) { shift = (second >= -noise) ? -1 : 0; used = -second / noise; }
-                        else if (xmax - floor(xmax) <= noise) { shift = -1; used = (xmax - floor(xmax)) / noise; }
-                        else if (ceil(xmax) - xmax <= noise) { shift = 1; used = (ceil(xmax) - xmax) / noise; }
-                        if (shift == 0) continue;
-                        (void)block_e4m3_as_seen(pblk, 32, shift, seen1);
-                    }
-                }
-                for (int t = 0; t < (pass == 0 ? nb : 1); ++t) {
-                    const int64_t j = j0 + t;
-                    int32_t kind;
-                    double big = 0.0;
-                    if (pass == 1) {
-                        kind = shift > 0 ? ORACLE_ALT_SCALE_UP : ORACLE_ALT_SCALE_DOWN;
-                        for (int d = 0; d < D; ++d) {
-                            double acc = 0.0;
-                            for (int u = 0; u < nb; ++u) acc += (seen1[u] - seen0[u]) * hv.vseen[(j0 + u) * D + d];
-                            mv[d] = acc * carry;
-                            if (fabs(mv[d]) > big) big = fabs(mv[d]);
-                        }
-                    } else {
-                        if (!(tr.s[j] > -INFINITY)) continue;
-                        const double mj = tr.m[j];
-                        const double p = exp2(tr.s[j] - mj);
-                        if (!(p > 0.0)) continue;
-                        const double carry_j = exp2(mj - tr.m_final) / tr.l_final;
-                        double rounded, other, spacing;
-                        if (p_round == 2) {
-                            const double y = ldexp(p, 127 - bsc);
-                            if (y >= 448.0) continue;
-                            spacing = ldexp(1.0, e4m3_quantum(y) + bsc - 127);
-                            rounded = seen0[t];
-                            other = e4m3_other_neighbour(p, bsc, rounded);
-                        } else {
-                            spacing = ldexp(1.0, bf16_quantum(p));
-                            rounded = oracle_round_to_bf16(p);
-                            other = other_grid_point(p, rounded, bf16_quantum(p));
-                        }
-                        if (other == rounded) continue;
-                        const double r = p / spacing;
-                        const double to_midpoint = fabs(r - floor(r) - 0.5) * spacing;
-                        const double allowance = score_noise(tr.s[j], mj) * 0.6931471805599453 * p;
-                        if (to_midpoint > allowance) continue;
-                        used = to_midpoint / allowance;
-                        kind = ORACLE_ALT_NEIGHBOUR;
-                        for (int d = 0; d < D; ++d) {
-                            const double vv = (p_round == 2) ? hv.vseen[j * D + d] : (double)oracle_bf16_to_f32(vh[j * D + d]);
-                            mv[d] = (other - rounded) * vv * carry_j;
-                            if (fabs(mv[d]) > big) big = fabs(mv[d]);
-                        }
-                    }
-                    if (big < min_move) continue;
-                    if (found == cap) {
-                        cap *= 2;
-                        ck = (int64_t *)realloc(ck, sizeof(int64_t) * (size_t)cap);
-                        cn = (int32_t *)realloc(cn, sizeof(int32_t) * (size_t)cap);
-                        cm = (double *)realloc(cm, sizeof(double) * (size_t)cap * (size_t)D);
-                        cr = (double *)realloc(cr, sizeof(double) * (size_t)cap);
-                        if (!ck || !cn || !cm || !cr) break;
-                    }
-                    ck[found] = j; cn[found] = kind; cr[found] = used;
-                    memcpy(cm + found * D, mv, sizeof(double) * (size_t)D);
-                    ++found;
-                }
-            }
-        }
-        if (!ck || !cn || !cm || !cr || !mv) {
+        open_list L = { 0, 0, D, NULL, NULL, NULL, NULL, 0 };
+        list_open_decisions(&tr, n_keys, tile, D, p_round, values, min_move, &L);
+        if (L.failed) {
             rc = ORACLE_ERR_MEM;
         } else {
-            /* selection sort of the first max_cand by largest |move| */
-            *n_cand = found;
-            for (int64_t a = 0; a < found && a < max_cand; ++a) {
+            *n_cand = L.n;
+            for (int64_t a = 0; a < L.n && a < max_cand; ++a) {           /* selection of the largest moves, in order */
                 int64_t best = -1;
                 double bestv = -1.0;
-                for (int64_t c2 = 0; c2 < found; ++c2) {
-                    if (cn[c2] == 0) continue;
-                    double big = 0.0;
-                    for (int d = 0; d < D; ++d) if (fabs(cm[c2 * D + d]) > big) big = fabs(cm[c2 * D + d]);
+                for (int64_t c2 = 0; c2 < L.n; ++c2) {
+                    if (L.kind[c2] == 0) continue;                         /* taken */
+                    const double big = largest_abs(L.move + c2 * D, D);
                     if (big > bestv) { bestv = big; best = c2; }
                 }
-                cand_key[a] = ck[best]; cand_kind[a] = cn[best]; cand_margin[a] = cr[best];
-                memcpy(cand_move + a * D, cm + best * D, sizeof(double) * (size_t)D);
-                cn[best] = 0;                                  /* taken */
+                cand_key[a] = L.key[best]; cand_kind[a] = L.kind[best]; cand_margin[a] = L.used[best];
+                memcpy(cand_move + a * D, L.move + best * D, sizeof(double) * (size_t)D);
+                L.kind[best] = 0;
             }
         }
-        free(ck); free(cn); free(cm); free(cr); free(mv);
+        free(L.key); free(L.kind); free(L.used); free(L.move);
     }
+    if (values != hv.vseen) free(values);
     free(tr.s);
     head_view_free(&hv);
     free(qamax);
