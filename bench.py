@@ -36,6 +36,7 @@ HBM_PEAK_GBS = 8000.0
 SECOND_WORKLOAD = "gqa_32k"           # timed besides the headline workload in the default run
 SECOND_STEPS, SECOND_WARMUP = 40, 10
 RAMP_MS = 60.0                        # untimed work before the timed region (clock ramp-up), see main()
+CLOCK_MHZ = 2400                      # nominal shader clock of the MI355X, for figures quoted in clocks
 COPY_CALIBRATION_BYTES = 1 << 29      # dma_diag_copy reads and writes this many bytes once per run
 
 
@@ -123,6 +124,29 @@ def cpu_baseline(w, q, k, v, band, budget_rows):
                       f"workload's flops), C oracle in double with OpenMP"}
 
 
+def pipes_report(binding, torch):
+    """One JSON line: clocks per wave instruction (at the nominal 2.4 GHz) of every stream of some combinations of
+    streams that share a SIMD, measured by dma_diag_pipes after a clock ramp-up."""
+    B = binding
+    names = {B.PIPE_MFMA_BF16: "mfma_bf16_32x32x16", B.PIPE_MFMA_FP4: "mfma_fp4_32x32x64", B.PIPE_MFMA_FP8: "mfma_fp8_32x32x64",
+             B.PIPE_FMA: "v_fma_f32", B.PIPE_EXP: "v_exp_f32", B.PIPE_CVT_PK_BF16: "v_cvt_pk_bf16_f32"}
+    M, F, E, C = B.PIPE_MFMA_BF16, B.PIPE_FMA, B.PIPE_EXP, B.PIPE_CVT_PK_BF16
+    combos = [(M,), (B.PIPE_MFMA_FP4,), (B.PIPE_MFMA_FP8,), (M, M), (F,), (F, F), (F, F, F), (E,), (E, E), (C,), (C, C),
+              (M, F), (M, F, F), (M, E), (M, E, F), (M, C, F), (B.PIPE_MFMA_FP4, F, F), (B.PIPE_MFMA_FP8, F, F)]
+    us = 300
+    for _ in range(300):                                  # >= 60 ms of work: the clocks are up
+        B.dma_diag_pipes((F, F), us)
+    torch.cuda.synchronize()
+    rows = []
+    for combo in combos:
+        counts, wgs = B.dma_diag_pipes(combo, us)
+        torch.cuda.synchronize()
+        rows.append({"streams": [names[k] for k in combo],
+                     "clk_per_instruction": [round(us * CLOCK_MHZ * 4 * wgs / c, 1) if c else None for c in counts]})
+    print(json.dumps({"metric": "clocks per wave instruction of instruction streams sharing one SIMD", "clock_mhz": CLOCK_MHZ,
+                      "microseconds_per_run": us, "rows": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -138,6 +162,8 @@ def main():
                     help="with --per-token: the group of rows that shares a Step-2 scale (Sec. 5.3); block = one tile of one head")
     ap.add_argument("--pv-mx", action="store_true", help="P V in MXFP8-E4M3 with blocks of 32 keys (variant beyond Alg. 1)")
     ap.add_argument("--single", action="store_true", help="time --workload only (the default run also times gqa_32k)")
+    ap.add_argument("--pipes", action="store_true",
+                    help="instead of the forward: the rates of pure matrix and vector instruction streams side by side on one SIMD")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=200000)
     args = ap.parse_args()
@@ -151,6 +177,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+    if args.pipes:
+        pipes_report(binding, torch)
+        return
     binding.load()
     coarse = args.per_token and args.granularity != "token"
     gran = {"token": binding.GRAN_TOKEN, "block": binding.GRAN_BLOCK, "tensor": binding.GRAN_TENSOR}[args.granularity]

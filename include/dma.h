@@ -182,6 +182,25 @@ int dma_diag_copy(const void* src, void* dst, int64_t bytes, void* stream);
 int dma_diag_mfma(const void* a, const void* b, const void* a_scales, const void* b_scales, int fmt,
                   void* out_f32, void* stream);
 
+/* Diagnostic, not part of the method: the rates pure instruction streams reach side by side on one SIMD -- the evidence
+ * for how much of the matrix time of the forward can hide behind its vector work.  One workgroup per compute unit;
+ * wave slot s (waves 4 s .. 4 s + 3 of the workgroup, one on each SIMD) issues the stream kinds[s] back to back for
+ * `microseconds` and adds the number of instructions it issued to counts_u64[s]; the waves stop by the clock.
+ *   kinds       host, n_slots ints (1 <= n_slots <= 3), each a DMA_PIPE_* id
+ *   microseconds  1 .. 100 000
+ *   counts_u64  device, 8-byte aligned, 3 x uint64, zeroed by the caller before the call; slot s receives the sum over
+ *               all its waves (4 per workgroup)
+ *   workgroups  host, may be NULL: receives the number of workgroups launched (the compute units of the device)
+ * Clocks per instruction of slot s = microseconds x clock [MHz] x 4 x workgroups / counts_u64[s]. */
+#define DMA_PIPE_IDLE 0
+#define DMA_PIPE_MFMA_BF16 1        /* v_mfma_f32_32x32x16_bf16 */
+#define DMA_PIPE_MFMA_FP4 2         /* v_mfma_scale_f32_32x32x64_f8f6f4, E2M1 operands */
+#define DMA_PIPE_MFMA_FP8 3         /* the same instruction, E4M3 operands */
+#define DMA_PIPE_FMA 4              /* v_fma_f32 */
+#define DMA_PIPE_EXP 5              /* v_exp_f32 */
+#define DMA_PIPE_CVT_PK_BF16 6      /* v_cvt_pk_bf16_f32 */
+int dma_diag_pipes(const int* kinds, int n_slots, int microseconds, void* counts_u64, int* workgroups, void* stream);
+
 /* Static, NUL-terminated description of a return code. */
 const char* dma_error_string(int code);
 

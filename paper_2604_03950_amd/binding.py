@@ -18,7 +18,9 @@ FMT_MXFP4_E2M1 = 2
 FMT_MXFP8_E5M2 = 3
 
 EXPORTS = ("dma_mx_quantize", "dma_mx_quantize_token", "dma_mx_quantize_dual", "dma_mx_group_amax", "dma_attn_fwd", "dma_attn_fwd_ex",
-           "dma_attn_fwd_workspace_bytes", "dma_diag_copy", "dma_diag_mfma", "dma_error_string", "dma_version")
+           "dma_attn_fwd_workspace_bytes", "dma_diag_copy", "dma_diag_mfma", "dma_diag_pipes", "dma_error_string", "dma_version")
+
+PIPE_IDLE, PIPE_MFMA_BF16, PIPE_MFMA_FP4, PIPE_MFMA_FP8, PIPE_FMA, PIPE_EXP, PIPE_CVT_PK_BF16 = range(7)
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdma_mi355x.so")
 _lib = None
@@ -66,6 +68,8 @@ def load() -> ctypes.CDLL:
         L.dma_diag_copy.argtypes = [vp, vp, i64, vp]
         L.dma_diag_mfma.restype = ci
         L.dma_diag_mfma.argtypes = [vp, vp, vp, vp, ci, vp, vp]
+        L.dma_diag_pipes.restype = ci
+        L.dma_diag_pipes.argtypes = [ctypes.POINTER(ci), ci, ci, vp, ctypes.POINTER(ci), vp]
         L.dma_error_string.restype = ctypes.c_char_p
         L.dma_error_string.argtypes = [ci]
         L.dma_version.restype = ci
@@ -226,6 +230,19 @@ def dma_diag_mfma(a: torch.Tensor, b: torch.Tensor, a_scales: torch.Tensor | Non
     if rc:
         raise DmaError(rc, "dma_diag_mfma")
     return out
+
+
+def dma_diag_pipes(kinds, microseconds: int = 300) -> tuple[list[int], int]:
+    """Instruction streams kinds[s] (PIPE_* ids, one to three) side by side on every SIMD for `microseconds` (diagnostic).
+    Returns (instructions issued per slot, summed over all waves; workgroups launched): a slot has 4 waves per workgroup."""
+    kinds = [int(k) for k in kinds]
+    counts = torch.zeros(3, dtype=torch.int64, device="cuda")
+    arr = (ctypes.c_int * len(kinds))(*kinds)
+    wgs = ctypes.c_int(0)
+    rc = load().dma_diag_pipes(arr, len(kinds), int(microseconds), counts.data_ptr(), ctypes.byref(wgs), _stream())
+    if rc:
+        raise DmaError(rc, "dma_diag_pipes")
+    return [int(c) for c in counts.cpu().tolist()[:len(kinds)]], int(wgs.value)
 
 
 def bits_to_bf16_tensor(bits, device="cuda") -> torch.Tensor:

@@ -166,6 +166,20 @@ int dma_diag_mfma(const void* a, const void* b, const void* a_scales, const void
     return dma::launch_diag_mfma(a, b, a_scales, b_scales, fmt, (float*)out_f32, (hipStream_t)stream);     // public ids 0, 1, 2 = product paths 0, 1, 2
 }
 
+int dma_diag_pipes(const int* kinds, int n_slots, int microseconds, void* counts_u64, int* workgroups, void* stream)
+{
+    if (!kinds || !counts_u64 || n_slots < 1 || n_slots > 3 || microseconds < 1 || microseconds > 100000) return DMA_ERR_INVALID_ARG;
+    if ((uintptr_t)counts_u64 % 8 != 0) return DMA_ERR_INVALID_ARG;
+    for (int s = 0; s < n_slots; ++s)
+        if (kinds[s] < DMA_PIPE_IDLE || kinds[s] > DMA_PIPE_CVT_PK_BF16) return DMA_ERR_INVALID_ARG;
+    if (workgroups) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return DMA_ERR_HIP;
+        *workgroups = cus;
+    }
+    return dma::launch_diag_pipes(kinds, n_slots, 100LL * microseconds, (unsigned long long*)counts_u64, (hipStream_t)stream);
+}
+
 const char* dma_error_string(int code)
 {
     switch (code) {

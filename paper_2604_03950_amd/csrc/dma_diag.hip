@@ -42,6 +42,94 @@ diag_mfma_kernel(const uint8_t* __restrict__ a, const uint8_t* __restrict__ b, c
     for (int t = 0; t < 16; ++t) out[(8 * (t / 4) + 4 * g + t % 4) * 32 + r] = acc[t];
 }
 
+// Pure instruction streams side by side on one SIMD.  One workgroup per CU; the waves of slot s (waves 4 s .. 4 s + 3, one
+// per SIMD) issue stream kind[s] back to back until `ticks` of the 100 MHz wall clock have passed and add the number of
+// instructions they issued to counts[s].  Every stream is a rotation over independent registers, so only the issue rate
+// and the pipes limit it.  Every wave leaves its loop when the clock says so: the grid always drains.
+struct PipeKinds { int k[3]; };
+
+template <typename F>
+DMA_DEV unsigned long long run_stream(long long t_end, int per_round, F&& round)
+{
+    unsigned long long n = 0;
+    do {
+        round();
+        n += per_round;
+    } while (wall_clock64() < t_end);
+    return n;
+}
+
+__global__ void __launch_bounds__(768)
+diag_pipes_kernel(PipeKinds kinds, long long ticks, unsigned long long* __restrict__ counts)
+{
+    const int slot = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);
+    const int kind = kinds.k[slot];
+    const long long t_end = wall_clock64() + ticks;
+    unsigned long long n = 0;
+    float sink = 0.f;
+    if (kind >= 1 && kind <= 3) {
+        // four accumulators in rotation, 32 instructions per look at the clock
+        v16f c[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[i] = v16f{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        const int seed = 0x22222222 + (int)(threadIdx.x & 1);
+        const v8i w8 = {seed, seed, seed, seed, seed, seed, seed, seed}, w4 = {seed, seed, seed, seed, 0, 0, 0, 0};
+        const v4i h = {0x3f803f80, 0x3f803f80, 0x3f803f80, 0x3f803f80};
+        if (kind == 1)
+            n = run_stream(t_end, 32, [&] {
+#pragma unroll
+                for (int r = 0; r < 32; ++r)
+                    c[r & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, h), __builtin_bit_cast(v8bf, h), c[r & 3], 0, 0, 0);
+            });
+        else if (kind == 2)
+            n = run_stream(t_end, 32, [&] {
+#pragma unroll
+                for (int r = 0; r < 32; ++r) c[r & 3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(w4, w4, c[r & 3], 4, 4, 0, 127, 0, 127);
+            });
+        else
+            n = run_stream(t_end, 32, [&] {
+#pragma unroll
+                for (int r = 0; r < 32; ++r) c[r & 3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(w8, w8, c[r & 3], 0, 0, 0, 127, 0, 127);
+            });
+        sink = c[0][0] + c[1][1] + c[2][2] + c[3][3];
+    } else if (kind >= 4 && kind <= 6) {
+        // sixteen registers in rotation, 128 instructions per look at the clock
+        float x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = 0.001f * (float)(threadIdx.x + i + 1);
+        const float mul = 0.999f, add = 0.0001f;
+        if (kind == 4)
+            n = run_stream(t_end, 128, [&] {
+#pragma unroll
+                for (int r = 0; r < 128; ++r) asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(x[r & 15]) : "v"(mul), "v"(add));
+            });
+        else if (kind == 5)
+            n = run_stream(t_end, 128, [&] {
+#pragma unroll
+                for (int r = 0; r < 128; ++r) asm volatile("v_exp_f32 %0, %0" : "+v"(x[r & 15]));
+            });
+        else
+            n = run_stream(t_end, 128, [&] {
+#pragma unroll
+                for (int r = 0; r < 128; ++r) asm volatile("v_cvt_pk_bf16_f32 %0, %0, %1" : "+v"(x[r & 15]) : "v"(mul));
+            });
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sink += x[i];
+    }
+    if (sink == 12345.678f) n += 1;                  // keeps the streams alive; never true in practice, and harmless
+    if ((threadIdx.x & 63) == 0 && n) atomicAdd(&counts[slot], n);
+}
+
+int launch_diag_pipes(const int* kinds, int n_slots, long long ticks, unsigned long long* counts, hipStream_t stream)
+{
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        return DMA_ERR_HIP_;
+    PipeKinds pk = {{0, 0, 0}};
+    for (int s = 0; s < n_slots; ++s) pk.k[s] = kinds[s];
+    return launch(diag_pipes_kernel, dim3(cus), dim3(256 * n_slots), stream, pk, ticks, counts);
+}
+
 int launch_diag_mfma(const void* a, const void* b, const void* sa, const void* sb, int fmt, float* out, hipStream_t stream)
 {
     const uint8_t *pa = (const uint8_t*)a, *pb = (const uint8_t*)b, *psa = (const uint8_t*)sa, *psb = (const uint8_t*)sb;

@@ -41,6 +41,9 @@ int launch_diag_copy(const void* src, void* dst, int64_t bytes, hipStream_t stre
 // One 32 x 32 x 64 product on the matrix instruction of format fmt (product-path id of dma_device.hpp: 0, 1 or 2).
 int launch_diag_mfma(const void* a, const void* b, const void* sa, const void* sb, int fmt, float* out, hipStream_t stream);
 
+// Instruction streams of kinds[0 .. n_slots) (1 <= n_slots <= 3) side by side on every SIMD for `ticks` of the 100 MHz clock.
+int launch_diag_pipes(const int* kinds, int n_slots, long long ticks, unsigned long long* counts, hipStream_t stream);
+
 // Group maxima for Alg. 2 Step 2 (granularity 1 = row, 2 = block of block_rows rows per [S, D] matrix, 3 = everything).
 int launch_group_amax(const void* x, int64_t n_mat, int64_t S, int D, int is_query, int granularity, int64_t block_rows,
                       float* amax, hipStream_t stream);

@@ -89,3 +89,12 @@ def test_argument_checks_return_before_any_launch(lib):
     assert lib.dma_diag_mfma(fake, ctypes.c_void_p(0x1008), None, None, 0, fake, None) == -1   # misaligned
     assert lib.dma_diag_copy(fake, fake, 24, None) == -1                             # not a multiple of 16 bytes
     assert lib.dma_diag_copy(fake, fake, 0, None) == 0
+    kinds = (ctypes.c_int * 3)(1, 4, 4)
+    assert lib.dma_diag_pipes(kinds, 0, 100, fake, None, None) == -1                 # one to three slots
+    assert lib.dma_diag_pipes(kinds, 4, 100, fake, None, None) == -1
+    assert lib.dma_diag_pipes(kinds, 3, 0, fake, None, None) == -1                   # 1 .. 100 000 microseconds
+    assert lib.dma_diag_pipes(kinds, 3, 100001, fake, None, None) == -1
+    assert lib.dma_diag_pipes(kinds, 3, 100, None, None, None) == -1
+    assert lib.dma_diag_pipes(kinds, 3, 100, ctypes.c_void_p(0x1004), None, None) == -1     # misaligned counters
+    assert lib.dma_diag_pipes((ctypes.c_int * 3)(1, 7, 4), 3, 100, fake, None, None) == -1   # no such stream
+    assert lib.dma_diag_pipes(None, 3, 100, fake, None, None) == -1

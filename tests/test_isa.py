@@ -27,11 +27,19 @@ def test_fp4_convert_groups_read_four_registers(tmp_path, lo, hi):
     assert not re.search(r"\bv_pk_(add|mul|fma)_f32\b", text)
     lines = [ln.strip() for ln in text.splitlines() if "v_cvt_scalef32_pk_fp4_bf16" in ln]
     assert len(lines) >= 16 and len(lines) % 4 == 0
+    # The four converts into one destination dword fill its bytes in order (op_sel of the destination byte); the
+    # scheduler may interleave the groups of different destinations, so the groups are collected per destination.
     want_sel = ["", "[0,0,1,0]", "[0,0,0,1]", "[0,0,1,1]"]
-    for i in range(0, len(lines), 4):
-        grp = lines[i:i + 4]
-        sels = [(re.search(r"op_sel:(\[[0-9,]+\])", ln).group(1) if "op_sel" in ln else "") for ln in grp]
-        assert sels == want_sel, grp
-        ops = [ln.split() for ln in grp]
-        assert len({o[1] for o in ops}) == 1, grp             # one destination dword
-        assert len({o[2] for o in ops}) == 4, grp             # four different source registers
+    open_groups, n_groups = {}, 0
+    for ln in lines:
+        ops = ln.split()
+        dst, src = ops[1].rstrip(","), ops[2].rstrip(",")
+        sel = re.search(r"op_sel:(\[[0-9,]+\])", ln).group(1) if "op_sel" in ln else ""
+        grp = open_groups.setdefault(dst, [])
+        assert sel == want_sel[len(grp)], (dst, grp, ln)     # the next byte of this destination, nothing else
+        grp.append(src)
+        if len(grp) == 4:
+            assert len(set(grp)) == 4, (dst, grp)            # four different source registers
+            del open_groups[dst]
+            n_groups += 1
+    assert not open_groups and n_groups == len(lines) // 4
