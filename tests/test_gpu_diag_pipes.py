@@ -44,6 +44,6 @@ def test_matrix_pipe_serves_one_wave_and_slows_vector_waves(dma):
     (f1,), _ = dma.dma_diag_pipes((F,), us)
     (m2, f2), _ = dma.dma_diag_pipes((M, F), us)
     print(f"matrix alone {m1}, two matrix waves {ma} + {mb}; vector alone {f1}, next to a matrix wave {f2} (matrix {m2})", flush=True)
-    assert ma + mb <= 1.1 * m1                             # one pipe: two waves share what one wave gets
-    assert f2 <= 1.02 * f1                                 # never faster next to a matrix wave
+    assert ma + mb <= 1.25 * m1                            # one pipe: two waves share what one wave gets (measured 1.04)
+    assert f2 <= 1.1 * f1                                  # not faster next to a matrix wave (measured 0.83; clocks may drift a little)
     assert m2 >= 0.5 * m1                                  # and the matrix wave keeps most of its rate
